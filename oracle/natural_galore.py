@@ -1,0 +1,223 @@
+"""Plain float64 definition of one Natural GaLore optimizer step (numpy only).
+
+TEST INFRASTRUCTURE: imported only by tests, the smoke check and the
+benchmark's CPU-baseline leg.  It is deliberately slow and literal -- every
+function follows one passage of the paper, in the paper's order, with no
+blocking, fusion or reordering -- and it shares no code with the HIP library.
+
+Letters.  The paper writes the weight/gradient as n x m and the projector as
+n x r; here (as in the rest of this repository) the weight W and gradient G are
+m x n, the projector P is m x r with orthonormal columns, the low-rank gradient
+R = P^T G is r x n, the Adam moments M, V are r x n and the history H keeps the
+last s low-rank gradients (s x r x n).  The paper's stacked matrix "G" of
+vectorised low-rank gradients is called ``Hmat`` (rn x s) here to keep it apart
+from the full gradient.
+
+Readings of the paper taken here (the paper is silent or inconsistent):
+  * the empirical Fisher carries the 1/h normaliser of Sec. 2.2's empirical-FIM
+    equation, with h = s fixed:  F = lambda*I + (1/s) * sum_i vec(H_i) vec(H_i)^T,
+    i.e. Woodbury's U is Hmat / sqrt(s);  empty slots are zero;
+  * the history holds exactly s slots and the current low-rank gradient is
+    pushed into it before the transform (Sec. 2.4 lists vec(g_k) first);
+  * s = 0 bypasses the transform: the step is then GaLore with Adam (Sec. 2.2,
+    the sentence after the Adam equations);
+  * "sent to the Adam optimizer" (end of Sec. 2.4) means Adam as published by
+    Kingma & Ba: bias-corrected moments, epsilon outside the root
+    (``adam_mode="standard"``).  The three equations exactly as printed in
+    Sec. 2.2 -- no bias correction, epsilon inside the root -- are
+    ``adam_mode="printed"``;
+  * update  W <- W - lr * (scale * P N + weight_decay * W)  (Sec. 2.2, update
+    equation; scale and weight_decay default to 1 and 0);
+  * a refresh keeps M, V and the step counter and clears the history (its slots
+    are coordinates in the old basis).
+
+Pins (tests/test_oracle_pins.py): the Woodbury route against the explicit
+rn x rn damped-Fisher solve, closed forms for one slot and for orthogonal
+slots, the large-lambda limit, GaLore-Adam against torch.optim.Adam when s = 0,
+the first-step Adam closed form, orthonormality / lossless projection /
+Eckart-Young for the projector, exact integer bookkeeping, and bf16 rounding
+against torch's conversion.  Parity unpinned: the individual trailing singular
+vectors returned by ``top_r_left_singular_vectors`` when the r-th and (r+1)-th
+singular values are not separated (only subspace invariants are pinned there).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import scipy.linalg
+
+
+@dataclass
+class HParams:
+    s: int = 4
+    lam: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    scale: float = 1.0
+    weight_decay: float = 0.0
+    adam_mode: str = "standard"      # "standard" | "printed"
+    weight_dtype: str = "f32"        # "f32" | "bf16": storage type of W
+
+
+@dataclass
+class OracleState:
+    P: np.ndarray                    # m x r
+    M: np.ndarray                    # r x n
+    V: np.ndarray                    # r x n
+    H: np.ndarray                    # s x r x n ring buffer
+    t: int = 0                       # steps taken (1-based after the first step)
+    head: int = 0                    # slot the next push writes
+    count: int = 0                   # valid slots, min(pushes since clear, s)
+    n_refresh: int = 0
+    trace: dict = field(default_factory=dict)   # intermediates of the last step
+
+
+def init_state(m: int, n: int, r: int, s: int) -> OracleState:
+    return OracleState(
+        P=np.zeros((m, r)), M=np.zeros((r, n)), V=np.zeros((r, n)),
+        H=np.zeros((max(s, 0), r, n)))
+
+
+# --------------------------------------------------------------------------
+# Sec. 1, "Gradient Low-Rank Projection (GaLore)": compact SVD and projection
+# --------------------------------------------------------------------------
+def top_r_left_singular_vectors(G: np.ndarray, r: int) -> np.ndarray:
+    """P of the compact SVD G = P Sigma Q^T, first r columns (Sec. 1; Sec. 2.2).
+
+    LAPACK via numpy.  Each column's sign is fixed so that its entry of largest
+    magnitude is positive (an SVD leaves the sign free).
+    """
+    U, _, _ = np.linalg.svd(np.asarray(G, dtype=np.float64), full_matrices=False)
+    P = U[:, :r].copy()
+    rows = np.argmax(np.abs(P), axis=0)
+    signs = np.sign(P[rows, np.arange(P.shape[1])])
+    signs[signs == 0] = 1.0
+    return P * signs
+
+
+def project(P: np.ndarray, G: np.ndarray) -> np.ndarray:
+    """Low-rank gradient R = P^T G (Sec. 1, projection equation)."""
+    return P.T @ np.asarray(G, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.4: history of the last s low-rank gradients
+# --------------------------------------------------------------------------
+def push_history(state: OracleState, R: np.ndarray) -> int:
+    """Store R in slot ``head`` and advance the ring.  Returns the slot used."""
+    s = state.H.shape[0]
+    slot = state.head
+    state.H[slot] = R
+    state.head = (state.head + 1) % s
+    state.count = min(state.count + 1, s)
+    return slot
+
+
+def fisher_history_matrix(H: np.ndarray) -> np.ndarray:
+    """rn x s matrix whose columns are the vectorised history slots (Sec. 2.4)."""
+    s = H.shape[0]
+    return H.reshape(s, -1).T.copy()
+
+
+def natural_gradient_transform(H: np.ndarray, R: np.ndarray, lam: float) -> tuple:
+    """Inverse damped empirical Fisher applied to R through Woodbury (Sec. 2.4).
+
+    F = lam*I + U U^T with U = Hmat / sqrt(s).  Following the section's steps:
+    S = I + U^T U / lam,  y = U^T vec(R),  Cholesky solve S z = y,
+    g~ = vec(R)/lam - U z / lam^2.  Returns (g~ as r x n, dict of K, S, y, z).
+    """
+    s = H.shape[0]
+    Hmat = fisher_history_matrix(H)
+    U = Hmat / np.sqrt(s)
+    g = R.reshape(-1)
+    K = Hmat.T @ Hmat                       # s x s Gram of the stored slots
+    S = np.eye(s) + (U.T @ U) / lam
+    y = U.T @ g
+    z = scipy.linalg.cho_solve(scipy.linalg.cho_factor(S, lower=True), y)
+    g_nat = g / lam - (U @ z) / lam ** 2
+    return g_nat.reshape(R.shape), {"K": K, "S": S, "y": y, "z": z}
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.2: Adam moments in the r x n space, and the weight update
+# --------------------------------------------------------------------------
+def adam_moments(M, V, g, t: int, hp: HParams):
+    """Moment recursion and update direction N (Sec. 2.2, Adam equations)."""
+    M_new = hp.beta1 * M + (1.0 - hp.beta1) * g
+    V_new = hp.beta2 * V + (1.0 - hp.beta2) * g * g
+    if hp.adam_mode == "standard":
+        m_hat = M_new / (1.0 - hp.beta1 ** t)
+        v_hat = V_new / (1.0 - hp.beta2 ** t)
+        N = m_hat / (np.sqrt(v_hat) + hp.eps)
+    elif hp.adam_mode == "printed":
+        N = M_new / np.sqrt(V_new + hp.eps)
+    else:
+        raise ValueError(hp.adam_mode)
+    return M_new, V_new, N
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float64 values to the nearest bfloat16 (ties to even), as float64.
+
+    bfloat16 keeps 1 sign, 8 exponent and 7 mantissa bits.  Works on the
+    float64 bit pattern directly (one rounding, not two); valid for finite
+    values inside bfloat16's normal range, which is asserted.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    a = np.abs(x)
+    nz = a[a > 0]
+    if nz.size:
+        assert nz.min() >= 2.0 ** -126 and nz.max() < 2.0 ** 127, "outside bf16 normal range"
+    bits = x.view(np.uint64)
+    drop = np.uint64(52 - 7)
+    lsb = (bits >> drop) & np.uint64(1)
+    rounded = bits + ((np.uint64(1) << (drop - np.uint64(1))) - np.uint64(1)) + lsb
+    rounded &= ~((np.uint64(1) << drop) - np.uint64(1))
+    return rounded.view(np.float64).reshape(x.shape)
+
+
+def back_project_update(W, P, N, lr: float, hp: HParams):
+    """W <- W - lr * (scale * P N + weight_decay * W) (Sec. 2.2, update equation)."""
+    W = np.asarray(W, dtype=np.float64)
+    W_new = W - lr * (hp.scale * (P @ N) + hp.weight_decay * W)
+    if hp.weight_dtype == "bf16":
+        W_new = round_to_bf16(W_new)
+    return W_new
+
+
+# --------------------------------------------------------------------------
+# The step and the refresh
+# --------------------------------------------------------------------------
+def refresh_projector(state: OracleState, G: np.ndarray) -> None:
+    """P <- top-r left singular vectors of the current gradient; clear history."""
+    r = state.P.shape[1]
+    state.P = top_r_left_singular_vectors(G, r)
+    state.H[...] = 0.0
+    state.head = 0
+    state.count = 0
+    state.n_refresh += 1
+
+
+def step(state: OracleState, G: np.ndarray, W: np.ndarray, lr: float, hp: HParams) -> np.ndarray:
+    """One Natural GaLore step on one weight matrix.  Returns the new W.
+
+    Order (Sec. 2.4, first and last paragraphs): project, push into the
+    history, natural-gradient transform, Adam, back-project and update.
+    """
+    state.t += 1
+    R = project(state.P, G)
+    tr = {"R": R}
+    if hp.s > 0:
+        slot = push_history(state, R)
+        g_nat, parts = natural_gradient_transform(state.H, R, hp.lam)
+        tr.update(parts)
+        tr["slot"] = slot
+    else:
+        g_nat = R
+    tr["g_nat"] = g_nat
+    state.M, state.V, N = adam_moments(state.M, state.V, g_nat, state.t, hp)
+    tr["N"] = N
+    state.trace = tr
+    return back_project_update(W, state.P, N, lr, hp)

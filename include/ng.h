@@ -1,0 +1,182 @@
+/*
+ * ng.h -- C ABI of the Natural GaLore optimizer step for AMD MI355X (gfx950).
+ *
+ * One handle (ng_state) drives a whole "layer set": n_mats independent weight
+ * matrices that are stepped together.  For each matrix W (m x n) with gradient
+ * G (m x n) the library keeps
+ *     P  m x r   projector with orthonormal columns          (paper Sec. 1, compact SVD)
+ *     M,V r x n  Adam moments of the transformed gradient     (paper Sec. 2.2, Adam equations)
+ *     H  s x r x n  ring buffer of the last s low-rank gradients  (paper Sec. 2.4, stacked matrix)
+ *     K  s x s   Gram matrix of the ring's slots               (paper Sec. 2.4, the s x s system)
+ * The paper writes matrices as n x m; here m counts rows and n columns.
+ *
+ * Conventions
+ *   - Every pointer in ng_matrix_buffers, `workspace`, `grads[i]` and
+ *     `weights[i]` is a DEVICE pointer; every other pointer (descriptors,
+ *     hyper-parameters, the arrays `grads`/`weights` themselves, out-params) is a
+ *     HOST pointer.
+ *   - All matrices are row-major.  ld_* are in elements.
+ *   - All device memory is owned by the caller and must outlive the handle.  The
+ *     library allocates no device memory and frees none.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     that take a stream only enqueue work on it and do not synchronise, except
+ *     where stated.  Calls on one handle must not overlap.
+ *   - Every function returns an int: NG_OK (0) or a negative NG_ERR_* code.  No
+ *     C++ exception crosses this boundary.  A call that fails leaves the
+ *     handle's integer counters unchanged.
+ */
+#ifndef NG_H_
+#define NG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ng_state ng_state;   /* opaque, host-side; created by ng_init_state */
+typedef void* ng_stream;            /* a hipStream_t */
+
+/* storage type of gradients AND weights */
+enum { NG_F32 = 0, NG_BF16 = 1 };
+
+/* NG_ADAM_STANDARD: bias-corrected moments, eps outside the root (Adam as
+ * published; "sent to the Adam optimizer", end of paper Sec. 2.4).
+ * NG_ADAM_PRINTED: the three equations exactly as printed in paper Sec. 2.2:
+ * no bias correction, u = m / sqrt(v + eps). */
+enum { NG_ADAM_STANDARD = 0, NG_ADAM_PRINTED = 1 };
+
+enum {
+    NG_OK = 0,
+    NG_ERR_INVALID_ARG = -1,   /* null pointer, bad index, bad count                  */
+    NG_ERR_SHAPE = -2,         /* m,n,r <= 0, r > min(m,n), ld < n, s out of range    */
+    NG_ERR_DTYPE = -3,         /* unknown grad_dtype / adam_mode                      */
+    NG_ERR_HPARAM = -4,        /* lambda <= 0, beta outside [0,1), eps <= 0, ...      */
+    NG_ERR_NO_PROJECTOR = -5,  /* ng_step before any refresh / commit                 */
+    NG_ERR_HIP = -6,           /* a HIP runtime call or kernel launch failed          */
+    NG_ERR_NUMERIC = -7,       /* device flag: non-positive pivot or non-finite value */
+    NG_ERR_WORKSPACE = -8      /* workspace too small or misaligned                   */
+};
+
+/* per-matrix caller-owned device buffers, sizes from ng_query_sizes */
+enum {
+    NG_BUF_P = 0,   /* float  [m][r]                      projector                                   */
+    NG_BUF_M,       /* float  [r][ldn]                    first moment                                */
+    NG_BUF_V,       /* float  [r][ldn]                    second moment                               */
+    NG_BUF_H,       /* float  [max(s,1)][r][ldn]          history ring (one scratch slot when s = 0)  */
+    NG_BUF_K,       /* double [s*s] Gram, double [s] w, then float [s] w  (see ng_matrix_layout)      */
+    NG_BUF_N,       /* update direction: float [r][ldn] (NG_F32) or bf16 [ceil(r/8)][ldn][8] (NG_BF16) */
+    NG_BUF_AUX,     /* NG_BF16 only: bf16 copies of P; 0 bytes for NG_F32 (pointer may be NULL)       */
+    NG_NBUF
+};
+
+typedef struct ng_matrix_desc {
+    int32_t m, n, r;       /* weight is m x n, rank r, 1 <= r <= min(m, n)            */
+    int32_t reserved;      /* must be 0                                               */
+    int64_t ld_w, ld_g;    /* leading dimensions of weight and gradient, >= n         */
+} ng_matrix_desc;
+
+typedef struct ng_hparams {
+    int32_t s;               /* history length, 0 <= s <= 64; 0 = no Fisher transform (GaLore-Adam) */
+    float lambda;            /* Tikhonov damping of the empirical Fisher, > 0 (paper Sec. 2.4)     */
+    float beta1, beta2, eps; /* Adam (paper Sec. 2.2)                                              */
+    float scale;             /* multiplies P N in the update                                       */
+    float weight_decay;      /* decoupled weight decay, multiplies W in the update                 */
+    int32_t grad_dtype;      /* NG_F32 | NG_BF16                                                   */
+    int32_t adam_mode;       /* NG_ADAM_STANDARD | NG_ADAM_PRINTED                                 */
+    int32_t refresh_power_iters;  /* subspace-iteration passes q >= 0 of the refresh               */
+    int32_t refresh_oversample;   /* extra sketch columns p >= 0; sketch width l = min(r+p, m, n)  */
+    int32_t refresh_sweeps;       /* maximum Jacobi sweeps of the l x l eigen-solve, >= 1          */
+    uint64_t seed;                /* seed of the refresh's random sketch                            */
+} ng_hparams;
+
+typedef struct ng_matrix_buffers {
+    void* buf[NG_NBUF];
+} ng_matrix_buffers;
+
+typedef struct ng_matrix_layout {
+    int32_t ldn;        /* padded row length (elements) of M, V, N and of every H slot; columns >= n are 0 */
+    int32_t l;          /* sketch width of the refresh                                                   */
+    int64_t slot_elems; /* r * ldn: elements per history slot                                            */
+    int64_t k_gram_off, k_w64_off, k_w32_off;  /* byte offsets inside the K buffer                       */
+} ng_matrix_layout;
+
+/* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
+ * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps, seed 0. */
+int ng_default_hparams(ng_hparams* hp);
+
+/* Bytes the caller must allocate.  bytes[i*NG_NBUF + b] = size of buffer b of
+ * matrix i (256-byte aligned device memory); *workspace_bytes = size of the one
+ * shared workspace (tables, reduction partials, the refresh's scratch).
+ * Host-only; touches no device. */
+int ng_query_sizes(const ng_matrix_desc* descs, int n_mats, const ng_hparams* hp,
+                   size_t* bytes, size_t* workspace_bytes);
+
+/* flags for ng_init_state */
+enum { NG_INIT_DEFAULT = 0,
+       NG_INIT_NO_CLEAR = 1   /* caller has already zero-filled (or restored) every buffer */ };
+
+/* Create a handle over caller-owned buffers.  Unless NG_INIT_NO_CLEAR is given,
+ * enqueues zero-fills of M, V, H, K, N on `stream`.  Uploads its tables into
+ * `workspace` (synchronous copies).  Counters start at t = head = count =
+ * n_refresh = 0 and the projector is marked invalid. */
+int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, int n_mats,
+                  const ng_hparams* hp, void* workspace, size_t workspace_bytes,
+                  uint32_t flags, ng_stream stream, ng_state** out);
+
+/* Periodic subspace refresh (paper Sec. 1: P from the compact SVD of the
+ * gradient, updated every ~200 iterations; Sec. 2.2).  For every matrix:
+ * P <- approximation of the top-r left singular vectors of grads[i] by
+ * randomised subspace iteration + Rayleigh-Ritz, columns ordered by descending
+ * Ritz value, each column's largest-magnitude entry positive.  Keeps M, V and t;
+ * clears H and K; head = count = 0; n_refresh += 1.  grads[i]: m x n, ld_g,
+ * grad_dtype; read-only. */
+int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream stream);
+
+/* The caller has written P (float [m][r], orthonormal columns) into every
+ * NG_BUF_P itself (resume from a checkpoint, an external SVD).  Builds the
+ * internal copies, marks the projector valid.  clear_history != 0 also clears H,
+ * K and sets head = count = 0 and n_refresh += 1 (as a refresh does). */
+int ng_commit_projector(ng_state* st, int clear_history, ng_stream stream);
+
+/* One optimizer step on every matrix (paper Sec. 2.4 with Sec. 2.2):
+ *   R = P^T G                           -> written into ring slot `head`
+ *   K[head][:] = <R, H_j>_F             -> (lambda I + K/s) w = e_head   (fp64, Cholesky)
+ *   g~ = sum_j w_j H_j                  == (lambda I + (1/s) sum_j vec(H_j)vec(H_j)^T)^{-1} vec(R)
+ *   M, V <- Adam moments of g~ ;  N = update direction
+ *   W <- W - lr * (scale * P N + weight_decay * W)
+ * then t += 1, head = (head+1) mod s, count = min(count+1, s) on the host.
+ * grads[i] read-only, weights[i] (m x n, ld_w, grad_dtype) updated in place. */
+int ng_step(ng_state* st, const void* const* grads, void* const* weights, float lr,
+            ng_stream stream);
+
+int ng_get_counters(const ng_state* st, int mat, int64_t* t, int32_t* head, int32_t* count,
+                    int64_t* n_refresh);
+/* Resume: requires 0 <= head < max(s,1), 0 <= count <= s, t >= 0. */
+int ng_set_counters(ng_state* st, int mat, int64_t t, int32_t head, int32_t count,
+                    int64_t n_refresh);
+
+int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out);
+
+/* Synchronises `stream`, reads and clears the device's sticky flag.  Returns
+ * NG_OK, NG_ERR_NUMERIC or NG_ERR_HIP. */
+int ng_get_status(ng_state* st, ng_stream stream);
+
+/* Phase timing with HIP events on the stream of the call.  When enabled, ng_step
+ * records an event before each phase (project, gram, solve, adam, update) and
+ * one after the last.  ng_get_phase_ms synchronises on the last event and adds
+ * the elapsed milliseconds of every profiled step since the last reset into
+ * ms[0..4]; *steps = number of steps accumulated.  reset != 0 clears the sums. */
+enum { NG_PHASE_PROJECT = 0, NG_PHASE_GRAM, NG_PHASE_SOLVE, NG_PHASE_ADAM, NG_PHASE_UPDATE,
+       NG_NPHASE };
+int ng_set_profiling(ng_state* st, int enabled);
+int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset);
+
+const char* ng_strerror(int code);
+void ng_destroy(ng_state* st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NG_H_ */

@@ -1,0 +1,365 @@
+// HBM-bound phases of the Natural GaLore step (paper Sec. 2.4 and the Adam
+// equations of Sec. 2.2), plus small utility kernels.
+//
+//   k_gram_row        y_j = <R, H_j>_F for all s ring slots (the new row of the s x s Gram matrix)
+//   k_solve           (lambda I + K/s) w = e_head by Cholesky in fp64, one wavefront per matrix
+//   k_transform_adam  g~ = sum_j w_j H_j, Adam moments, update direction N
+//
+// The transform is evaluated as H_mat (lambda I + K/s)^{-1} e_head.  This equals
+// the section's g/lambda - U z/lambda^2 (push U through the inverse: the current
+// gradient is slot `head` of the stack) but has no cancellation, which the printed
+// form has at about log10(||R||^2 / (s lambda)) digits.
+#include "ng_internal.h"
+
+namespace ng {
+
+// ------------------------------------------------------------------ helpers
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
+    unsigned int u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------ per-step table upload
+__global__ void k_upload_dyn(MatDyn* table, DynChunk chunk, int first, int n) {
+    int i = threadIdx.x;
+    if (i < n) table[first + i] = chunk.e[i];
+}
+
+hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, hipStream_t stream) {
+    hipLaunchKernelGGL(k_upload_dyn, dim3(1), dim3(128), 0, stream, table, chunk, first, n);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ zero fill
+__global__ void k_fill_zero(uint4* p16, size_t n16, unsigned int* tail, int ntail) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint4 z = make_uint4(0, 0, 0, 0);
+    for (; i < n16; i += stride) p16[i] = z;
+    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0u;
+}
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    size_t n16 = bytes / 16;
+    int ntail = (int)((bytes % 16) / 4);
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, stream, (uint4*)ptr, n16,
+                       (unsigned int*)((char*)ptr + n16 * 16), ntail);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ Gram row
+// One workgroup = one contiguous part of the flat r*ldn range of one matrix.
+// Products and 4-term sums in fp32, running sums in fp64, fixed reduction order.
+template <int SMAX>
+__global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mats,
+                                                  const MatDyn* __restrict__ dyn,
+                                                  const TileRef* __restrict__ chunks, int s) {
+    const TileRef c = chunks[blockIdx.x];
+    const MatDev& md = mats[c.mat];
+    const int head = dyn[c.mat].head;
+    const long long total4 = md.slot_elems >> 2;
+    const long long span = (long long)md.dot_iters * 256;
+    const long long q0 = (long long)c.ti * span;
+    long long q1 = q0 + span;
+    if (q1 > total4) q1 = total4;
+    const float4* __restrict__ R = reinterpret_cast<const float4*>(md.H + (long long)head * md.slot_elems);
+    const float4* __restrict__ H = reinterpret_cast<const float4*>(md.H);
+
+    double acc[SMAX];
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) acc[j] = 0.0;
+
+    for (long long q = q0 + threadIdx.x; q < q1; q += 256) {
+        const float4 rv = R[q];
+#pragma unroll
+        for (int j = 0; j < SMAX; ++j) {
+            if (j < s) {
+                const float4 h = H[(long long)j * total4 + q];
+                float p = h.x * rv.x;
+                p = fmaf(h.y, rv.y, p);
+                p = fmaf(h.z, rv.z, p);
+                p = fmaf(h.w, rv.w, p);
+                acc[j] += (double)p;
+            }
+        }
+    }
+
+    __shared__ double red[4][SMAX];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) {
+        double v = wave_sum(acc[j]);
+        if (lane == 0) red[wv][j] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < s) {
+        double v = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+        md.dot_parts[(long long)c.ti * s + threadIdx.x] = v;
+    }
+}
+
+hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks, int s,
+                           hipStream_t stream) {
+    if (n_chunks == 0) return hipSuccess;
+    dim3 g(n_chunks), b(256);
+    if (s <= 4) hipLaunchKernelGGL(k_gram_row<4>, g, b, 0, stream, mats, dyn, chunks, s);
+    else if (s <= 8) hipLaunchKernelGGL(k_gram_row<8>, g, b, 0, stream, mats, dyn, chunks, s);
+    else if (s <= 16) hipLaunchKernelGGL(k_gram_row<16>, g, b, 0, stream, mats, dyn, chunks, s);
+    else if (s <= 32) hipLaunchKernelGGL(k_gram_row<32>, g, b, 0, stream, mats, dyn, chunks, s);
+    else hipLaunchKernelGGL(k_gram_row<64>, g, b, 0, stream, mats, dyn, chunks, s);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ s x s solve
+// One wavefront per matrix.  Sums the partial dot products in a fixed order,
+// writes row/column `head` of K, factors A = lambda I + K/s (Cholesky, fp64, in
+// LDS) and solves A w = e_head.  A non-positive or non-finite pivot sets bit 0
+// of *status; a non-finite w sets bit 1.
+__global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
+                                              StepScalars sc, int* status) {
+    __shared__ double A[kMaxS][kMaxS + 1];
+    __shared__ double bc[kMaxS];
+    const MatDev& md = mats[blockIdx.x];
+    const int s = sc.s;
+    const int head = dyn[blockIdx.x].head;
+    const int i = threadIdx.x;
+
+    // old Gram matrix into LDS, then overwrite row and column `head` with the new dots
+    if (i < s)
+        for (int j = 0; j < s; ++j) A[i][j] = md.K[(long long)i * s + j];
+    __syncthreads();
+    if (i < s) {
+        double v = 0.0;
+        for (int p = 0; p < md.dot_nparts; ++p) v += md.dot_parts[(long long)p * s + i];
+        md.K[(long long)head * s + i] = v;
+        md.K[(long long)i * s + head] = v;
+        A[head][i] = v;
+        A[i][head] = v;
+    }
+    __syncthreads();
+    const double lam = (double)sc.lambda;
+    const double inv_s = 1.0 / (double)s;
+    if (i < s)
+        for (int j = 0; j < s; ++j) A[i][j] = A[i][j] * inv_s + (i == j ? lam : 0.0);
+    __syncthreads();
+
+    bool bad = false;
+    for (int k = 0; k < s; ++k) {
+        double d = A[k][k];
+        if (!(d > 0.0) || !(d < 1.0e300)) {
+            bad = true;
+            d = 1.0;
+        }
+        d = sqrt(d);
+        __syncthreads();
+        if (i == k) A[k][k] = d;
+        if (i > k && i < s) A[i][k] = A[i][k] / d;
+        __syncthreads();
+        if (i > k && i < s) {
+            const double lik = A[i][k];
+            for (int j = k + 1; j <= i; ++j) A[i][j] -= lik * A[j][k];
+        }
+        __syncthreads();
+    }
+
+    // forward: L y = e_head
+    double b = (i == head) ? 1.0 : 0.0;
+    for (int k = 0; k < s; ++k) {
+        if (i == k) bc[k] = b / A[k][k];
+        __syncthreads();
+        if (i > k && i < s) b -= A[i][k] * bc[k];
+        __syncthreads();
+    }
+    // backward: L^T w = y
+    double y = (i < s) ? bc[i] : 0.0;
+    __syncthreads();
+    for (int k = s - 1; k >= 0; --k) {
+        if (i == k) bc[k] = y / A[k][k];
+        __syncthreads();
+        if (i < k) y -= A[k][i] * bc[k];
+        __syncthreads();
+    }
+    if (i < s) {
+        const double w = bc[i];
+        if (!(fabs(w) < 1.0e300)) bad = true;
+        md.w64[i] = w;
+        md.w32[i] = (float)w;
+    }
+    if (bad) atomicOr(status, 1);
+}
+
+hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int n_mats, StepScalars sc, int* status,
+                        hipStream_t stream) {
+    hipLaunchKernelGGL(k_solve, dim3(n_mats), dim3(64), 0, stream, mats, dyn, sc, status);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ transform + Adam
+// One thread owns an 8 (rows) x 4 (columns) patch of the r x ldn space, a
+// wavefront 8 rows x 256 columns, a workgroup 32 rows x 256 columns.
+//   g~ = sum_j w_j H_j          (second pass over the ring; w from k_solve)
+//   M <- b1 M + (1-b1) g~ ; V <- b2 V + (1-b2) g~^2
+//   N  = (M * bc1) / (sqrt(V) * bc2 + eps)         standard
+//      = M / sqrt(V + eps)                          as printed
+// N is stored either as float [r][ldn] or as bf16 [r/8][ldn][8] (eight
+// consecutive rows of one column adjacent: the k-packing the update GEMM's MFMA
+// operand wants, so that kernel needs no transpose).
+template <bool BF16_N>
+__global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict__ mats,
+                                                        const MatDyn* __restrict__ dyn,
+                                                        const TileRef* __restrict__ patches, StepScalars sc,
+                                                        int* status) {
+    const TileRef pr = patches[blockIdx.x];
+    const MatDev& md = mats[pr.mat];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int row0 = pr.ti * 32 + wv * 8;
+    const int col0 = pr.tj * 256 + lane * 4;
+    const int ldn = md.ldn, r = md.r;
+    if (row0 >= r || col0 >= ldn) return;
+    const int nrow = (r - row0 < 8) ? (r - row0) : 8;
+    const long long base = (long long)row0 * ldn + col0;
+
+    float4 g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    const int s = sc.s;
+    if (sc.use_fisher) {
+        const float* __restrict__ w = md.w32;
+        for (int j = 0; j < s; ++j) {
+            const float wj = w[j];
+            const float* __restrict__ Hj = md.H + (long long)j * md.slot_elems + base;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (e < nrow) {
+                    const float4 h = *reinterpret_cast<const float4*>(Hj + (long long)e * ldn);
+                    g[e].x = fmaf(wj, h.x, g[e].x);
+                    g[e].y = fmaf(wj, h.y, g[e].y);
+                    g[e].z = fmaf(wj, h.z, g[e].z);
+                    g[e].w = fmaf(wj, h.w, g[e].w);
+                }
+            }
+        }
+    } else {
+        const float* __restrict__ H0 = md.H + base;   // the single scratch slot holds R
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < nrow) g[e] = *reinterpret_cast<const float4*>(H0 + (long long)e * ldn);
+    }
+
+    const float b1 = sc.beta1, b2 = sc.beta2, ob1 = 1.0f - sc.beta1, ob2 = 1.0f - sc.beta2;
+    const float bc1 = dyn[pr.mat].bc1, bc2 = dyn[pr.mat].bc2;
+    float4 nv[8];
+    bool bad = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        nv[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (e < nrow) {
+            float4* Mp = reinterpret_cast<float4*>(md.M + base + (long long)e * ldn);
+            float4* Vp = reinterpret_cast<float4*>(md.V + base + (long long)e * ldn);
+            float4 m = *Mp, v = *Vp;
+            const float4 ge = g[e];
+            m.x = fmaf(b1, m.x, ob1 * ge.x);
+            m.y = fmaf(b1, m.y, ob1 * ge.y);
+            m.z = fmaf(b1, m.z, ob1 * ge.z);
+            m.w = fmaf(b1, m.w, ob1 * ge.w);
+            v.x = fmaf(b2, v.x, ob2 * ge.x * ge.x);
+            v.y = fmaf(b2, v.y, ob2 * ge.y * ge.y);
+            v.z = fmaf(b2, v.z, ob2 * ge.z * ge.z);
+            v.w = fmaf(b2, v.w, ob2 * ge.w * ge.w);
+            *Mp = m;
+            *Vp = v;
+            float4 o;
+            if (sc.adam_mode == NG_ADAM_STANDARD) {
+                o.x = (m.x * bc1) / (sqrtf(v.x) * bc2 + sc.eps);
+                o.y = (m.y * bc1) / (sqrtf(v.y) * bc2 + sc.eps);
+                o.z = (m.z * bc1) / (sqrtf(v.z) * bc2 + sc.eps);
+                o.w = (m.w * bc1) / (sqrtf(v.w) * bc2 + sc.eps);
+            } else {
+                o.x = m.x / sqrtf(v.x + sc.eps);
+                o.y = m.y / sqrtf(v.y + sc.eps);
+                o.z = m.z / sqrtf(v.z + sc.eps);
+                o.w = m.w / sqrtf(v.w + sc.eps);
+            }
+            bad |= !(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
+                   !(fabsf(o.w) <= 3.0e38f);
+            nv[e] = o;
+        }
+    }
+
+    if (BF16_N) {
+        // [octet][col][8]: this thread's 4 columns are 4 consecutive 16-byte units
+        uint4* Np = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(md.N) +
+                                             ((long long)(row0 >> 3) * ldn + col0) * 8);
+        const float* f = reinterpret_cast<const float*>(nv);   // f[e*4 + c]
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint4 o;
+            o.x = (unsigned)f32_to_bf16_rne(f[0 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[1 * 4 + c]) << 16);
+            o.y = (unsigned)f32_to_bf16_rne(f[2 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[3 * 4 + c]) << 16);
+            o.z = (unsigned)f32_to_bf16_rne(f[4 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[5 * 4 + c]) << 16);
+            o.w = (unsigned)f32_to_bf16_rne(f[6 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[7 * 4 + c]) << 16);
+            Np[c] = o;
+        }
+    } else {
+        float* Nf = reinterpret_cast<float*>(md.N) + base;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < nrow) *reinterpret_cast<float4*>(Nf + (long long)e * ldn) = nv[e];
+    }
+    if (bad) atomicOr(status, 2);
+}
+
+hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,
+                                 StepScalars sc, int grad_dtype, int* status, hipStream_t stream) {
+    if (n_patches == 0) return hipSuccess;
+    if (grad_dtype == NG_BF16)
+        hipLaunchKernelGGL(k_transform_adam<true>, dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches, sc,
+                           status);
+    else
+        hipLaunchKernelGGL(k_transform_adam<false>, dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches, sc,
+                           status);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bf16 copies of P
+// Pb[i][rho] = bf16(P[i][rho]) (zero for r <= rho < ldr), PbT[rho][i] = bf16(P[i][rho])
+// (zero for m <= i < ldk).  32 x 32 tiles through LDS so both writes are row-contiguous.
+__global__ __launch_bounds__(256) void k_make_bf16_copies(const MatDev* __restrict__ mats) {
+    __shared__ float tile[32][33];
+    const MatDev& md = mats[blockIdx.z];
+    const int i0 = blockIdx.y * 32, r0 = blockIdx.x * 32;
+    if (i0 >= md.ldk || r0 >= md.ldr) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int yy = ty; yy < 32; yy += 8) {
+        const int i = i0 + yy, rho = r0 + tx;
+        float v = 0.f;
+        if (i < md.m && rho < md.r) v = md.P[(long long)i * md.r + rho];
+        tile[yy][tx] = v;
+        if (i < md.m && rho < md.ldr) md.Pb[(long long)i * md.ldr + rho] = f32_to_bf16_rne(v);
+    }
+    __syncthreads();
+    for (int yy = ty; yy < 32; yy += 8) {
+        const int rho = r0 + yy, i = i0 + tx;
+        if (rho < md.r && i < md.ldk) md.PbT[(long long)rho * md.ldk + i] = f32_to_bf16_rne(tile[tx][yy]);
+    }
+}
+
+hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, int max_r, hipStream_t stream) {
+    dim3 g((max_r + 31) / 32, (max_m + 8 + 31) / 32, n_mats);
+    hipLaunchKernelGGL(k_make_bf16_copies, g, dim3(256), 0, stream, mats);
+    return hipGetLastError();
+}
+
+}  // namespace ng

@@ -1,0 +1,363 @@
+// Small dense linear algebra of the projector refresh (paper Sec. 1: P = leading
+// left singular vectors of the gradient, recomputed every ~200 steps).  The
+// large products run on the grouped fp32 MFMA GEMM; this file holds what sits
+// between them, one launch for all matrices of the layer set:
+//
+//   k_fill_gaussian     random sketch Omega (counter-based generator, Box-Muller)
+//   k_cholesky          T = L L^T in place (fp64, left-looking, one workgroup per matrix)
+//   k_tri_inverse       Linv = L^{-1} as float (the GEMM then applies X <- X Linv^T)
+//   k_jacobi_*          blocked one-sided Jacobi on the rows of the l x l Rayleigh-Ritz matrix
+//                       T = (Q^T G)(Q^T G)^T: at convergence row i = ritz_i * u_i^T
+//   k_ritz_sort / k_build_rotation   order by descending Ritz value, stage U[:, top r]
+//   k_sign_fix          copy the orthonormalised basis into P, largest-magnitude entry of each
+//                       column made positive
+#include "ng_internal.h"
+
+namespace ng {
+
+// ------------------------------------------------------------------ random sketch
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void k_fill_gaussian(const MatDev* __restrict__ mats, unsigned long long seed,
+                                                       unsigned long long call_id) {
+    const MatDev& md = mats[blockIdx.y];
+    const long long total = (long long)md.n * md.l;
+    const unsigned long long key =
+        mix64(seed ^ (call_id * 0x9E3779B97F4A7C15ULL) ^ ((unsigned long long)(blockIdx.y + 1) * 0xD1B54A32D192ED03ULL));
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const unsigned long long z = mix64(key + (unsigned long long)(i + 1) * 0x9E3779B97F4A7C15ULL);
+        const float u1 = ((float)(unsigned int)(z >> 40) + 1.0f) * (1.0f / 16777216.0f);      // (0, 1]
+        const float u2 = (float)(unsigned int)((z >> 8) & 0xFFFFFFu) * (1.0f / 16777216.0f);   // [0, 1)
+        md.Yb[i] = sqrtf(-2.0f * logf(u1)) * cosf(6.28318530717958647692f * u2);
+    }
+}
+
+hipError_t launch_fill_gaussian(const MatDev* mats, int n_mats, int max_rows, unsigned long long seed,
+                                unsigned long long call_id, hipStream_t stream) {
+    int gx = (max_rows + 3) / 4;   // grid-stride loop covers the rest
+    if (gx < 1) gx = 1;
+    if (gx > 4096) gx = 4096;
+    hipLaunchKernelGGL(k_fill_gaussian, dim3(gx, n_mats), dim3(256), 0, stream, mats, seed, call_id);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ Cholesky (fp64, in place, lower)
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+constexpr int kCholThreads = 1024;
+constexpr int kCholMaxOrder = 4096;
+
+// which: 0 -> order l, 1 -> order r.  T has leading dimension lp.  shift_rel * trace(T) is added
+// to the diagonal first.  A non-positive pivot sets bit 2 of *status (the pivot is replaced by 1).
+__global__ __launch_bounds__(kCholThreads) void k_cholesky(const MatDev* __restrict__ mats, int which,
+                                                           double shift_rel, int* status) {
+    __shared__ double rowk[kCholMaxOrder];
+    __shared__ double red[16];
+    __shared__ double piv;
+    const MatDev& md = mats[blockIdx.x];
+    const int nn = which == 0 ? md.l : md.r;
+    const long long ld = md.lp;
+    double* __restrict__ A = md.T;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    constexpr int NWV = kCholThreads / 64;
+
+    if (shift_rel > 0.0) {
+        double tr = 0.0;
+        for (int i = tid; i < nn; i += kCholThreads) tr += A[i * ld + i];
+        tr = wave_sum_d(tr);
+        if (lane == 0) red[wv] = tr;
+        __syncthreads();
+        double tot = 0.0;
+        for (int w = 0; w < NWV; ++w) tot += red[w];
+        const double shift = shift_rel * tot;
+        __syncthreads();
+        for (int i = tid; i < nn; i += kCholThreads) A[i * ld + i] += shift;
+        __syncthreads();
+    }
+
+    bool bad = false;
+    for (int k = 0; k < nn; ++k) {
+        for (int j = tid; j < k; j += kCholThreads) rowk[j] = A[(long long)k * ld + j];
+        __syncthreads();
+        // rows i >= k: A[i][k] -= sum_{j<k} L[i][j] L[k][j]
+        for (int i = k + wv; i < nn; i += NWV) {
+            const double* __restrict__ ri = A + (long long)i * ld;
+            double d = 0.0;
+            for (int j = lane; j < k; j += 64) d += ri[j] * rowk[j];
+            d = wave_sum_d(d);
+            if (lane == 0) {
+                const double v = ri[k] - d;
+                A[(long long)i * ld + k] = v;
+                if (i == k) piv = v;
+            }
+        }
+        __syncthreads();
+        double d = piv;
+        if (!(d > 0.0) || !(d < 1.0e300)) {
+            bad = true;
+            d = 1.0;
+        }
+        d = sqrt(d);
+        const double inv = 1.0 / d;
+        for (int i = k + tid; i < nn; i += kCholThreads) {
+            if (i == k) A[(long long)k * ld + k] = d;
+            else A[(long long)i * ld + k] *= inv;
+        }
+        __syncthreads();
+    }
+    if (bad && tid == 0) atomicOr(status, 4);
+}
+
+hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shift_rel, int* status,
+                           hipStream_t stream) {
+    hipLaunchKernelGGL(k_cholesky, dim3(n_mats), dim3(kCholThreads), 0, stream, mats, which, shift_rel, status);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ inverse of the Cholesky factor
+// Thread c owns column c of Linv = L^{-1} (forward substitution on e_c); all threads walk the
+// rows together so L[i][p] is one broadcast load and Linv[p][c] is coalesced over c.
+__global__ __launch_bounds__(1024) void k_tri_inverse(const MatDev* __restrict__ mats, int which) {
+    const MatDev& md = mats[blockIdx.x];
+    const int nn = which == 0 ? md.l : md.r;
+    const long long ld = md.lp;
+    const double* __restrict__ L = md.T;
+    float* __restrict__ X = md.Linv;
+    for (int c = threadIdx.x; c < nn; c += blockDim.x) {
+        // forward substitution L x = e_c; entries above the diagonal come out as exact zeros
+        for (int i = 0; i < nn; ++i) {
+            const double* __restrict__ li = L + (long long)i * ld;
+            double acc = 0.0;
+            for (int p = 0; p < i; ++p) acc += li[p] * (double)X[(long long)p * ld + c];
+            X[(long long)i * ld + c] = (float)(((i == c ? 1.0 : 0.0) - acc) / li[i]);
+        }
+    }
+}
+
+hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, hipStream_t stream) {
+    hipLaunchKernelGGL(k_tri_inverse, dim3(n_mats), dim3(1024), 0, stream, mats, which);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ blocked one-sided Jacobi
+// X (lp x lp, fp64, row-major) starts as the symmetric matrix T (rows/columns >= l zero).
+// Rotating ROWS until they are mutually orthogonal gives X = Lambda U^T: row i is
+// ritz_i * u_i^T.  Rows are grouped in blocks of jb; one workgroup holds two blocks in LDS and
+// sweeps all row pairs of the 2*jb rows; block pairs follow a round-robin tournament so the
+// lp/jb - 1 rounds of one sweep meet every block pair once.
+__device__ __forceinline__ void tournament_pair(int players, int round, int k, int* a, int* b) {
+    const int N = players - 1;
+    if (k == 0) {
+        *a = N;
+        *b = round % N;
+    } else {
+        *a = (round + k) % N;
+        *b = (round - k + N) % N;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_jacobi_prepare(const MatDev* __restrict__ mats) {
+    const MatDev& md = mats[blockIdx.y];
+    const int lp = md.lp, l = md.l;
+    const long long total = (long long)lp * lp;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256) {
+        const int i = (int)(q / lp), j = (int)(q % lp);
+        if (i >= l || j >= l) md.T[q] = 0.0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) md.jflag[threadIdx.x] = 0;
+}
+
+hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t stream) {
+    hipLaunchKernelGGL(k_jacobi_prepare, dim3(64, n_mats), dim3(256), 0, stream, mats);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_jacobi_round(const MatDev* __restrict__ mats, int round) {
+    extern __shared__ __attribute__((aligned(16))) double xs[];   // [2*jb][lp]
+    __shared__ int nrot_s;
+    const MatDev& md = mats[blockIdx.y];
+    const int lp = md.lp, jb = md.jb;
+    const int nb = lp / jb;
+    if ((int)blockIdx.x >= nb / 2 || round >= nb - 1) return;
+    if (md.jflag[1] != 0) return;   // converged in an earlier sweep
+    int bp, bq;
+    tournament_pair(nb, round, blockIdx.x, &bp, &bq);
+    const int tid = threadIdx.x;
+    const int R = 2 * jb;
+    double* __restrict__ X = md.T;
+    for (int q = tid; q < jb * lp; q += 256) {
+        xs[q] = X[(long long)bp * jb * lp + q];
+        xs[jb * lp + q] = X[(long long)bq * jb * lp + q];
+    }
+    if (tid == 0) nrot_s = 0;
+    __syncthreads();
+
+    const int tpp = 256 / jb;            // threads per row pair (power of two, <= 64)
+    const int pi = tid / tpp, sub = tid % tpp;
+    int nrot = 0;
+    for (int ir = 0; ir < R - 1; ++ir) {
+        int a, b;
+        tournament_pair(R, ir, pi, &a, &b);
+        double* xa = xs + a * lp;
+        double* xb = xs + b * lp;
+        double al = 0.0, be = 0.0, ga = 0.0;
+        for (int c = sub; c < lp; c += tpp) {
+            const double va = xa[c], vb = xb[c];
+            al += va * va;
+            be += vb * vb;
+            ga += va * vb;
+        }
+        for (int off = tpp >> 1; off > 0; off >>= 1) {
+            al += __shfl_xor(al, off, 64);
+            be += __shfl_xor(be, off, 64);
+            ga += __shfl_xor(ga, off, 64);
+        }
+        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-24 * al * be);
+        if (rot) {
+            const double zeta = (be - al) / (2.0 * ga);
+            const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+            const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+            for (int c = sub; c < lp; c += tpp) {
+                const double va = xa[c], vb = xb[c];
+                xa[c] = cs * va - sn * vb;
+                xb[c] = sn * va + cs * vb;
+            }
+            if (sub == 0) ++nrot;
+        }
+        __syncthreads();
+    }
+    if (nrot) atomicAdd(&nrot_s, nrot);
+    __syncthreads();
+    for (int q = tid; q < jb * lp; q += 256) {
+        X[(long long)bp * jb * lp + q] = xs[q];
+        X[(long long)bq * jb * lp + q] = xs[jb * lp + q];
+    }
+    if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
+}
+
+hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
+                               hipStream_t stream) {
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kJacobiLdsBudget);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(k_jacobi_round, dim3(max_pairs, n_mats), dim3(256), lds_bytes, stream, mats, round);
+    return hipGetLastError();
+}
+
+__global__ void k_jacobi_sweep_end(const MatDev* __restrict__ mats, int n_mats) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_mats) return;
+    int* f = mats[i].jflag;
+    if (f[1] == 0) {
+        f[2] += 1;                 // sweeps performed
+        if (f[0] == 0) f[1] = 1;   // no rotation in this sweep: converged
+    }
+    f[0] = 0;
+}
+
+hipError_t launch_jacobi_sweep_end(const MatDev* mats, int n_mats, hipStream_t stream) {
+    hipLaunchKernelGGL(k_jacobi_sweep_end, dim3((n_mats + 63) / 64), dim3(64), 0, stream, mats, n_mats);
+    return hipGetLastError();
+}
+
+// Ritz values (row norms), descending order, then the l x r rotation U[:, top r] as floats in Bm.
+__global__ __launch_bounds__(256) void k_ritz_sort(const MatDev* __restrict__ mats, int* status) {
+    const MatDev& md = mats[blockIdx.x];
+    const int lp = md.lp;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int i = wv; i < lp; i += 4) {
+        const double* __restrict__ row = md.T + (long long)i * lp;
+        double a = 0.0;
+        for (int c = lane; c < lp; c += 64) a += row[c] * row[c];
+        a = wave_sum_d(a);
+        if (lane == 0) md.ritz[i] = sqrt(a);
+    }
+    __syncthreads();
+    __threadfence_block();
+    bool bad = false;
+    for (int i = threadIdx.x; i < lp; i += 256) {
+        const double vi = md.ritz[i];
+        int rank = 0;
+        for (int j = 0; j < lp; ++j) {
+            const double vj = md.ritz[j];
+            rank += (vj > vi) || (vj == vi && j < i);
+        }
+        md.order[rank] = i;
+        if (rank < md.r && !(vi > 0.0)) bad = true;
+    }
+    if (bad) atomicOr(status, 8);
+}
+
+__global__ __launch_bounds__(256) void k_build_rotation(const MatDev* __restrict__ mats) {
+    const MatDev& md = mats[blockIdx.y];
+    const int l = md.l, r = md.r, lp = md.lp;
+    const long long total = (long long)l * r;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256) {
+        const int k = (int)(q / r), j = (int)(q % r);
+        const int src = md.order[j];
+        const double nrm = md.ritz[src];
+        md.Bm[q] = nrm > 0.0 ? (float)(md.T[(long long)src * lp + k] / nrm) : 0.f;
+    }
+}
+
+hipError_t launch_jacobi_finish(const MatDev* mats, int n_mats, int* status, hipStream_t stream) {
+    hipLaunchKernelGGL(k_ritz_sort, dim3(n_mats), dim3(256), 0, stream, mats, status);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_build_rotation, dim3(128, n_mats), dim3(256), 0, stream, mats);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ sign convention, copy into P
+// Source: Ya viewed as [m][r].  Each column is multiplied by the sign of its entry of largest
+// magnitude (first one on ties) and written to P.
+__global__ __launch_bounds__(256) void k_sign_fix(const MatDev* __restrict__ mats) {
+    __shared__ float best[4][64];
+    __shared__ int besti[4][64];
+    const MatDev& md = mats[blockIdx.y];
+    const int r = md.r, m = md.m;
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int rg = threadIdx.x >> 6;
+    if (blockIdx.x * 64 >= r) return;
+    const float* __restrict__ src = md.Ya;
+    float bv = -1.f;
+    int bi = 0;
+    if (c < r)
+        for (int i = rg; i < m; i += 4) {
+            const float a = fabsf(src[(long long)i * r + c]);
+            if (a > bv) { bv = a; bi = i; }
+        }
+    best[rg][threadIdx.x & 63] = bv;
+    besti[rg][threadIdx.x & 63] = bi;
+    __syncthreads();
+    float sgn = 1.f;
+    if (c < r) {
+        float v = best[0][threadIdx.x & 63];
+        int idx = besti[0][threadIdx.x & 63];
+        for (int g = 1; g < 4; ++g) {
+            const float v2 = best[g][threadIdx.x & 63];
+            const int i2 = besti[g][threadIdx.x & 63];
+            if (v2 > v || (v2 == v && i2 < idx)) { v = v2; idx = i2; }
+        }
+        sgn = src[(long long)idx * r + c] < 0.f ? -1.f : 1.f;
+        for (int i = rg; i < m; i += 4) md.P[(long long)i * r + c] = sgn * src[(long long)i * r + c];
+    }
+}
+
+hipError_t launch_sign_fix(const MatDev* mats, int n_mats, int max_r, hipStream_t stream) {
+    hipLaunchKernelGGL(k_sign_fix, dim3((max_r + 63) / 64, n_mats), dim3(256), 0, stream, mats);
+    return hipGetLastError();
+}
+
+}  // namespace ng

@@ -1,0 +1,712 @@
+// C ABI and host-side scheduler of the Natural GaLore step library.
+// Validates arguments, owns the integer bookkeeping (step counter, ring head,
+// valid-slot count, refresh count), lays out the caller's workspace and
+// enqueues the grouped kernels of every phase.  Allocates no device memory.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "ng_internal.h"
+
+using namespace ng;
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+struct Sizes {   // per-matrix derived sizes
+    int ldn, l, ldk, ldr, roct, lp, jb;
+    size_t bytes[NG_NBUF];
+    size_t k_gram_off, k_w64_off, k_w32_off;
+    size_t aux_pb_off, aux_pbt_off;
+    // refresh scratch
+    size_t ws_y, ws_bm, ws_t, ws_linv, ws_ritz, ws_order, ws_flag, ws_parts;
+};
+
+int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
+    if (!d || !hp || n_mats <= 0) return NG_ERR_INVALID_ARG;
+    if (hp->grad_dtype != NG_F32 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
+    if (hp->adam_mode != NG_ADAM_STANDARD && hp->adam_mode != NG_ADAM_PRINTED) return NG_ERR_DTYPE;
+    if (hp->s < 0 || hp->s > kMaxS) return NG_ERR_SHAPE;
+    if (!(hp->lambda > 0.f) || !isfinite(hp->lambda)) return NG_ERR_HPARAM;
+    if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f)) return NG_ERR_HPARAM;
+    if (!(hp->eps > 0.f) || !isfinite(hp->eps)) return NG_ERR_HPARAM;
+    if (!isfinite(hp->scale) || !isfinite(hp->weight_decay)) return NG_ERR_HPARAM;
+    if (hp->refresh_power_iters < 0 || hp->refresh_power_iters > 16) return NG_ERR_HPARAM;
+    if (hp->refresh_oversample < 0 || hp->refresh_sweeps < 1 || hp->refresh_sweeps > 64) return NG_ERR_HPARAM;
+    for (int i = 0; i < n_mats; ++i) {
+        const ng_matrix_desc& x = d[i];
+        if (x.m <= 0 || x.n <= 0 || x.r <= 0) return NG_ERR_SHAPE;
+        if (x.r > x.m || x.r > x.n) return NG_ERR_SHAPE;
+        if (x.ld_w < x.n || x.ld_g < x.n) return NG_ERR_SHAPE;
+        if (x.reserved != 0) return NG_ERR_INVALID_ARG;
+        if ((long long)x.m > (1 << 24) || (long long)x.n > (1 << 24)) return NG_ERR_SHAPE;
+        if ((long long)x.r + hp->refresh_oversample > 2048) return NG_ERR_SHAPE;   // LDS budget of the Jacobi blocks
+    }
+    return NG_OK;
+}
+
+void derive(const ng_matrix_desc& d, const ng_hparams& hp, Sizes* z) {
+    memset(z, 0, sizeof(*z));
+    const int s = hp.s;
+    z->ldn = (int)align_up((size_t)d.n, 32);
+    int l = d.r + hp.refresh_oversample;
+    if (l > d.m) l = d.m;
+    if (l > d.n) l = d.n;
+    z->l = l;
+    z->ldk = (int)align_up((size_t)d.m, 8);
+    z->ldr = (int)align_up((size_t)d.r, 8);
+    z->roct = ceil_div(d.r, 8);
+    int jb = 16;
+    for (; jb > 4; jb >>= 1) {
+        size_t lp = align_up((size_t)l, (size_t)2 * jb);
+        if ((size_t)2 * jb * lp * sizeof(double) <= (size_t)kJacobiLdsBudget) break;
+    }
+    z->jb = jb;
+    z->lp = (int)align_up((size_t)l, (size_t)2 * jb);
+    const size_t rn = (size_t)d.r * z->ldn;
+    z->bytes[NG_BUF_P] = align_up((size_t)d.m * d.r * 4, 256);
+    z->bytes[NG_BUF_M] = align_up(rn * 4, 256);
+    z->bytes[NG_BUF_V] = align_up(rn * 4, 256);
+    z->bytes[NG_BUF_H] = align_up(rn * 4 * (size_t)(s > 0 ? s : 1), 256);
+    z->k_gram_off = 0;
+    z->k_w64_off = align_up((size_t)s * s * 8, 16);
+    z->k_w32_off = z->k_w64_off + align_up((size_t)s * 8, 16);
+    z->bytes[NG_BUF_K] = align_up(z->k_w32_off + (size_t)s * 4 + 16, 256);
+    if (hp.grad_dtype == NG_BF16) {
+        z->bytes[NG_BUF_N] = align_up((size_t)z->roct * z->ldn * 8 * 2, 256);
+        z->aux_pb_off = 0;
+        z->aux_pbt_off = align_up((size_t)d.m * z->ldr * 2, 256);
+        z->bytes[NG_BUF_AUX] = z->aux_pbt_off + align_up((size_t)d.r * z->ldk * 2, 256);
+    } else {
+        z->bytes[NG_BUF_N] = align_up(rn * 4, 256);
+        z->bytes[NG_BUF_AUX] = 0;
+    }
+    const size_t rows = (size_t)(d.m > d.n ? d.m : d.n);
+    z->ws_y = align_up(rows * l * 4, 256);
+    z->ws_bm = align_up((size_t)l * z->ldn * 4, 256);
+    z->ws_t = align_up((size_t)z->lp * z->lp * 8, 256);
+    z->ws_linv = align_up((size_t)z->lp * z->lp * 4, 256);
+    z->ws_ritz = align_up((size_t)z->lp * 8, 256);
+    z->ws_order = align_up((size_t)z->lp * 4, 256);
+    z->ws_flag = 256;
+    z->ws_parts = align_up((size_t)kDotPartsMax * (s > 0 ? s : 1) * 8, 256);
+}
+
+// Tables that live at the front of the workspace.
+struct Plan {
+    std::vector<Sizes> sz;
+    std::vector<TileRef> proj, upd, dots, patches;
+    size_t off_status, off_mats, off_dyn, off_proj, off_upd, off_dots, off_patches, off_scratch;
+    size_t total;
+};
+
+// Round-robin workgroup dispatch puts workgroup id w on XCD (w mod 8).  To let one XCD work
+// through a contiguous run of the logical tile order (tiles that share operand panels stay
+// in one L2), hardware id w takes logical index (w mod 8) * ceil(T/8) + w / 8.
+void xcd_order(const std::vector<TileRef>& logical, std::vector<TileRef>* out) {
+    const size_t T = logical.size();
+    const size_t per = (T + 7) / 8;
+    out->assign(per * 8, TileRef{-1, 0, 0, 0});
+    for (size_t w = 0; w < per * 8; ++w) {
+        size_t idx = (w % 8) * per + w / 8;
+        if (idx < T) (*out)[w] = logical[idx];
+    }
+}
+
+void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* p) {
+    p->sz.resize(n_mats);
+    int bm = 128, bn = 128;
+    bf16_tile_shape(&bm, &bn);
+    std::vector<TileRef> proj, upd;
+    p->dots.clear();
+    p->patches.clear();
+    for (int i = 0; i < n_mats; ++i) {
+        derive(d[i], hp, &p->sz[i]);
+        const Sizes& z = p->sz[i];
+        if (hp.grad_dtype == NG_BF16) {
+            for (int tj = 0; tj < ceil_div(z.ldn, bn); ++tj)
+                for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) proj.push_back(TileRef{i, ti, tj, 0});
+            for (int tj = 0; tj < ceil_div(d[i].n, bn); ++tj)
+                for (int ti = 0; ti < ceil_div(d[i].m, bm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
+        }
+        for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
+            for (int tj = 0; tj < ceil_div(z.ldn, 256); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
+    }
+    xcd_order(proj, &p->proj);
+    xcd_order(upd, &p->upd);
+    // Gram-row parts are appended in make_mats (they need dot_nparts)
+    size_t off = 0;
+    p->off_status = off; off += 256;
+    p->off_mats = off;   off += align_up(sizeof(MatDev) * (size_t)n_mats, 256);
+    p->off_dyn = off;    off += align_up(sizeof(MatDyn) * (size_t)n_mats, 256);
+    p->off_proj = off;   off += align_up(sizeof(TileRef) * p->proj.size(), 256);
+    p->off_upd = off;    off += align_up(sizeof(TileRef) * p->upd.size(), 256);
+    p->off_dots = off;   off += align_up(sizeof(TileRef) * (size_t)n_mats * kDotPartsMax, 256);
+    p->off_patches = off; off += align_up(sizeof(TileRef) * p->patches.size(), 256);
+    p->off_scratch = off;
+    for (int i = 0; i < n_mats; ++i) {
+        const Sizes& z = p->sz[i];
+        off += z.ws_parts + 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag;
+    }
+    p->total = off;
+}
+
+constexpr int kProfRing = 64;
+
+}  // namespace
+
+struct ng_state {
+    int n_mats;
+    ng_hparams hp;
+    std::vector<ng_matrix_desc> descs;
+    std::vector<ng_matrix_buffers> bufs;
+    std::vector<MatDev> mats;
+    Plan plan;
+    std::vector<int64_t> t, n_refresh;
+    std::vector<int32_t> head, count;
+    bool projector_valid;
+    char* ws;
+    MatDev* d_mats;
+    MatDyn* d_dyn;
+    int* d_status;
+    TileRef *d_proj, *d_upd, *d_dots, *d_patches;
+    int n_dots;
+    int max_m, max_n, max_r, max_l, max_lp, max_rows;
+    int max_ti[OP_COUNT], max_tj[OP_COUNT];
+    int max_jpairs;
+    size_t jacobi_lds;
+    // profiling
+    bool profiling;
+    hipEvent_t ev[kProfRing][NG_NPHASE + 1];
+    bool ev_created;
+    int ev_head, ev_pending;
+    double phase_ms[NG_NPHASE];
+    int64_t phase_steps;
+};
+
+namespace {
+
+#define NG_HIP(expr)                        \
+    do {                                    \
+        hipError_t e_ = (expr);             \
+        if (e_ != hipSuccess) return NG_ERR_HIP; \
+    } while (0)
+
+int upload_dyn(ng_state* st, const void* const* grads, void* const* weights, bool stepping, hipStream_t stream) {
+    DynChunk chunk;
+    const int s = st->hp.s;
+    for (int first = 0; first < st->n_mats; first += kDynChunk) {
+        int n = st->n_mats - first;
+        if (n > kDynChunk) n = kDynChunk;
+        memset(&chunk, 0, sizeof(chunk));
+        for (int i = 0; i < n; ++i) {
+            const int k = first + i;
+            MatDyn& e = chunk.e[i];
+            e.g = grads ? grads[k] : nullptr;
+            e.w = weights ? weights[k] : nullptr;
+            e.head = (s > 0) ? st->head[k] : 0;
+            int c = st->count[k] + (stepping ? 1 : 0);
+            e.count = c > s ? s : c;
+            const double tt = (double)(st->t[k] + 1);
+            if (st->hp.adam_mode == NG_ADAM_STANDARD) {
+                e.bc1 = (float)(1.0 / (1.0 - pow((double)st->hp.beta1, tt)));
+                e.bc2 = (float)(1.0 / sqrt(1.0 - pow((double)st->hp.beta2, tt)));
+            } else {
+                e.bc1 = 1.f;
+                e.bc2 = 1.f;
+            }
+        }
+        NG_HIP(launch_upload_dyn(st->d_dyn, chunk, first, n, stream));
+    }
+    return NG_OK;
+}
+
+StepScalars make_scalars(const ng_state* st, float lr) {
+    StepScalars sc;
+    memset(&sc, 0, sizeof(sc));
+    sc.lambda = st->hp.lambda;
+    sc.beta1 = st->hp.beta1;
+    sc.beta2 = st->hp.beta2;
+    sc.eps = st->hp.eps;
+    sc.lr_scale = lr * st->hp.scale;
+    sc.lr_wd = lr * st->hp.weight_decay;
+    sc.adam_mode = st->hp.adam_mode;
+    sc.s = st->hp.s > 0 ? st->hp.s : 1;
+    sc.use_fisher = st->hp.s > 0 ? 1 : 0;
+    return sc;
+}
+
+int clear_history(ng_state* st, hipStream_t stream) {
+    for (int i = 0; i < st->n_mats; ++i) {
+        NG_HIP(launch_fill_zero(st->bufs[i].buf[NG_BUF_H], st->plan.sz[i].bytes[NG_BUF_H], stream));
+        NG_HIP(launch_fill_zero(st->bufs[i].buf[NG_BUF_K], st->plan.sz[i].bytes[NG_BUF_K], stream));
+    }
+    return NG_OK;
+}
+
+int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
+    NG_HIP(launch_gemm_f32(op, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op],
+                           st->hp.grad_dtype, sc, stream));
+    return NG_OK;
+}
+
+// CholeskyQR of the sketch: X <- X L^{-T} twice (second pass repairs the loss of
+// orthogonality of the first).  rows_m: X has m rows (Ya) or n rows (Yb).
+int orthonormalise(ng_state* st, bool is_a, hipStream_t stream, const StepScalars& sc) {
+    int rc;
+    if ((rc = gemm(st, is_a ? OP_GRAM_A : OP_GRAM_B, stream, sc)) != NG_OK) return rc;
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 1e-10, st->d_status, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, stream));
+    if ((rc = gemm(st, is_a ? OP_APPLY_A2C : OP_APPLY_B2C, stream, sc)) != NG_OK) return rc;
+    if ((rc = gemm(st, is_a ? OP_GRAM_CA : OP_GRAM_CB, stream, sc)) != NG_OK) return rc;
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 0.0, st->d_status, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, stream));
+    if ((rc = gemm(st, is_a ? OP_APPLY_C2A : OP_APPLY_C2B, stream, sc)) != NG_OK) return rc;
+    return NG_OK;
+}
+
+int finish_projector(ng_state* st, bool clear, hipStream_t stream) {
+    if (st->hp.grad_dtype == NG_BF16)
+        NG_HIP(launch_make_bf16_copies(st->d_mats, st->n_mats, st->max_m, st->max_r, stream));
+    if (clear) {
+        int rc = clear_history(st, stream);
+        if (rc != NG_OK) return rc;
+    }
+    return NG_OK;
+}
+
+void drain_events(ng_state* st, bool all) {
+    while (st->ev_pending > 0 && (all || st->ev_pending >= kProfRing)) {
+        int slot = (st->ev_head - st->ev_pending + 2 * kProfRing) % kProfRing;
+        if (hipEventSynchronize(st->ev[slot][NG_NPHASE]) == hipSuccess) {
+            for (int p = 0; p < NG_NPHASE; ++p) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, st->ev[slot][p], st->ev[slot][p + 1]) == hipSuccess)
+                    st->phase_ms[p] += ms;
+            }
+            st->phase_steps += 1;
+        }
+        st->ev_pending -= 1;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int ng_default_hparams(ng_hparams* hp) {
+    if (!hp) return NG_ERR_INVALID_ARG;
+    memset(hp, 0, sizeof(*hp));
+    hp->s = 4;
+    hp->lambda = 1e-3f;
+    hp->beta1 = 0.9f;
+    hp->beta2 = 0.999f;
+    hp->eps = 1e-8f;
+    hp->scale = 1.0f;
+    hp->weight_decay = 0.0f;
+    hp->grad_dtype = NG_F32;
+    hp->adam_mode = NG_ADAM_STANDARD;
+    hp->refresh_power_iters = 2;
+    hp->refresh_oversample = 8;
+    hp->refresh_sweeps = 30;
+    hp->seed = 0;
+    return NG_OK;
+}
+
+int ng_query_sizes(const ng_matrix_desc* descs, int n_mats, const ng_hparams* hp, size_t* bytes,
+                   size_t* workspace_bytes) {
+    int rc = validate(descs, n_mats, hp);
+    if (rc != NG_OK) return rc;
+    if (!bytes || !workspace_bytes) return NG_ERR_INVALID_ARG;
+    try {
+        Plan plan;
+        make_plan(descs, n_mats, *hp, &plan);
+        for (int i = 0; i < n_mats; ++i)
+            for (int b = 0; b < NG_NBUF; ++b) bytes[(size_t)i * NG_NBUF + b] = plan.sz[i].bytes[b];
+        *workspace_bytes = plan.total;
+    } catch (...) {
+        return NG_ERR_INVALID_ARG;
+    }
+    return NG_OK;
+}
+
+int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, int n_mats, const ng_hparams* hp,
+                  void* workspace, size_t workspace_bytes, uint32_t flags, ng_stream stream_, ng_state** out) {
+    hipStream_t stream = (hipStream_t)stream_;
+    int rc = validate(descs, n_mats, hp);
+    if (rc != NG_OK) return rc;
+    if (!bufs || !out || !workspace) return NG_ERR_INVALID_ARG;
+    if (((uintptr_t)workspace & 255) != 0) return NG_ERR_WORKSPACE;
+    ng_state* st = nullptr;
+    try {
+        st = new ng_state();
+        st->n_mats = n_mats;
+        st->hp = *hp;
+        st->descs.assign(descs, descs + n_mats);
+        st->bufs.assign(bufs, bufs + n_mats);
+        make_plan(descs, n_mats, *hp, &st->plan);
+        if (workspace_bytes < st->plan.total) {
+            delete st;
+            return NG_ERR_WORKSPACE;
+        }
+        for (int i = 0; i < n_mats; ++i)
+            for (int b = 0; b < NG_NBUF; ++b) {
+                if (st->plan.sz[i].bytes[b] == 0) continue;
+                void* p = bufs[i].buf[b];
+                if (!p || ((uintptr_t)p & 15) != 0) {
+                    delete st;
+                    return NG_ERR_INVALID_ARG;
+                }
+            }
+        st->t.assign(n_mats, 0);
+        st->n_refresh.assign(n_mats, 0);
+        st->head.assign(n_mats, 0);
+        st->count.assign(n_mats, 0);
+        st->projector_valid = false;
+        st->profiling = false;
+        st->ev_created = false;
+        st->ev_head = st->ev_pending = 0;
+        memset(st->phase_ms, 0, sizeof(st->phase_ms));
+        st->phase_steps = 0;
+
+        char* ws = (char*)workspace;
+        st->ws = ws;
+        const Plan& pl = st->plan;
+        st->d_status = (int*)(ws + pl.off_status);
+        st->d_mats = (MatDev*)(ws + pl.off_mats);
+        st->d_dyn = (MatDyn*)(ws + pl.off_dyn);
+        st->d_proj = (TileRef*)(ws + pl.off_proj);
+        st->d_upd = (TileRef*)(ws + pl.off_upd);
+        st->d_dots = (TileRef*)(ws + pl.off_dots);
+        st->d_patches = (TileRef*)(ws + pl.off_patches);
+
+        st->mats.resize(n_mats);
+        std::vector<TileRef> dots;
+        size_t off = pl.off_scratch;
+        const int s_eff = hp->s > 0 ? hp->s : 1;
+        st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
+        st->max_jpairs = 0;
+        st->jacobi_lds = 0;
+        for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = 1;
+        for (int i = 0; i < n_mats; ++i) {
+            const Sizes& z = pl.sz[i];
+            MatDev& md = st->mats[i];
+            memset(&md, 0, sizeof(md));
+            md.m = descs[i].m; md.n = descs[i].n; md.r = descs[i].r; md.ldn = z.ldn;
+            md.l = z.l; md.ldk = z.ldk; md.ldr = z.ldr; md.roct = z.roct;
+            md.ld_w = descs[i].ld_w; md.ld_g = descs[i].ld_g;
+            md.slot_elems = (long long)md.r * z.ldn;
+            md.P = (float*)bufs[i].buf[NG_BUF_P];
+            md.M = (float*)bufs[i].buf[NG_BUF_M];
+            md.V = (float*)bufs[i].buf[NG_BUF_V];
+            md.H = (float*)bufs[i].buf[NG_BUF_H];
+            char* kb = (char*)bufs[i].buf[NG_BUF_K];
+            md.K = (double*)(kb + z.k_gram_off);
+            md.w64 = (double*)(kb + z.k_w64_off);
+            md.w32 = (float*)(kb + z.k_w32_off);
+            md.N = bufs[i].buf[NG_BUF_N];
+            if (hp->grad_dtype == NG_BF16) {
+                char* ab = (char*)bufs[i].buf[NG_BUF_AUX];
+                md.Pb = (bf16_t*)(ab + z.aux_pb_off);
+                md.PbT = (bf16_t*)(ab + z.aux_pbt_off);
+            }
+            md.dot_parts = (double*)(ws + off); off += z.ws_parts;
+            md.Ya = (float*)(ws + off); off += z.ws_y;
+            md.Yb = (float*)(ws + off); off += z.ws_y;
+            md.Yc = (float*)(ws + off); off += z.ws_y;
+            md.Bm = (float*)(ws + off); off += z.ws_bm;
+            md.T = (double*)(ws + off); off += z.ws_t;
+            md.Linv = (float*)(ws + off); off += z.ws_linv;
+            md.ritz = (double*)(ws + off); off += z.ws_ritz;
+            md.order = (int*)(ws + off); off += z.ws_order;
+            md.jflag = (int*)(ws + off); off += z.ws_flag;
+            md.lp = z.lp; md.jb = z.jb;
+            const long long total4 = md.slot_elems / 4;
+            long long iters = (total4 + 256LL * kDotPartsMax - 1) / (256LL * kDotPartsMax);
+            if (iters < 1) iters = 1;
+            md.dot_iters = (int)iters;
+            md.dot_nparts = (int)((total4 + iters * 256 - 1) / (iters * 256));
+            if (hp->s > 0)
+                for (int p = 0; p < md.dot_nparts; ++p) dots.push_back(TileRef{i, p, 0, 0});
+            if (md.m > st->max_m) st->max_m = md.m;
+            if (md.n > st->max_n) st->max_n = md.n;
+            if (md.r > st->max_r) st->max_r = md.r;
+            if (md.l > st->max_l) st->max_l = md.l;
+            if (md.lp > st->max_lp) st->max_lp = md.lp;
+            const int rows = md.m > md.n ? md.m : md.n;
+            if (rows > st->max_rows) st->max_rows = rows;
+            const int pairs = md.lp / md.jb / 2;
+            if (pairs > st->max_jpairs) st->max_jpairs = pairs;
+            const size_t jl = (size_t)2 * md.jb * md.lp * sizeof(double);
+            if (jl > st->jacobi_lds) st->jacobi_lds = jl;
+            for (int op = 0; op < OP_COUNT; ++op) {
+                int M, N;
+                gemm_f32_dims(op, md, &M, &N);
+                if (ceil_div(M, 64) > st->max_ti[op]) st->max_ti[op] = ceil_div(M, 64);
+                if (ceil_div(N, 64) > st->max_tj[op]) st->max_tj[op] = ceil_div(N, 64);
+            }
+            (void)s_eff;
+        }
+        st->n_dots = (int)dots.size();
+
+        // upload the tables (synchronous copies; init is not a hot path)
+        hipError_t e = hipSuccess;
+        int zero = 0;
+        e = hipMemcpy(st->d_status, &zero, sizeof(int), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(st->d_mats, st->mats.data(), sizeof(MatDev) * n_mats, hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pl.proj.empty())
+            e = hipMemcpy(st->d_proj, pl.proj.data(), sizeof(TileRef) * pl.proj.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pl.upd.empty())
+            e = hipMemcpy(st->d_upd, pl.upd.data(), sizeof(TileRef) * pl.upd.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !dots.empty())
+            e = hipMemcpy(st->d_dots, dots.data(), sizeof(TileRef) * dots.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pl.patches.empty())
+            e = hipMemcpy(st->d_patches, pl.patches.data(), sizeof(TileRef) * pl.patches.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess && !(flags & NG_INIT_NO_CLEAR)) {
+            delete st;
+            return NG_ERR_HIP;
+        }
+        // With NG_INIT_NO_CLEAR a failed table upload is tolerated so that the host-side logic
+        // can be exercised without a device; every later launch then reports NG_ERR_HIP.
+        if (e != hipSuccess) (void)hipGetLastError();
+
+        if (!(flags & NG_INIT_NO_CLEAR)) {
+            for (int i = 0; i < n_mats; ++i) {
+                const int ids[5] = {NG_BUF_M, NG_BUF_V, NG_BUF_H, NG_BUF_K, NG_BUF_N};
+                for (int b = 0; b < 5; ++b) {
+                    if (launch_fill_zero(bufs[i].buf[ids[b]], pl.sz[i].bytes[ids[b]], stream) != hipSuccess) {
+                        delete st;
+                        return NG_ERR_HIP;
+                    }
+                }
+            }
+        }
+    } catch (...) {
+        delete st;
+        return NG_ERR_INVALID_ARG;
+    }
+    *out = st;
+    return NG_OK;
+}
+
+int ng_commit_projector(ng_state* st, int clear, ng_stream stream_) {
+    if (!st) return NG_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    int rc = finish_projector(st, clear != 0, stream);
+    if (rc != NG_OK) return rc;
+    st->projector_valid = true;
+    if (clear) {
+        for (int i = 0; i < st->n_mats; ++i) {
+            st->head[i] = 0;
+            st->count[i] = 0;
+            st->n_refresh[i] += 1;
+        }
+    }
+    return NG_OK;
+}
+
+int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream stream_) {
+    if (!st || !grads) return NG_ERR_INVALID_ARG;
+    for (int i = 0; i < st->n_mats; ++i)
+        if (!grads[i]) return NG_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const StepScalars sc = make_scalars(st, 0.f);
+    int rc;
+    if ((rc = upload_dyn(st, grads, nullptr, false, stream)) != NG_OK) return rc;
+
+    // randomised subspace iteration: Ya = orth(G Omega); q times { Yb = orth(G^T Ya); Ya = orth(G Yb) }
+    NG_HIP(launch_fill_gaussian(st->d_mats, st->n_mats, st->max_n, st->hp.seed,
+                                (unsigned long long)st->n_refresh[0], stream));
+    if ((rc = gemm(st, OP_G_B2A, stream, sc)) != NG_OK) return rc;
+    if ((rc = orthonormalise(st, true, stream, sc)) != NG_OK) return rc;
+    for (int it = 0; it < st->hp.refresh_power_iters; ++it) {
+        if ((rc = gemm(st, OP_GT_A2B, stream, sc)) != NG_OK) return rc;
+        if ((rc = orthonormalise(st, false, stream, sc)) != NG_OK) return rc;
+        if ((rc = gemm(st, OP_G_B2A, stream, sc)) != NG_OK) return rc;
+        if ((rc = orthonormalise(st, true, stream, sc)) != NG_OK) return rc;
+    }
+    // Rayleigh-Ritz: B = Q^T G, T = B B^T = U diag(ritz^2) U^T, P = Q U[:, top r]
+    if ((rc = gemm(st, OP_QT_G, stream, sc)) != NG_OK) return rc;
+    if ((rc = gemm(st, OP_B_BT, stream, sc)) != NG_OK) return rc;
+    NG_HIP(launch_jacobi_prepare(st->d_mats, st->n_mats, stream));
+    for (int sw = 0; sw < st->hp.refresh_sweeps; ++sw) {
+        const int max_rounds = 2 * st->max_jpairs - 1;
+        for (int round = 0; round < (max_rounds > 0 ? max_rounds : 1); ++round)
+            NG_HIP(launch_jacobi_round(st->d_mats, st->n_mats, st->max_jpairs, round, st->jacobi_lds, stream));
+        NG_HIP(launch_jacobi_sweep_end(st->d_mats, st->n_mats, stream));
+    }
+    NG_HIP(launch_jacobi_finish(st->d_mats, st->n_mats, st->d_status, stream));
+    if ((rc = gemm(st, OP_ROTATE, stream, sc)) != NG_OK) return rc;
+    // one CholeskyQR pass on P (m x r) restores orthonormality to rounding level, then fix signs
+    if ((rc = gemm(st, OP_GRAM_P, stream, sc)) != NG_OK) return rc;
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 1, 0.0, st->d_status, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 1, stream));
+    if ((rc = gemm(st, OP_APPLY_P2A, stream, sc)) != NG_OK) return rc;
+    NG_HIP(launch_sign_fix(st->d_mats, st->n_mats, st->max_r, stream));
+
+    if ((rc = finish_projector(st, true, stream)) != NG_OK) return rc;
+    st->projector_valid = true;
+    for (int i = 0; i < st->n_mats; ++i) {
+        st->head[i] = 0;
+        st->count[i] = 0;
+        st->n_refresh[i] += 1;
+    }
+    return NG_OK;
+}
+
+int ng_step(ng_state* st, const void* const* grads, void* const* weights, float lr, ng_stream stream_) {
+    if (!st || !grads || !weights) return NG_ERR_INVALID_ARG;
+    if (!isfinite(lr)) return NG_ERR_HPARAM;
+    for (int i = 0; i < st->n_mats; ++i)
+        if (!grads[i] || !weights[i]) return NG_ERR_INVALID_ARG;
+    if (!st->projector_valid) return NG_ERR_NO_PROJECTOR;
+    hipStream_t stream = (hipStream_t)stream_;
+    const StepScalars sc = make_scalars(st, lr);
+    const bool bf = st->hp.grad_dtype == NG_BF16;
+    const bool prof = st->profiling && st->ev_created;
+    int slot = 0;
+    if (prof) {
+        drain_events(st, false);
+        slot = st->ev_head;
+    }
+    int rc;
+    if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
+    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), stream));
+    else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
+    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
+    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, st->n_mats, sc, st->d_status, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_ADAM], stream));
+    NG_HIP(launch_transform_adam(st->d_mats, st->d_dyn, st->d_patches, (int)st->plan.patches.size(), sc,
+                                 st->hp.grad_dtype, st->d_status, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
+    if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc, stream));
+    else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc)) != NG_OK) return rc;
+
+    if (prof) {
+        NG_HIP(hipEventRecord(st->ev[slot][NG_NPHASE], stream));
+        st->ev_head = (st->ev_head + 1) % kProfRing;
+        st->ev_pending += 1;
+    }
+
+    const int s = st->hp.s;
+    for (int i = 0; i < st->n_mats; ++i) {
+        st->t[i] += 1;
+        if (s > 0) {
+            st->head[i] = (st->head[i] + 1) % s;
+            if (st->count[i] < s) st->count[i] += 1;
+        }
+    }
+    return NG_OK;
+}
+
+int ng_get_counters(const ng_state* st, int mat, int64_t* t, int32_t* head, int32_t* count, int64_t* n_refresh) {
+    if (!st || mat < 0 || mat >= st->n_mats) return NG_ERR_INVALID_ARG;
+    if (t) *t = st->t[mat];
+    if (head) *head = st->head[mat];
+    if (count) *count = st->count[mat];
+    if (n_refresh) *n_refresh = st->n_refresh[mat];
+    return NG_OK;
+}
+
+int ng_set_counters(ng_state* st, int mat, int64_t t, int32_t head, int32_t count, int64_t n_refresh) {
+    if (!st || mat < 0 || mat >= st->n_mats) return NG_ERR_INVALID_ARG;
+    const int s = st->hp.s;
+    if (t < 0 || n_refresh < 0) return NG_ERR_INVALID_ARG;
+    if (head < 0 || head >= (s > 0 ? s : 1)) return NG_ERR_INVALID_ARG;
+    if (count < 0 || count > s) return NG_ERR_INVALID_ARG;
+    st->t[mat] = t;
+    st->head[mat] = head;
+    st->count[mat] = count;
+    st->n_refresh[mat] = n_refresh;
+    return NG_OK;
+}
+
+int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out) {
+    if (!st || !out || mat < 0 || mat >= st->n_mats) return NG_ERR_INVALID_ARG;
+    const Sizes& z = st->plan.sz[mat];
+    out->ldn = z.ldn;
+    out->l = z.l;
+    out->slot_elems = (int64_t)st->descs[mat].r * z.ldn;
+    out->k_gram_off = (int64_t)z.k_gram_off;
+    out->k_w64_off = (int64_t)z.k_w64_off;
+    out->k_w32_off = (int64_t)z.k_w32_off;
+    return NG_OK;
+}
+
+int ng_get_status(ng_state* st, ng_stream stream_) {
+    if (!st) return NG_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    NG_HIP(hipStreamSynchronize(stream));
+    int flag = 0;
+    NG_HIP(hipMemcpy(&flag, st->d_status, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag != 0) {
+        int zero = 0;
+        NG_HIP(hipMemcpy(st->d_status, &zero, sizeof(int), hipMemcpyHostToDevice));
+        return NG_ERR_NUMERIC;
+    }
+    return NG_OK;
+}
+
+int ng_set_profiling(ng_state* st, int enabled) {
+    if (!st) return NG_ERR_INVALID_ARG;
+    if (enabled && !st->ev_created) {
+        for (int i = 0; i < kProfRing; ++i)
+            for (int p = 0; p <= NG_NPHASE; ++p)
+                if (hipEventCreate(&st->ev[i][p]) != hipSuccess) return NG_ERR_HIP;
+        st->ev_created = true;
+    }
+    if (!enabled) drain_events(st, true);
+    st->profiling = enabled != 0;
+    return NG_OK;
+}
+
+int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset) {
+    if (!st || !ms || !steps) return NG_ERR_INVALID_ARG;
+    drain_events(st, true);
+    for (int p = 0; p < NG_NPHASE; ++p) ms[p] = st->phase_ms[p];
+    *steps = st->phase_steps;
+    if (reset) {
+        memset(st->phase_ms, 0, sizeof(st->phase_ms));
+        st->phase_steps = 0;
+    }
+    return NG_OK;
+}
+
+const char* ng_strerror(int code) {
+    switch (code) {
+        case NG_OK: return "ok";
+        case NG_ERR_INVALID_ARG: return "invalid argument";
+        case NG_ERR_SHAPE: return "invalid shape (m, n, r, ld or s)";
+        case NG_ERR_DTYPE: return "unknown dtype or mode";
+        case NG_ERR_HPARAM: return "hyper-parameter out of range";
+        case NG_ERR_NO_PROJECTOR: return "no projector: call ng_refresh_projector or ng_commit_projector first";
+        case NG_ERR_HIP: return "HIP runtime error";
+        case NG_ERR_NUMERIC: return "numeric failure on device (non-positive pivot or non-finite value)";
+        case NG_ERR_WORKSPACE: return "workspace too small or misaligned";
+        default: return "unknown error code";
+    }
+}
+
+void ng_destroy(ng_state* st) {
+    if (!st) return;
+    if (st->ev_created) {
+        for (int i = 0; i < kProfRing; ++i)
+            for (int p = 0; p <= NG_NPHASE; ++p) (void)hipEventDestroy(st->ev[i][p]);
+    }
+    delete st;
+}
+
+}  // extern "C"

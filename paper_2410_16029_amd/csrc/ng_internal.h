@@ -1,0 +1,146 @@
+// Internal declarations shared by the host scheduler and the kernel files.
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ng.h"
+
+namespace ng {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+
+constexpr int kMaxS = 64;        // history slots
+constexpr int kDotPartsMax = 64; // per-matrix partial sums of the Gram-row reduction
+constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (by kernel argument)
+constexpr int kJacobiLdsBudget = 147456;   // bytes of LDS the blocked Jacobi may use for its two row blocks
+
+// Static per-matrix description, lives in the workspace (device) and in the handle (host).
+struct MatDev {
+    int m, n, r, ldn;
+    int l;            // refresh sketch width
+    int ldk;          // row length of PbT (m rounded up to 8)
+    int ldr;          // row length of Pb (r rounded up to 8)
+    int roct;         // ceil(r/8): octets of N in the bf16 layout
+    long long ld_w, ld_g;
+    long long slot_elems;   // r * ldn
+    float* P;
+    float* M;
+    float* V;
+    float* H;
+    double* K;        // s*s Gram
+    double* w64;      // s
+    float* w32;       // s
+    void* N;
+    bf16_t* Pb;       // [m][ldr]   bf16 copy of P      (A operand of the update GEMM)
+    bf16_t* PbT;      // [r][ldk]   bf16 copy of P^T    (A operand of the projection GEMM)
+    double* dot_parts;   // [kDotPartsMax][s]
+    int dot_nparts;      // workgroups of the Gram-row reduction for this matrix
+    int dot_iters;       // grid-stride iterations per workgroup
+    // refresh scratch (all in the workspace)
+    float* Ya;        // [max(m,n)][l]
+    float* Yb;        // [max(m,n)][l]
+    float* Yc;        // [max(m,n)][l]
+    float* Bm;        // [l][ldn]   B = Q^T G; later the l x r rotation
+    double* T;        // [lp][lp]   Gram / Cholesky factor / Rayleigh-Ritz matrix
+    float* Linv;      // [lp][lp]   inverse Cholesky factor (float)
+    double* ritz;     // [lp]
+    int* order;       // [lp]
+    int* jflag;       // [0] rotations this sweep, [1] converged
+    int lp, jb;       // padded size and row-block size of the blocked Jacobi
+};
+
+// Per-step values: uploaded into the workspace by a tiny kernel that receives them by value.
+struct MatDyn {
+    const void* g;
+    void* w;
+    int head;      // slot written by this step
+    int count;     // valid slots after the push
+    float bc1, bc2;   // Adam bias corrections 1/(1-beta1^t), 1/sqrt(1-beta2^t)
+};
+
+struct DynChunk {
+    MatDyn e[kDynChunk];
+};
+
+struct StepScalars {
+    float lambda;
+    float beta1, beta2, eps;
+    float lr_scale, lr_wd;
+    int adam_mode;
+    int s;               // slots read by the kernels (>= 1; the s = 0 case uses one scratch slot)
+    int use_fisher;      // 0 when hparams.s == 0
+};
+
+// Grouped-launch work item: which matrix and which tile / part of it a workgroup takes.
+// mat < 0 marks a padding entry (the workgroup exits).
+struct TileRef {
+    int mat;
+    int ti, tj;
+    int pad;
+};
+
+// ---------------------------------------------------------------- launchers
+// Every launcher enqueues on `stream` and returns hipGetLastError().
+
+hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, hipStream_t stream);
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);   // bytes % 4 == 0
+
+// fp32 MFMA grouped GEMM with selectable operands (k_gemm_f32.hip)
+enum GemmOp {
+    OP_PROJECT_F32 = 0,   // R(slot head) = P^T G                     (step, NG_F32)
+    OP_UPDATE_F32,        // W -= lr*(scale * P N + wd W)             (step, NG_F32)
+    OP_G_B2A,             // Ya = G Yb     (m x l)
+    OP_GT_A2B,            // Yb = G^T Ya   (n x l)
+    OP_GRAM_A,            // T = Ya^T Ya   (rows m) -> double
+    OP_GRAM_B,            // T = Yb^T Yb   (rows n)
+    OP_GRAM_CA,           // T = Yc^T Yc   (rows m)
+    OP_GRAM_CB,           // T = Yc^T Yc   (rows n)
+    OP_APPLY_A2C,         // Yc = Ya Linv^T (rows m)
+    OP_APPLY_B2C,         // Yc = Yb Linv^T (rows n)
+    OP_APPLY_C2A,         // Ya = Yc Linv^T (rows m)
+    OP_APPLY_C2B,         // Yb = Yc Linv^T (rows n)
+    OP_QT_G,              // Bm = Ya^T G   (l x ldn)
+    OP_B_BT,              // T = Bm Bm^T   (l x l) -> double
+    OP_ROTATE,            // P = Ya * Urot (m x r), Urot (l x r floats) staged in Bm
+    OP_GRAM_P,            // T = P^T P (r x r) -> double
+    OP_APPLY_P2A,         // Ya[m][r] = P Linv^T
+    OP_COUNT
+};
+void gemm_f32_dims(int op, const MatDev& md, int* M, int* N);
+hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats,
+                           int max_tiles_i, int max_tiles_j, int grad_dtype, StepScalars sc,
+                           hipStream_t stream);
+
+// bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
+void bf16_tile_shape(int* bm, int* bn);
+hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
+                               hipStream_t stream);
+hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
+                              StepScalars sc, hipStream_t stream);
+
+// Gram row, solve, fused transform + Adam (k_elementwise.hip)
+hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,
+                           int s, hipStream_t stream);
+hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int n_mats, StepScalars sc, int* status,
+                        hipStream_t stream);
+hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,
+                                 StepScalars sc, int grad_dtype, int* status, hipStream_t stream);
+hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, int max_r, hipStream_t stream);
+
+// refresh helpers (k_refresh.hip)
+hipError_t launch_fill_gaussian(const MatDev* mats, int n_mats, int max_rows, unsigned long long seed,
+                                unsigned long long call_id, hipStream_t stream);   // fills Yb (n x l)
+// which: 0 -> order l (sketch), 1 -> order r (final P)
+hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shift_rel, int* status,
+                           hipStream_t stream);
+hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, hipStream_t stream);
+hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t stream);
+hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
+                               hipStream_t stream);
+hipError_t launch_jacobi_sweep_end(const MatDev* mats, int n_mats, hipStream_t stream);
+hipError_t launch_jacobi_finish(const MatDev* mats, int n_mats, int* status, hipStream_t stream);
+hipError_t launch_sign_fix(const MatDev* mats, int n_mats, int max_r, hipStream_t stream);
+
+}  // namespace ng

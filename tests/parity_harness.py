@@ -1,0 +1,105 @@
+"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle on
+the same bytes and report per-tensor errors  max|x - x_oracle| / max|x_oracle|."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2410_16029_amd import binding as B
+
+
+def rel_err(x, ref) -> float:
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    denom = np.max(np.abs(ref))
+    if denom == 0.0:
+        return float(np.max(np.abs(x)))
+    return float(np.max(np.abs(x - ref)) / denom)
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def oracle_hparams(ls: B.LayerSet) -> oracle.HParams:
+    hp = ls.hp
+    return oracle.HParams(s=hp.s, lam=float(hp.lambda_), beta1=float(hp.beta1), beta2=float(hp.beta2),
+                          eps=float(hp.eps), scale=float(hp.scale), weight_decay=float(hp.weight_decay),
+                          adam_mode="standard" if hp.adam_mode == B.NG_ADAM_STANDARD else "printed",
+                          weight_dtype=ls.dtype)
+
+
+class Lockstep:
+    """GPU layer set + one oracle state per checked matrix, advanced together (free-running)."""
+
+    def __init__(self, ls: B.LayerSet, check=None):
+        self.ls = ls
+        self.check = list(range(len(ls.shapes))) if check is None else list(check)
+        self.ohp = oracle_hparams(ls)
+        self.states = {}
+        for i in self.check:
+            m, n = ls.shapes[i]
+            self.states[i] = oracle.init_state(m, n, ls.descs[i].r, ls.hp.s)
+        self.Wo = {}
+
+    def adopt_gpu_projector(self):
+        """The oracle steps with the very projector the GPU holds (its basis is not unique)."""
+        torch.cuda.synchronize()
+        for i in self.check:
+            self.states[i].P = to_f64(self.ls.P(i))
+
+    def set_weights(self, weights):
+        for i in self.check:
+            self.Wo[i] = to_f64(weights[i])
+
+    def refresh(self, grads):
+        self.ls.refresh(grads)
+        for i in self.check:
+            st = self.states[i]
+            st.H[...] = 0.0
+            st.head = 0
+            st.count = 0
+            st.n_refresh += 1
+        self.adopt_gpu_projector()
+
+    def step(self, grads, weights, lr):
+        """One step on both sides.  Returns {matrix: {tensor name: rel err}}."""
+        ls = self.ls
+        slot = {i: ls.counters(i)[1] for i in self.check}
+        ls.step(grads, weights, lr)
+        torch.cuda.synchronize()
+        out = {}
+        for i in self.check:
+            st = self.states[i]
+            n = ls.shapes[i][1]
+            self.Wo[i] = oracle.step(st, to_f64(grads[i]), self.Wo[i], lr, self.ohp)
+            tr = st.trace
+            e = {}
+            H = ls.H(i)
+            e["R"] = rel_err(to_f64(H[slot[i] if ls.hp.s > 0 else 0][:, :n]), tr["R"])
+            if ls.hp.s > 0:
+                assert tr["slot"] == slot[i]
+                e["K_row"] = rel_err(to_f64(ls.K(i)[slot[i]]), tr["K"][slot[i]])
+                e["K"] = rel_err(to_f64(ls.K(i)), tr["K"])
+                # w = (lambda I + K/s)^{-1} e_slot, from the oracle's own K
+                s = ls.hp.s
+                w_ref = np.linalg.solve(self.ohp.lam * np.eye(s) + tr["K"] / s, np.eye(s)[slot[i]])
+                e["w"] = rel_err(to_f64(ls.w(i)), w_ref)
+                e["pad"] = float(H[:, :, n:].abs().max().item()) if H.shape[2] > n else 0.0
+            e["M"] = rel_err(to_f64(ls.M(i)[:, :n]), st.M)
+            e["V"] = rel_err(to_f64(ls.V(i)[:, :n]), st.V)
+            e["N"] = rel_err(to_f64(ls.N(i)), tr["N"])
+            Wg = to_f64(weights[i])
+            e["W"] = rel_err(Wg, self.Wo[i])
+            if ls.dtype == "bf16":
+                e["W_mismatch_frac"] = float(np.mean(Wg != self.Wo[i]))
+            t, head, count, nref = ls.counters(i)
+            assert (t, head, count, nref) == (st.t, st.head if ls.hp.s > 0 else 0, st.count, st.n_refresh), \
+                ((t, head, count, nref), (st.t, st.head, st.count, st.n_refresh))
+            out[i] = e
+        return out
+
+
+def worst(errs_list, key):
+    return max(e[key] for step in errs_list for e in step.values() if key in e)

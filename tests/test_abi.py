@@ -1,0 +1,152 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/ng.h
+declares, sizes and argument validation are right, and the host-side integer
+bookkeeping behaves (no kernel is run here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2410_16029_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "ng.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(ng_[a-z_]+)\s*\(", text))
+    assert {"ng_init_state", "ng_step", "ng_refresh_projector", "ng_query_sizes", "ng_commit_projector",
+            "ng_get_counters", "ng_set_counters", "ng_get_status", "ng_strerror", "ng_destroy"} <= names
+    lib = C.CDLL(B.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_query_sizes_c1_and_bf16_layout():
+    hp = B.ng_default_hparams()
+    assert (hp.s, hp.grad_dtype, hp.adam_mode) == (4, B.NG_F32, B.NG_ADAM_STANDARD)
+    assert abs(hp.lambda_ - 1e-3) < 1e-9 and abs(hp.beta2 - 0.999) < 1e-6
+    descs = B.make_descs([(256, 512)], 32)
+    sizes, ws = B.ng_query_sizes(descs, hp)
+    sz = sizes[0]
+    assert sz[B.NG_BUF_P] == 256 * 32 * 4
+    assert sz[B.NG_BUF_M] == sz[B.NG_BUF_V] == 32 * 512 * 4
+    assert sz[B.NG_BUF_H] == 4 * 32 * 512 * 4
+    assert sz[B.NG_BUF_N] == 32 * 512 * 4
+    assert sz[B.NG_BUF_AUX] == 0
+    assert sz[B.NG_BUF_K] >= 4 * 4 * 8 + 4 * 8 + 4 * 4 and sz[B.NG_BUF_K] % 256 == 0
+    assert ws > 0
+    # bf16, odd n: rows padded to a multiple of 32, N in octets, bf16 copies of P
+    hp.grad_dtype = B.NG_BF16
+    hp.s = 16
+    descs = B.make_descs([(2048, 5461)], 512)
+    sizes, _ = B.ng_query_sizes(descs, hp)
+    ldn = 5472
+    assert sizes[0][B.NG_BUF_M] == 512 * ldn * 4
+    assert sizes[0][B.NG_BUF_H] == 16 * 512 * ldn * 4
+    assert sizes[0][B.NG_BUF_N] == (512 // 8) * ldn * 8 * 2
+    assert sizes[0][B.NG_BUF_AUX] >= 2 * 2048 * 512 * 2
+    # s = 0 keeps one scratch slot for the projected gradient
+    hp.s = 0
+    sizes, _ = B.ng_query_sizes(descs, hp)
+    assert sizes[0][B.NG_BUF_H] == 512 * ldn * 4
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda d, hp: setattr(hp, "lambda_", 0.0), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "lambda_", -1.0), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "beta1", 1.0), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "beta2", -0.1), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "eps", 0.0), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "s", -1), B.NG_ERR_SHAPE),
+    (lambda d, hp: setattr(hp, "s", 65), B.NG_ERR_SHAPE),
+    (lambda d, hp: setattr(hp, "grad_dtype", 7), B.NG_ERR_DTYPE),
+    (lambda d, hp: setattr(hp, "adam_mode", 2), B.NG_ERR_DTYPE),
+    (lambda d, hp: setattr(hp, "refresh_sweeps", 0), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(d[0], "r", 0), B.NG_ERR_SHAPE),
+    (lambda d, hp: setattr(d[0], "r", 300), B.NG_ERR_SHAPE),      # r > min(m, n)
+    (lambda d, hp: setattr(d[0], "m", 0), B.NG_ERR_SHAPE),
+    (lambda d, hp: setattr(d[0], "ld_w", 100), B.NG_ERR_SHAPE),   # ld < n
+    (lambda d, hp: setattr(d[0], "ld_g", 511), B.NG_ERR_SHAPE),
+    (lambda d, hp: setattr(d[0], "reserved", 1), B.NG_ERR_INVALID_ARG),
+])
+def test_argument_validation(mutate, code):
+    hp = B.ng_default_hparams()
+    descs = B.make_descs([(256, 512)], 32)
+    mutate(descs, hp)
+    with pytest.raises(B.NgError) as e:
+        B.ng_query_sizes(descs, hp)
+    assert e.value.code == code
+    assert B.ng_strerror(code) != "unknown error code"
+
+
+def test_null_pointers_rejected():
+    hp = B.ng_default_hparams()
+    descs = B.make_descs([(256, 512)], 32)
+    assert B._lib.ng_query_sizes(None, 1, C.byref(hp), None, None) == B.NG_ERR_INVALID_ARG
+    assert B._lib.ng_query_sizes(descs, 0, C.byref(hp), None, None) == B.NG_ERR_INVALID_ARG
+    assert B._lib.ng_step(None, None, None, 1e-3, None) == B.NG_ERR_INVALID_ARG
+    assert B._lib.ng_get_counters(None, 0, None, None, None, None) == B.NG_ERR_INVALID_ARG
+    B._lib.ng_destroy(None)
+
+
+def _host_only_handle(s=3):
+    """A handle over host memory: legal as long as no kernel runs (NG_INIT_NO_CLEAR)."""
+    return B.LayerSet([(64, 96), (96, 64)], 16, s=s, dtype="f32", device="cpu", no_clear=True)
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="exercises the no-device error path")
+def test_host_bookkeeping_without_device():
+    ls = _host_only_handle()
+    assert ls.counters(0) == (0, 0, 0, 0)
+    g = [torch.zeros(64, 96), torch.zeros(96, 64)]
+    w = [torch.zeros(64, 96), torch.zeros(96, 64)]
+    # no projector yet
+    with pytest.raises(B.NgError) as e:
+        ls.step(g, w, 1e-3)
+    assert e.value.code == B.NG_ERR_NO_PROJECTOR
+    # resume counters, bounds checked
+    B.ng_set_counters(ls.st, 1, 41, 2, 3, 5)
+    assert ls.counters(1) == (41, 2, 3, 5)
+    for bad in [(-1, 0, 0, 0), (0, 3, 0, 0), (0, -1, 0, 0), (0, 0, 4, 0), (0, 0, 0, -1)]:
+        with pytest.raises(B.NgError):
+            B.ng_set_counters(ls.st, 0, *bad)
+    with pytest.raises(B.NgError):
+        B.ng_get_counters(ls.st, 2)
+    # f32 commit without clearing launches nothing: marks the projector valid
+    ls.commit_projector(clear_history=False)
+    before = [ls.counters(i) for i in range(2)]
+    with pytest.raises(B.NgError) as e:
+        ls.step(g, w, 1e-3)             # the first launch fails: no device here
+    assert e.value.code == B.NG_ERR_HIP
+    assert [ls.counters(i) for i in range(2)] == before   # a failed call leaves the counters alone
+    lay = B.ng_get_layout(ls.st, 0)
+    assert lay.ldn == 96 and lay.slot_elems == 16 * 96
+    ls.close()
+
+
+def test_workspace_too_small_and_misaligned():
+    hp = B.ng_default_hparams()
+    descs = B.make_descs([(64, 96)], 16)
+    sizes, ws = B.ng_query_sizes(descs, hp)
+    bufs = (B.ng_matrix_buffers * 1)()
+    keep = []
+    for b in range(B.NG_NBUF):
+        t = torch.zeros(max(sizes[0][b], 16) + 256, dtype=torch.uint8)
+        keep.append(t)
+        bufs[0].buf[b] = (t.data_ptr() + 255) // 256 * 256
+    wsbuf = torch.zeros(ws + 512, dtype=torch.uint8)
+    base = (wsbuf.data_ptr() + 255) // 256 * 256
+    st = C.c_void_p()
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws - 1, B.NG_INIT_NO_CLEAR, None,
+                              C.byref(st))
+    assert rc == B.NG_ERR_WORKSPACE
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base + 8), ws, B.NG_INIT_NO_CLEAR, None,
+                              C.byref(st))
+    assert rc == B.NG_ERR_WORKSPACE
+    bufs[0].buf[B.NG_BUF_M] = None
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws, B.NG_INIT_NO_CLEAR, None,
+                              C.byref(st))
+    assert rc == B.NG_ERR_INVALID_ARG

@@ -41,7 +41,7 @@ def algorithmic_work(cfg, mats):
     return w
 
 
-def cpu_baseline(cfg, ls, grads_pool, weights, budget_s=30.0):
+def cpu_baseline(cfg, ls, grads_pool, weights, per_shape_s=5.0):
     """The float64 oracle timed on the host cores: one matrix of each distinct shape,
     one warm + one timed step each, scaled by the shape's multiplicity."""
     import numpy as np
@@ -59,7 +59,6 @@ def cpu_baseline(cfg, ls, grads_pool, weights, budget_s=30.0):
     hp = oracle_hparams(ls)
     mats = cfg.matrices()
     total = 0.0
-    used = 0.0
     parts = []
     for (m, n, mult) in cfg.distinct_shapes():
         i = mats.index((m, n))
@@ -69,17 +68,20 @@ def cpu_baseline(cfg, ls, grads_pool, weights, budget_s=30.0):
         G0 = to_f64(grads_pool[0][i])
         G1 = to_f64(grads_pool[1 % len(grads_pool)][i])
         W = oracle.step(st, G0, W, cfg.lr, hp)          # warm (allocations, BLAS threads)
-        t0 = time.perf_counter()
-        W = oracle.step(st, G1, W, cfg.lr, hp)
-        dt = time.perf_counter() - t0
-        used += dt
+        reps, spent = 0, 0.0
+        while reps < 2 or (spent < per_shape_s and reps < 50):
+            G = to_f64(grads_pool[(reps + 1) % len(grads_pool)][i])
+            t0 = time.perf_counter()
+            W = oracle.step(st, G, W, cfg.lr, hp)
+            spent += time.perf_counter() - t0
+            reps += 1
+        dt = spent / reps
         total += dt * mult
-        parts.append("%dx%d:%.2fs" % (m, n, dt))
-        if used > budget_s:
-            break
+        parts.append("%dx%d: %d steps, %.3f s/step" % (m, n, reps, dt))
     return {"value": 1.0 / total, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": "1 timed step on 1 matrix of each distinct shape (%s), scaled by multiplicity to the "
-                      "%d-matrix set; numpy float64" % (", ".join(parts), len(mats))}
+            "sample": "1 matrix of each distinct shape stepped for about %.0f s (%s), mean step time scaled by "
+                      "the shape's multiplicity to the %d-matrix set; numpy float64"
+                      % (per_shape_s, "; ".join(parts), len(mats))}
 
 
 def main() -> int:

@@ -7,6 +7,7 @@ It shares no code with the HIP library and never imports it.
 from .natural_galore import (  # noqa: F401
     HParams,
     OracleState,
+    adam_direction,
     adam_moments,
     back_project_update,
     fisher_history_matrix,

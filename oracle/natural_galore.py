@@ -143,19 +143,22 @@ def natural_gradient_transform(H: np.ndarray, R: np.ndarray, lam: float) -> tupl
 # --------------------------------------------------------------------------
 # Sec. 2.2: Adam moments in the r x n space, and the weight update
 # --------------------------------------------------------------------------
+def adam_direction(M, V, t: int, hp: HParams):
+    """Update direction N from the moments after step t (Sec. 2.2, third Adam equation)."""
+    if hp.adam_mode == "standard":
+        m_hat = M / (1.0 - hp.beta1 ** t)
+        v_hat = V / (1.0 - hp.beta2 ** t)
+        return m_hat / (np.sqrt(v_hat) + hp.eps)
+    if hp.adam_mode == "printed":
+        return M / np.sqrt(V + hp.eps)
+    raise ValueError(hp.adam_mode)
+
+
 def adam_moments(M, V, g, t: int, hp: HParams):
     """Moment recursion and update direction N (Sec. 2.2, Adam equations)."""
     M_new = hp.beta1 * M + (1.0 - hp.beta1) * g
     V_new = hp.beta2 * V + (1.0 - hp.beta2) * g * g
-    if hp.adam_mode == "standard":
-        m_hat = M_new / (1.0 - hp.beta1 ** t)
-        v_hat = V_new / (1.0 - hp.beta2 ** t)
-        N = m_hat / (np.sqrt(v_hat) + hp.eps)
-    elif hp.adam_mode == "printed":
-        N = M_new / np.sqrt(V_new + hp.eps)
-    else:
-        raise ValueError(hp.adam_mode)
-    return M_new, V_new, N
+    return M_new, V_new, adam_direction(M_new, V_new, t, hp)
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:

@@ -8,16 +8,22 @@ import torch
 import oracle
 from paper_2410_16029_amd import binding as B
 from paper_2410_16029_amd import workloads
-from parity_harness import Lockstep, rel_err, to_f64, worst
+from parity_harness import Lockstep, rel_err, summarize, to_f64, worst
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 TOL_F32 = 1e-4
 TOL_BF16 = 2e-2
-FLOAT_KEYS = ("R", "K_row", "K", "w", "M", "V", "N", "W")
+FLOAT_KEYS = ("R", "K_row", "K", "w", "M", "V", "N_formula", "W", "dW")
 
 
 def _assert_all(errs, tol, label):
+    print(label, {k: float("%.3g" % v) for k, v in summarize(errs).items()})
+    if any("W_upd_excess" in e for step in errs for e in step.values()):
+        # bf16 weights: the applied update equals the oracle's update of the GPU's own N up to
+        # one bf16 rounding step (+ the GEMM tolerance), and differs at all in few elements
+        assert worst(errs, "W_upd_excess") <= 1.0, label
+        assert worst(errs, "W_mismatch_frac") <= 0.05, label
     for k in FLOAT_KEYS:
         vals = [e[k] for step in errs for e in step.values() if k in e]
         if vals:
@@ -34,7 +40,7 @@ def test_c1_free_running_10_steps_with_gpu_refresh():
     stream = workloads.NumpyGradientStream(m, n, cfg.k, cfg.noise, cfg.seed)
     W = torch.from_numpy(workloads.numpy_weight(m, n, cfg.seed).astype(np.float32)).to(DEV)
     ls = B.LayerSet([(m, n)], cfg.r, s=cfg.s, lam=cfg.lam, dtype="f32", device=DEV)
-    lk = Lockstep(ls)
+    lk = Lockstep(ls, tol=TOL_F32)
     lk.set_weights([W])
     errs = []
     for step in range(10):
@@ -54,7 +60,7 @@ def test_f32_step_with_committed_oracle_projector_and_options():
     stream = workloads.NumpyGradientStream(m, n, 8, 0.02, seed=5)
     G0 = stream.next().astype(np.float32)
     ls = B.LayerSet([(m, n)], r, s=s, lam=1e-2, scale=0.25, weight_decay=0.05, dtype="f32", device=DEV)
-    lk = Lockstep(ls)
+    lk = Lockstep(ls, tol=TOL_F32)
     P = oracle.top_r_left_singular_vectors(G0.astype(np.float64), r)
     ls.P(0).copy_(torch.from_numpy(P.astype(np.float32)))
     ls.commit_projector(clear_history=True)
@@ -76,7 +82,7 @@ def test_f32_s0_is_galore_adam_and_printed_adam_mode():
     for s, mode in ((0, "standard"), (2, "printed")):
         stream = workloads.NumpyGradientStream(m, n, 4, 0.01, seed=9)
         ls = B.LayerSet([(m, n)], r, s=s, dtype="f32", adam_mode=mode, device=DEV)
-        lk = Lockstep(ls)
+        lk = Lockstep(ls, tol=TOL_F32)
         W = torch.from_numpy(workloads.numpy_weight(m, n, 9).astype(np.float32)).to(DEV)
         lk.set_weights([W])
         errs = []
@@ -95,7 +101,7 @@ def test_many_small_matrices_in_one_launch():
     stream = workloads.TorchGradientStream(shapes, 8, 0.01, 17, "f32", DEV)
     W = workloads.torch_weights(shapes, 17, "f32", DEV)
     ls = B.LayerSet(shapes, 16, s=2, dtype="f32", device=DEV)
-    lk = Lockstep(ls, check=[0, 69, 70, 95, 96, 97, 129])
+    lk = Lockstep(ls, check=[0, 69, 70, 95, 96, 97, 129], tol=TOL_F32)
     lk.set_weights(W)
     errs = []
     for step in range(3):
@@ -115,7 +121,7 @@ def _bf16_run(shapes, r, s, k, steps, seed, check=None, collinear=False, lr=1e-3
     stream = workloads.TorchGradientStream(shapes, k, 0.01, seed, "bf16", DEV, collinear=collinear)
     W = workloads.torch_weights(shapes, seed, "bf16", DEV)
     ls = B.LayerSet(shapes, r, s=s, dtype="bf16", device=DEV)
-    lk = Lockstep(ls, check=check)
+    lk = Lockstep(ls, check=check, tol=TOL_BF16)
     lk.set_weights(W)
     errs = []
     for step in range(steps):
@@ -132,8 +138,6 @@ def test_bf16_ragged_shapes_free_running():
     # several tiles, odd n (unaligned rows), K tails, ring wrap-around (steps > s)
     ls, errs = _bf16_run(BF16_SHAPES, 64, 4, 16, 7, seed=23)
     _assert_all(errs, TOL_BF16, "bf16 ragged")
-    # the bf16 weight may differ from the oracle's by one rounding step in a few places only
-    assert worst(errs, "W_mismatch_frac") < 0.2
 
 
 def test_bf16_c2_shapes_one_block():
@@ -155,8 +159,9 @@ def test_bf16_collinear_history_stays_finite_and_close():
     # nearly collinear history (fixed B): an ill-conditioned s x s system.  Not a
     # tolerance case of the benchmark; the solve must stay finite and close.
     ls, errs = _bf16_run([(256, 384)], 32, 4, 8, 6, seed=31, collinear=True)
-    assert worst(errs, "N") < 0.25
+    print("collinear", {k: float("%.3g" % v) for k, v in summarize(errs).items()})
     assert worst(errs, "K") < TOL_BF16
+    assert worst(errs, "M") < 0.25 and worst(errs, "W") < TOL_BF16
 
 
 # ----------------------------------------------------------------------------- refresh invariants

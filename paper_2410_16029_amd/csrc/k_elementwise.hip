@@ -13,6 +13,12 @@
 
 namespace ng {
 
+// Pointers read out of the per-matrix table are cast to the global address space so that the
+// streaming kernels use global_load / global_store instead of flat accesses.
+#define NG_AS1 __attribute__((address_space(1)))
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
 // ------------------------------------------------------------------ helpers
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
     unsigned int u = __float_as_uint(x);
@@ -73,25 +79,30 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
     const long long q0 = (long long)c.ti * span;
     long long q1 = q0 + span;
     if (q1 > total4) q1 = total4;
-    const float4* __restrict__ R = reinterpret_cast<const float4*>(md.H + (long long)head * md.slot_elems);
-    const float4* __restrict__ H = reinterpret_cast<const float4*>(md.H);
+    const NG_AS1 f32x4_t* __restrict__ R = (const NG_AS1 f32x4_t*)(md.H + (long long)head * md.slot_elems);
+    const NG_AS1 f32x4_t* __restrict__ H = (const NG_AS1 f32x4_t*)md.H;
 
     double acc[SMAX];
 #pragma unroll
     for (int j = 0; j < SMAX; ++j) acc[j] = 0.0;
 
+    // Branch-free inner loop: a slot index beyond s is clamped to s-1 (its sum is never
+    // written out), so all SMAX loads of one position are issued back to back.
+    long long slot_off[SMAX];
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) slot_off[j] = (long long)(j < s ? j : s - 1) * total4;
     for (long long q = q0 + threadIdx.x; q < q1; q += 256) {
-        const float4 rv = R[q];
+        const f32x4_t rv = R[q];
+        f32x4_t hv[SMAX];
+#pragma unroll
+        for (int j = 0; j < SMAX; ++j) hv[j] = H[slot_off[j] + q];
 #pragma unroll
         for (int j = 0; j < SMAX; ++j) {
-            if (j < s) {
-                const float4 h = H[(long long)j * total4 + q];
-                float p = h.x * rv.x;
-                p = fmaf(h.y, rv.y, p);
-                p = fmaf(h.z, rv.z, p);
-                p = fmaf(h.w, rv.w, p);
-                acc[j] += (double)p;
-            }
+            float p = hv[j].x * rv.x;
+            p = fmaf(hv[j].y, rv.y, p);
+            p = fmaf(hv[j].z, rv.z, p);
+            p = fmaf(hv[j].w, rv.w, p);
+            acc[j] += (double)p;
         }
     }
 
@@ -105,7 +116,7 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
     __syncthreads();
     if ((int)threadIdx.x < s) {
         double v = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
-        md.dot_parts[(long long)c.ti * s + threadIdx.x] = v;
+        ((NG_AS1 double*)md.dot_parts)[(long long)c.ti * s + threadIdx.x] = v;
     }
 }
 
@@ -113,11 +124,20 @@ hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef*
                            hipStream_t stream) {
     if (n_chunks == 0) return hipSuccess;
     dim3 g(n_chunks), b(256);
-    if (s <= 4) hipLaunchKernelGGL(k_gram_row<4>, g, b, 0, stream, mats, dyn, chunks, s);
-    else if (s <= 8) hipLaunchKernelGGL(k_gram_row<8>, g, b, 0, stream, mats, dyn, chunks, s);
-    else if (s <= 16) hipLaunchKernelGGL(k_gram_row<16>, g, b, 0, stream, mats, dyn, chunks, s);
-    else if (s <= 32) hipLaunchKernelGGL(k_gram_row<32>, g, b, 0, stream, mats, dyn, chunks, s);
-    else hipLaunchKernelGGL(k_gram_row<64>, g, b, 0, stream, mats, dyn, chunks, s);
+#define NG_GRAM_CASE(S) hipLaunchKernelGGL(k_gram_row<S>, g, b, 0, stream, mats, dyn, chunks, s)
+    if (s <= 1) NG_GRAM_CASE(1);
+    else if (s <= 2) NG_GRAM_CASE(2);
+    else if (s <= 3) NG_GRAM_CASE(3);
+    else if (s <= 4) NG_GRAM_CASE(4);
+    else if (s <= 6) NG_GRAM_CASE(6);
+    else if (s <= 8) NG_GRAM_CASE(8);
+    else if (s <= 12) NG_GRAM_CASE(12);
+    else if (s <= 16) NG_GRAM_CASE(16);
+    else if (s <= 24) NG_GRAM_CASE(24);
+    else if (s <= 32) NG_GRAM_CASE(32);
+    else if (s <= 48) NG_GRAM_CASE(48);
+    else NG_GRAM_CASE(64);
+#undef NG_GRAM_CASE
     return hipGetLastError();
 }
 
@@ -222,101 +242,113 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
                                                         int* status) {
     const TileRef pr = patches[blockIdx.x];
     const MatDev& md = mats[pr.mat];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int row0 = pr.ti * 32 + wv * 8;
     const int col0 = pr.tj * 256 + lane * 4;
     const int ldn = md.ldn, r = md.r;
     if (row0 >= r || col0 >= ldn) return;
     const int nrow = (r - row0 < 8) ? (r - row0) : 8;
     const long long base = (long long)row0 * ldn + col0;
-
-    float4 g[8];
+    // Branch-free loads: a row beyond nrow re-reads row nrow-1 and its result is dropped.
+    long long rowoff[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) g[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e = 0; e < 8; ++e) rowoff[e] = (long long)(e < nrow ? e : nrow - 1) * ldn;
+
+    f32x4_t g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     const int s = sc.s;
+    const NG_AS1 float* __restrict__ Hb = (const NG_AS1 float*)md.H + base;
     if (sc.use_fisher) {
-        const float* __restrict__ w = md.w32;
+        const NG_AS1 float* __restrict__ w = (const NG_AS1 float*)md.w32;
         for (int j = 0; j < s; ++j) {
             const float wj = w[j];
-            const float* __restrict__ Hj = md.H + (long long)j * md.slot_elems + base;
+            const NG_AS1 float* __restrict__ Hj = Hb + (long long)j * md.slot_elems;
+            f32x4_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = *(const NG_AS1 f32x4_t*)(Hj + rowoff[e]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                if (e < nrow) {
-                    const float4 h = *reinterpret_cast<const float4*>(Hj + (long long)e * ldn);
-                    g[e].x = fmaf(wj, h.x, g[e].x);
-                    g[e].y = fmaf(wj, h.y, g[e].y);
-                    g[e].z = fmaf(wj, h.z, g[e].z);
-                    g[e].w = fmaf(wj, h.w, g[e].w);
-                }
+                g[e].x = fmaf(wj, h[e].x, g[e].x);
+                g[e].y = fmaf(wj, h[e].y, g[e].y);
+                g[e].z = fmaf(wj, h[e].z, g[e].z);
+                g[e].w = fmaf(wj, h[e].w, g[e].w);
             }
         }
     } else {
-        const float* __restrict__ H0 = md.H + base;   // the single scratch slot holds R
+        // the single scratch slot holds R
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (e < nrow) g[e] = *reinterpret_cast<const float4*>(H0 + (long long)e * ldn);
+        for (int e = 0; e < 8; ++e) g[e] = *(const NG_AS1 f32x4_t*)(Hb + rowoff[e]);
     }
 
     const float b1 = sc.beta1, b2 = sc.beta2, ob1 = 1.0f - sc.beta1, ob2 = 1.0f - sc.beta2;
     const float bc1 = dyn[pr.mat].bc1, bc2 = dyn[pr.mat].bc2;
-    float4 nv[8];
+    NG_AS1 float* Mb = (NG_AS1 float*)md.M + base;
+    NG_AS1 float* Vb = (NG_AS1 float*)md.V + base;
+    f32x4_t mv[8], vv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        mv[e] = *(const NG_AS1 f32x4_t*)(Mb + rowoff[e]);
+        vv[e] = *(const NG_AS1 f32x4_t*)(Vb + rowoff[e]);
+    }
+    f32x4_t nv[8];
     bool bad = false;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        nv[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (e < nrow) {
-            float4* Mp = reinterpret_cast<float4*>(md.M + base + (long long)e * ldn);
-            float4* Vp = reinterpret_cast<float4*>(md.V + base + (long long)e * ldn);
-            float4 m = *Mp, v = *Vp;
-            const float4 ge = g[e];
-            m.x = fmaf(b1, m.x, ob1 * ge.x);
-            m.y = fmaf(b1, m.y, ob1 * ge.y);
-            m.z = fmaf(b1, m.z, ob1 * ge.z);
-            m.w = fmaf(b1, m.w, ob1 * ge.w);
-            v.x = fmaf(b2, v.x, ob2 * ge.x * ge.x);
-            v.y = fmaf(b2, v.y, ob2 * ge.y * ge.y);
-            v.z = fmaf(b2, v.z, ob2 * ge.z * ge.z);
-            v.w = fmaf(b2, v.w, ob2 * ge.w * ge.w);
-            *Mp = m;
-            *Vp = v;
-            float4 o;
-            if (sc.adam_mode == NG_ADAM_STANDARD) {
-                o.x = (m.x * bc1) / (sqrtf(v.x) * bc2 + sc.eps);
-                o.y = (m.y * bc1) / (sqrtf(v.y) * bc2 + sc.eps);
-                o.z = (m.z * bc1) / (sqrtf(v.z) * bc2 + sc.eps);
-                o.w = (m.w * bc1) / (sqrtf(v.w) * bc2 + sc.eps);
-            } else {
-                o.x = m.x / sqrtf(v.x + sc.eps);
-                o.y = m.y / sqrtf(v.y + sc.eps);
-                o.z = m.z / sqrtf(v.z + sc.eps);
-                o.w = m.w / sqrtf(v.w + sc.eps);
-            }
-            bad |= !(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
-                   !(fabsf(o.w) <= 3.0e38f);
-            nv[e] = o;
+        f32x4_t m = mv[e], v = vv[e];
+        const f32x4_t ge = g[e];
+        m.x = fmaf(b1, m.x, ob1 * ge.x);
+        m.y = fmaf(b1, m.y, ob1 * ge.y);
+        m.z = fmaf(b1, m.z, ob1 * ge.z);
+        m.w = fmaf(b1, m.w, ob1 * ge.w);
+        v.x = fmaf(b2, v.x, ob2 * ge.x * ge.x);
+        v.y = fmaf(b2, v.y, ob2 * ge.y * ge.y);
+        v.z = fmaf(b2, v.z, ob2 * ge.z * ge.z);
+        v.w = fmaf(b2, v.w, ob2 * ge.w * ge.w);
+        f32x4_t o;
+        if (sc.adam_mode == NG_ADAM_STANDARD) {
+            o.x = (m.x * bc1) / (sqrtf(v.x) * bc2 + sc.eps);
+            o.y = (m.y * bc1) / (sqrtf(v.y) * bc2 + sc.eps);
+            o.z = (m.z * bc1) / (sqrtf(v.z) * bc2 + sc.eps);
+            o.w = (m.w * bc1) / (sqrtf(v.w) * bc2 + sc.eps);
+        } else {
+            o.x = m.x / sqrtf(v.x + sc.eps);
+            o.y = m.y / sqrtf(v.y + sc.eps);
+            o.z = m.z / sqrtf(v.z + sc.eps);
+            o.w = m.w / sqrtf(v.w + sc.eps);
         }
+        const bool live = e < nrow;
+        if (live) {
+            *(NG_AS1 f32x4_t*)(Mb + rowoff[e]) = m;
+            *(NG_AS1 f32x4_t*)(Vb + rowoff[e]) = v;
+        }
+        bad |= live && (!(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
+                        !(fabsf(o.w) <= 3.0e38f));
+        nv[e].x = live ? o.x : 0.f;
+        nv[e].y = live ? o.y : 0.f;
+        nv[e].z = live ? o.z : 0.f;
+        nv[e].w = live ? o.w : 0.f;
     }
 
     if (BF16_N) {
         // [octet][col][8]: this thread's 4 columns are 4 consecutive 16-byte units
-        uint4* Np = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(md.N) +
-                                             ((long long)(row0 >> 3) * ldn + col0) * 8);
-        const float* f = reinterpret_cast<const float*>(nv);   // f[e*4 + c]
+        NG_AS1 u32x4_t* Np = (NG_AS1 u32x4_t*)((NG_AS1 bf16_t*)md.N + ((long long)(row0 >> 3) * ldn + col0) * 8);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint4 o;
-            o.x = (unsigned)f32_to_bf16_rne(f[0 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[1 * 4 + c]) << 16);
-            o.y = (unsigned)f32_to_bf16_rne(f[2 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[3 * 4 + c]) << 16);
-            o.z = (unsigned)f32_to_bf16_rne(f[4 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[5 * 4 + c]) << 16);
-            o.w = (unsigned)f32_to_bf16_rne(f[6 * 4 + c]) | ((unsigned)f32_to_bf16_rne(f[7 * 4 + c]) << 16);
+            u32x4_t o;
+            o.x = (unsigned)f32_to_bf16_rne(nv[0][c]) | ((unsigned)f32_to_bf16_rne(nv[1][c]) << 16);
+            o.y = (unsigned)f32_to_bf16_rne(nv[2][c]) | ((unsigned)f32_to_bf16_rne(nv[3][c]) << 16);
+            o.z = (unsigned)f32_to_bf16_rne(nv[4][c]) | ((unsigned)f32_to_bf16_rne(nv[5][c]) << 16);
+            o.w = (unsigned)f32_to_bf16_rne(nv[6][c]) | ((unsigned)f32_to_bf16_rne(nv[7][c]) << 16);
             Np[c] = o;
         }
     } else {
-        float* Nf = reinterpret_cast<float*>(md.N) + base;
+        NG_AS1 float* Nf = (NG_AS1 float*)md.N + base;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (e < nrow) *reinterpret_cast<float4*>(Nf + (long long)e * ldn) = nv[e];
+            if (e < nrow) *(NG_AS1 f32x4_t*)(Nf + rowoff[e]) = nv[e];
     }
     if (bad) atomicOr(status, 2);
 }

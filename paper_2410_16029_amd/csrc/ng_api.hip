@@ -46,6 +46,10 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
         if (x.reserved != 0) return NG_ERR_INVALID_ARG;
         if ((long long)x.m > (1 << 24) || (long long)x.n > (1 << 24)) return NG_ERR_SHAPE;
         if ((long long)x.r + hp->refresh_oversample > 2048) return NG_ERR_SHAPE;   // LDS budget of the Jacobi blocks
+        // the kernels address one matrix with 32-bit offsets
+        const long long ldmax = x.ld_w > x.ld_g ? x.ld_w : x.ld_g;
+        if ((long long)x.m * ldmax * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
+        if ((long long)x.r * (x.n + 32) * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
     }
     return NG_OK;
 }

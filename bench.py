@@ -94,6 +94,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true")
     ap.add_argument("--refresh-in-loop", type=int, default=0, help="refresh every this many timed steps (0 = never)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 10 plain device-to-device copies of MIB MiB "
+                         "(calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (matrices are independent; sharding by "
@@ -108,6 +111,15 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4, "copies": 10}))
+        return 0
     cfg = workloads.CONFIGS[args.config]
     mats = cfg.matrices()
 
@@ -165,6 +177,17 @@ def main() -> int:
                     ph["frac_mfma"] = round(ph["TFLOP/s"] / MFMA_PEAK_TFLOPS[cfg.dtype], 4)
             phases[name] = ph
 
+    def measured_traffic(kernel):
+        """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+        path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, args.config))
+        try:
+            for line in open(path):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+        except OSError:
+            pass
+        return None
+
     roofline = None
     if phases:
         dom = max(phases, key=lambda k: phases[k]["ms"])
@@ -172,11 +195,11 @@ def main() -> int:
             # at the 1.1B shapes the two GEMMs sit at the MFMA/HBM ridge; price them against MFMA
             roofline = {"kernel": dom, "bound": "mfma", "achieved": phases[dom]["TFLOP/s"],
                         "peak": MFMA_PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
-                        "frac": phases[dom]["frac_mfma"], "traffic": None}
+                        "frac": phases[dom]["frac_mfma"], "traffic": measured_traffic(dom)}
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": phases[dom].get("GB/s"),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": phases[dom].get("frac_hbm"),
-                        "traffic": None}
+                        "traffic": measured_traffic(dom)}
 
     out = {
         "metric": "natural_galore_optimizer_steps_per_s",

@@ -147,21 +147,33 @@ hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef*
 // LDS) and solves A w = e_head.  A non-positive or non-finite pivot sets bit 0
 // of *status; a non-finite w sets bit 1.
 __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
-                                              StepScalars sc, int* status) {
+                                              int first, StepScalars sc, int* status) {
     __shared__ double A[kMaxS][kMaxS + 1];
     __shared__ double bc[kMaxS];
-    const MatDev& md = mats[blockIdx.x];
+    const MatDev& md = mats[first + blockIdx.x];
     const int s = sc.s;
-    const int head = dyn[blockIdx.x].head;
+    const int head = dyn[first + blockIdx.x].head;
     const int i = threadIdx.x;
 
     // old Gram matrix into LDS, then overwrite row and column `head` with the new dots
     if (i < s)
         for (int j = 0; j < s; ++j) A[i][j] = md.K[(long long)i * s + j];
     __syncthreads();
-    if (i < s) {
+    // partial sums: lane (sub, j) adds parts sub, sub+nsub, ... in order; the nsub sub-sums of a
+    // slot are then added in order (a fixed order: the result does not depend on timing)
+    {
+        const int nsub = 64 / s;
+        const int j = i % s, sub = i / s;
         double v = 0.0;
-        for (int p = 0; p < md.dot_nparts; ++p) v += md.dot_parts[(long long)p * s + i];
+        if (sub < nsub)
+            for (int p = sub; p < md.dot_nparts; p += nsub) v += md.dot_parts[(long long)p * s + j];
+        bc[i] = v;
+    }
+    __syncthreads();
+    if (i < s) {
+        const int nsub = 64 / s;
+        double v = 0.0;
+        for (int q = 0; q < nsub; ++q) v += bc[q * s + i];
         md.K[(long long)head * s + i] = v;
         md.K[(long long)i * s + head] = v;
         A[head][i] = v;
@@ -219,9 +231,9 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
     if (bad) atomicOr(status, 1);
 }
 
-hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int n_mats, StepScalars sc, int* status,
-                        hipStream_t stream) {
-    hipLaunchKernelGGL(k_solve, dim3(n_mats), dim3(64), 0, stream, mats, dyn, sc, status);
+hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_mats, StepScalars sc,
+                        int* status, hipStream_t stream) {
+    hipLaunchKernelGGL(k_solve, dim3(n_mats), dim3(64), 0, stream, mats, dyn, first, sc, status);
     return hipGetLastError();
 }
 

@@ -55,9 +55,10 @@ __device__ __forceinline__ u32x4_t zero_unless(bool ok, u32x4_t v) {
     return v;
 }
 
-template <int BM_, int BN_, int WM_, int WN_, int BK_>
+template <int BM_, int BN_, int WM_, int WN_, int BK_, bool DB_ = false>
 struct Cfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_;
+    static constexpr bool DB = DB_;                         // two LDS operand buffers, one barrier per k-step
     static constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN, NT = NW * 64;
     static constexpr int MI = WM / 32, NJ = WN / 32;
     static constexpr int LDS_K = BK + 8;                    // bf16 elements per LDS row
@@ -69,7 +70,8 @@ struct Cfg {
     static constexpr int OPER_BYTES = (BM + BN) * LDS_K * 2;
     static constexpr int LDC = BN + 8;                      // floats per staged C row
     static constexpr int STAGE_BYTES = NWM * 32 * LDC * 4;
-    static constexpr int LDS_BYTES = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
+    static constexpr int OPER_TOTAL = DB ? 2 * OPER_BYTES : OPER_BYTES;
+    static constexpr int LDS_BYTES = OPER_TOTAL > STAGE_BYTES ? OPER_TOTAL : STAGE_BYTES;
     static_assert(BM * KC % NT == 0 && BN * KC % NT == 0 && KG * (BN / 8) % NT == 0, "tile/thread mismatch");
     static_assert(NT % KC == 0 && NT % BN == 0 && NT % KG == 0, "per-thread invariants");
 };
@@ -292,27 +294,72 @@ __device__ __forceinline__ void zero_acc(floatx16 (&acc)[C::MI][C::NJ]) {
 }
 
 // =================================================================== projection
+// Adapter: the gradient loader with its FULL flag fixed at compile time.
 template <class C, bool FULL>
-__device__ __forceinline__ void project_mainloop(floatx16 (&acc)[C::MI][C::NJ], ALoader<C>& la, BTLoader<C>& lb,
-                                                 bf16_t* As, bf16_t* Bs, int nk, int t, int wm, int wn, int li,
-                                                 int h) {
-    la.load(0);
-    lb.template load<FULL>(0);
-    la.store(As, t);
-    lb.template store<FULL>(Bs, t);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) {
-            la.load((kt + 1) * C::BK);
-            lb.template load<FULL>((kt + 1) * C::BK);
-        }
-        mma_tile<C>(acc, As, Bs, wm, wn, li, h);
+struct BTView {
+    BTLoader<C>& l;
+    __device__ __forceinline__ void load(int k0) { l.template load<FULL>(k0); }
+    __device__ __forceinline__ void store(bf16_t* Bs, int t) const { l.template store<FULL>(Bs, t); }
+};
+
+// Main loop over the contraction.  LA / LB: load(k0) issues the global loads of one BK-deep
+// tile into registers, store(ptr, t) writes them (masked) to LDS.
+//   single buffer: loads of tile kt+1 are in flight during the MFMAs of tile kt; two barriers.
+//   double buffer: registers hold tile kt+1 (loaded one whole step earlier); they are written to
+//   the other LDS buffer while tile kt is multiplied, then the loads of tile kt+2 are issued;
+//   one barrier per step.
+template <class C, class LA, class LB>
+__device__ __forceinline__ void gemm_mainloop(floatx16 (&acc)[C::MI][C::NJ], LA& la, LB& lb, unsigned char* smem,
+                                              int nk, int t, int wm, int wn, int li, int h) {
+    bf16_t* As0 = reinterpret_cast<bf16_t*>(smem);
+    bf16_t* Bs0 = As0 + C::BM * C::LDS_K;
+    if (!C::DB) {
+        la.load(0);
+        lb.load(0);
+        la.store(As0, t);
+        lb.store(Bs0, t);
         __syncthreads();
-        if (kt + 1 < nk) {
-            la.store(As, t);
-            lb.template store<FULL>(Bs, t);
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt + 1 < nk) {
+                la.load((kt + 1) * C::BK);
+                lb.load((kt + 1) * C::BK);
+            }
+            mma_tile<C>(acc, As0, Bs0, wm, wn, li, h);
+            __syncthreads();
+            if (kt + 1 < nk) {
+                la.store(As0, t);
+                lb.store(Bs0, t);
+            }
+            __syncthreads();
+        }
+    } else {
+        bf16_t* As1 = reinterpret_cast<bf16_t*>(smem + C::OPER_BYTES);
+        bf16_t* Bs1 = As1 + C::BM * C::LDS_K;
+        la.load(0);
+        lb.load(0);
+        la.store(As0, t);
+        lb.store(Bs0, t);
+        if (nk > 1) {
+            la.load(C::BK);
+            lb.load(C::BK);
         }
         __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            bf16_t* Ac = (kt & 1) ? As1 : As0;
+            bf16_t* Bc = (kt & 1) ? Bs1 : Bs0;
+            bf16_t* An = (kt & 1) ? As0 : As1;
+            bf16_t* Bn = (kt & 1) ? Bs0 : Bs1;
+            if (kt + 1 < nk) {
+                la.store(An, t);
+                lb.store(Bn, t);
+            }
+            if (kt + 2 < nk) {
+                la.load((kt + 2) * C::BK);
+                lb.load((kt + 2) * C::BK);
+            }
+            mma_tile<C>(acc, Ac, Bc, wm, wn, li, h);
+            __syncthreads();
+        }
     }
 }
 
@@ -321,8 +368,6 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
                                                         const MatDyn* __restrict__ dyn,
                                                         const TileRef* __restrict__ tiles) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* As = reinterpret_cast<bf16_t*>(smem);
-    bf16_t* Bs = As + C::BM * C::LDS_K;
 
     const TileRef tr = tiles[blockIdx.x];
     if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
@@ -343,8 +388,13 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
     const int nk = (m + C::BK - 1) / C::BK;
     // uniform per workgroup: are all 8-column chunks of this tile whole?
     const bool full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
-    if (full) project_mainloop<C, true>(acc, la, lb, As, Bs, nk, t, wm, wn, li, h);
-    else project_mainloop<C, false>(acc, la, lb, As, Bs, nk, t, wm, wn, li, h);
+    if (full) {
+        BTView<C, true> v{lb};
+        gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+    } else {
+        BTView<C, false> v{lb};
+        gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+    }
 
     NG_AS1 float* R = (NG_AS1 float*)(md.H + (long long)dy.head * md.slot_elems);
 #pragma unroll
@@ -368,8 +418,6 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
                                                        const MatDyn* __restrict__ dyn,
                                                        const TileRef* __restrict__ tiles, StepScalars sc) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* As = reinterpret_cast<bf16_t*>(smem);
-    bf16_t* Bs = As + C::BM * C::LDS_K;
     float* Cs = reinterpret_cast<float*>(smem);
 
     const TileRef tr = tiles[blockIdx.x];
@@ -390,29 +438,13 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
     la.init(md.Pb, md.ldr, i0, m, md.ldr, t);
     lb.init(reinterpret_cast<const bf16_t*>(md.N), ldn, md.roct, j0, t);
     const int nk = (kdim + C::BK - 1) / C::BK;
-    la.load(0);
-    lb.load(0);
-    la.store(As, t);
-    lb.store(Bs, t);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) {
-            la.load((kt + 1) * C::BK);
-            lb.load((kt + 1) * C::BK);
-        }
-        mma_tile<C>(acc, As, Bs, wm, wn, li, h);
-        __syncthreads();
-        if (kt + 1 < nk) {
-            la.store(As, t);
-            lb.store(Bs, t);
-        }
-        __syncthreads();
-    }
+    NG_AS1 bf16_t* W = (NG_AS1 bf16_t*)dy.w;
+    const unsigned ld_w = (unsigned)md.ld_w;
+    gemm_mainloop<C>(acc, la, lb, smem, nk, t, wm, wn, li, h);
+    if (C::DB) __syncthreads();   // (the single-buffer loop already ends on a barrier)
 
     // Epilogue, one 32-row block of every wave-row at a time: accumulators -> LDS (float),
     // then each thread read-modify-writes 8 consecutive bf16 of one weight row.
-    NG_AS1 bf16_t* W = (NG_AS1 bf16_t*)dy.w;
-    const unsigned ld_w = (unsigned)md.ld_w;
     constexpr int ROWS = C::NWM * 32;
     constexpr int CH = C::BN / 8;                         // 8-column chunks per row
     constexpr int PER_T = ROWS * CH / C::NT;
@@ -488,22 +520,31 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
 }
 
 // =================================================================== launchers
-// Tile configurations; NG_GEMM_CFG (environment, read once) selects one for experiments.
+// Tile configurations.  Default: 256 x 128 workgroup tiles (128 x 64 per wavefront); the
+// projection falls back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half
+// empty).  NG_GEMM_CFG (environment, read once) forces one configuration for experiments:
+// 0 = 128x128, 2 = 256x128, 6 = 256x256 with two LDS buffers (8 wavefronts).
 typedef Cfg<128, 128, 64, 64, 64> Cfg0;
-typedef Cfg<128, 128, 64, 64, 128> Cfg1;
 typedef Cfg<256, 128, 128, 64, 64> Cfg2;
-typedef Cfg<128, 256, 64, 128, 64> Cfg3;
-typedef Cfg<256, 256, 128, 64, 64> Cfg4;
-constexpr int kDefaultCfg = 2;
+typedef Cfg<256, 256, 128, 64, 64, true> Cfg6;
 
-static int gemm_cfg() {
-    static int cfg = -1;
-    if (cfg < 0) {
+static int forced_cfg() {
+    static int cfg = -2;
+    if (cfg == -2) {
         const char* e = getenv("NG_GEMM_CFG");
-        cfg = e ? atoi(e) : kDefaultCfg;
-        if (cfg < 0 || cfg > 4) cfg = kDefaultCfg;
+        cfg = e ? atoi(e) : -1;
+        if (cfg != 0 && cfg != 2 && cfg != 6) cfg = -1;
     }
     return cfg;
+}
+static int project_cfg(int max_r) {
+    const int f = forced_cfg();
+    if (f >= 0) return f;
+    return max_r > 128 ? 2 : 0;
+}
+static int update_cfg() {
+    const int f = forced_cfg();
+    return f >= 0 ? f : 2;
 }
 
 template <class C>
@@ -533,13 +574,11 @@ static hipError_t run_update(const MatDev* mats, const MatDyn* dyn, const TileRe
 }
 
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               hipStream_t stream) {
+                               int max_r, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    switch (gemm_cfg()) {
+    switch (project_cfg(max_r)) {
         case 0: return run_project<Cfg0>(mats, dyn, tiles, n_tiles, stream);
-        case 1: return run_project<Cfg1>(mats, dyn, tiles, n_tiles, stream);
-        case 3: return run_project<Cfg3>(mats, dyn, tiles, n_tiles, stream);
-        case 4: return run_project<Cfg4>(mats, dyn, tiles, n_tiles, stream);
+        case 6: return run_project<Cfg6>(mats, dyn, tiles, n_tiles, stream);
         default: return run_project<Cfg2>(mats, dyn, tiles, n_tiles, stream);
     }
 }
@@ -547,21 +586,19 @@ hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const Tile
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    switch (gemm_cfg()) {
+    switch (update_cfg()) {
         case 0: return run_update<Cfg0>(mats, dyn, tiles, n_tiles, sc, stream);
-        case 1: return run_update<Cfg1>(mats, dyn, tiles, n_tiles, sc, stream);
-        case 3: return run_update<Cfg3>(mats, dyn, tiles, n_tiles, sc, stream);
-        case 4: return run_update<Cfg4>(mats, dyn, tiles, n_tiles, sc, stream);
+        case 6: return run_update<Cfg6>(mats, dyn, tiles, n_tiles, sc, stream);
         default: return run_update<Cfg2>(mats, dyn, tiles, n_tiles, sc, stream);
     }
 }
 
-void bf16_tile_shape(int* bm, int* bn) {
-    switch (gemm_cfg()) {
+// which: 0 = projection (needs the largest rank of the layer set), 1 = update
+void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
+    const int c = which == 0 ? project_cfg(max_r) : update_cfg();
+    switch (c) {
         case 0: *bm = Cfg0::BM; *bn = Cfg0::BN; break;
-        case 1: *bm = Cfg1::BM; *bn = Cfg1::BN; break;
-        case 3: *bm = Cfg3::BM; *bn = Cfg3::BN; break;
-        case 4: *bm = Cfg4::BM; *bn = Cfg4::BN; break;
+        case 6: *bm = Cfg6::BM; *bn = Cfg6::BN; break;
         default: *bm = Cfg2::BM; *bn = Cfg2::BN; break;
     }
 }

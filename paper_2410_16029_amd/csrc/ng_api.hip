@@ -124,8 +124,11 @@ void xcd_order(const std::vector<TileRef>& logical, std::vector<TileRef>* out) {
 
 void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* p) {
     p->sz.resize(n_mats);
-    int bm = 128, bn = 128;
-    bf16_tile_shape(&bm, &bn);
+    int max_r = 0;
+    for (int i = 0; i < n_mats; ++i) max_r = d[i].r > max_r ? d[i].r : max_r;
+    int pbm = 128, pbn = 128, ubm = 128, ubn = 128;
+    bf16_tile_shape(0, max_r, &pbm, &pbn);
+    bf16_tile_shape(1, max_r, &ubm, &ubn);
     std::vector<TileRef> proj, upd;
     p->dots.clear();
     p->patches.clear();
@@ -133,10 +136,10 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         derive(d[i], hp, &p->sz[i]);
         const Sizes& z = p->sz[i];
         if (hp.grad_dtype == NG_BF16) {
-            for (int tj = 0; tj < ceil_div(z.ldn, bn); ++tj)
-                for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) proj.push_back(TileRef{i, ti, tj, 0});
-            for (int tj = 0; tj < ceil_div(d[i].n, bn); ++tj)
-                for (int ti = 0; ti < ceil_div(d[i].m, bm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
+            for (int tj = 0; tj < ceil_div(z.ldn, pbn); ++tj)
+                for (int ti = 0; ti < ceil_div(d[i].r, pbm); ++ti) proj.push_back(TileRef{i, ti, tj, 0});
+            for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
+                for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
         }
         for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
             for (int tj = 0; tj < ceil_div(z.ldn, 256); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
@@ -180,6 +183,7 @@ struct ng_state {
     int* d_status;
     TileRef *d_proj, *d_upd, *d_dots, *d_patches;
     int n_dots;
+    std::vector<int> dots_begin, patch_begin;   // per matrix: first entry in the tables (+ end sentinel)
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
     int max_ti[OP_COUNT], max_tj[OP_COUNT];
     int max_jpairs;
@@ -435,6 +439,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             if (iters < 1) iters = 1;
             md.dot_iters = (int)iters;
             md.dot_nparts = (int)((total4 + iters * 256 - 1) / (iters * 256));
+            st->dots_begin.push_back((int)dots.size());
             if (hp->s > 0)
                 for (int p = 0; p < md.dot_nparts; ++p) dots.push_back(TileRef{i, p, 0, 0});
             if (md.m > st->max_m) st->max_m = md.m;
@@ -457,6 +462,13 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             (void)s_eff;
         }
         st->n_dots = (int)dots.size();
+        st->dots_begin.push_back((int)dots.size());
+        {
+            // patches were appended matrix by matrix in make_plan
+            st->patch_begin.assign(n_mats + 1, 0);
+            for (size_t q = 0; q < pl.patches.size(); ++q) st->patch_begin[pl.patches[q].mat + 1] += 1;
+            for (int i = 0; i < n_mats; ++i) st->patch_begin[i + 1] += st->patch_begin[i];
+        }
 
         // upload the tables (synchronous copies; init is not a hot path)
         hipError_t e = hipSuccess;
@@ -582,14 +594,14 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), stream));
+    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, stream));
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
     if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
-    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, st->n_mats, sc, st->d_status, stream));
+    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, st->d_status, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_ADAM], stream));
     NG_HIP(launch_transform_adam(st->d_mats, st->d_dyn, st->d_patches, (int)st->plan.patches.size(), sc,

@@ -12,7 +12,7 @@ namespace ng {
 typedef unsigned short bf16_t;   // raw bfloat16 bits
 
 constexpr int kMaxS = 64;        // history slots
-constexpr int kDotPartsMax = 64; // per-matrix partial sums of the Gram-row reduction
+constexpr int kDotPartsMax = 256; // per-matrix partial sums of the Gram-row reduction
 constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (by kernel argument)
 constexpr int kJacobiLdsBudget = 147456;   // bytes of LDS the blocked Jacobi may use for its two row blocks
 
@@ -114,17 +114,17 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
                            hipStream_t stream);
 
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
-void bf16_tile_shape(int* bm, int* bn);
+void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               hipStream_t stream);
+                               int max_r, hipStream_t stream);
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,
                            int s, hipStream_t stream);
-hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int n_mats, StepScalars sc, int* status,
-                        hipStream_t stream);
+hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_mats, StepScalars sc,
+                        int* status, hipStream_t stream);
 hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,
                                  StepScalars sc, int grad_dtype, int* status, hipStream_t stream);
 hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, int max_r, hipStream_t stream);

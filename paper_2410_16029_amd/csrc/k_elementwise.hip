@@ -20,11 +20,16 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ helpers
-__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
-    unsigned int u = __float_as_uint(x);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> two bf16 (round to nearest even) in one v_cvt_pk_bf16_f32; a in the low half
+__device__ __forceinline__ unsigned int pack_bf16x2(float a, float b) {
+    const f32x2_t f = {a, b};
+    bf16x2_t hv = __builtin_convertvector(f, bf16x2_t);
+    return *reinterpret_cast<unsigned int*>(&hv);
 }
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) { return (unsigned short)(pack_bf16x2(x, 0.f) & 0xffffu); }
 
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -350,10 +355,10 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             u32x4_t o;
-            o.x = (unsigned)f32_to_bf16_rne(nv[0][c]) | ((unsigned)f32_to_bf16_rne(nv[1][c]) << 16);
-            o.y = (unsigned)f32_to_bf16_rne(nv[2][c]) | ((unsigned)f32_to_bf16_rne(nv[3][c]) << 16);
-            o.z = (unsigned)f32_to_bf16_rne(nv[4][c]) | ((unsigned)f32_to_bf16_rne(nv[5][c]) << 16);
-            o.w = (unsigned)f32_to_bf16_rne(nv[6][c]) | ((unsigned)f32_to_bf16_rne(nv[7][c]) << 16);
+            o.x = pack_bf16x2(nv[0][c], nv[1][c]);
+            o.y = pack_bf16x2(nv[2][c], nv[3][c]);
+            o.z = pack_bf16x2(nv[4][c], nv[5][c]);
+            o.w = pack_bf16x2(nv[6][c], nv[7][c]);
             Np[c] = o;
         }
     } else {

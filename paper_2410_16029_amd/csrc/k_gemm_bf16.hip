@@ -42,11 +42,16 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef u32x4_t __attribute__((aligned(2))) u32x4_a2;   // 16-byte access at 2-byte alignment
 typedef const NG_AS1 bf16_t* gbf16_cptr;
 
-__device__ __forceinline__ unsigned int f2bf(float x) {
-    unsigned int u = __float_as_uint(x);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> two bf16 (round to nearest even) in one v_cvt_pk_bf16_f32; a in the low half
+__device__ __forceinline__ unsigned int pack_bf16x2(float a, float b) {
+    const f32x2_t f = {a, b};
+    bf16x2_t hv = __builtin_convertvector(f, bf16x2_t);
+    return *reinterpret_cast<unsigned int*>(&hv);
 }
+__device__ __forceinline__ unsigned int f2bf(float x) { return pack_bf16x2(x, 0.f) & 0xffffu; }
 __device__ __forceinline__ u32x4_t zero_unless(bool ok, u32x4_t v) {
     v.x = ok ? v.x : 0u;
     v.y = ok ? v.y : 0u;
@@ -450,11 +455,12 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
     constexpr int PER_T = ROWS * CH / C::NT;
     static_assert(ROWS * CH % C::NT == 0, "epilogue mapping");
     const bool cols_full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
+    // All weight loads of the tile are issued up front (the main loop's staging registers are
+    // free now), so the HBM latency is paid once per tile, not once per pass.
+    u32x4_t wv4[C::MI][PER_T];
+    if (cols_full) {
 #pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi) {
-        // this pass's weight loads are issued before the accumulators are staged
-        u32x4_t wv4[PER_T];
-        if (cols_full) {
+        for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
             for (int p = 0; p < PER_T; ++p) {
                 const int q = t + C::NT * p;
@@ -463,9 +469,11 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
                 const int col = j0 + cc * 8;
                 const unsigned rc = (unsigned)(row < m ? row : m - 1);
                 const unsigned jc = (unsigned)((col + 8 <= n) ? col : n - 8);
-                wv4[p] = *(const NG_AS1 u32x4_a2*)(W + (rc * ld_w + jc));
+                wv4[mi][p] = *(const NG_AS1 u32x4_a2*)(W + (rc * ld_w + jc));
             }
-        }
+    }
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
 #pragma unroll
         for (int nj = 0; nj < C::NJ; ++nj)
 #pragma unroll
@@ -488,11 +496,11 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
                 u32x4_t ov;
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    const unsigned wi = wv4[p][d];
+                    const unsigned wi = wv4[mi][p][d];
                     const float w0 = __uint_as_float(wi << 16), w1 = __uint_as_float(wi & 0xffff0000u);
                     const float n0 = w0 - (sc.lr_scale * cv[2 * d] + sc.lr_wd * w0);
                     const float n1 = w1 - (sc.lr_scale * cv[2 * d + 1] + sc.lr_wd * w1);
-                    ov[d] = f2bf(n0) | (f2bf(n1) << 16);
+                    ov[d] = pack_bf16x2(n0, n1);
                 }
                 if (row < m && col + 8 <= n) *(NG_AS1 u32x4_a2*)(W + ((unsigned)row * ld_w + (unsigned)col)) = ov;
             }

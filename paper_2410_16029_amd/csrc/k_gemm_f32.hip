@@ -49,14 +49,16 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.C = dy ? dy->w : nullptr; v.ldc = md.ld_w; v.epi = EPI_W_F32;
             break;
         case OP_G_B2A:
+        case OP_G_C2A:
             v.A = G; v.sAi = md.ld_g; v.sAk = 1; v.a_bf16 = gb;
-            v.B = md.Yb; v.sBk = md.l; v.sBj = 1;
+            v.B = (op == OP_G_B2A) ? md.Yb : md.Yc; v.sBk = md.l; v.sBj = 1;
             v.M = md.m; v.N = md.l; v.Nvalid = md.l; v.K = md.n;
             v.C = md.Ya; v.ldc = md.l;
             break;
         case OP_GT_A2B:
+        case OP_GT_C2B:
             v.A = G; v.sAi = 1; v.sAk = md.ld_g; v.a_bf16 = gb;
-            v.B = md.Ya; v.sBk = md.l; v.sBj = 1;
+            v.B = (op == OP_GT_A2B) ? md.Ya : md.Yc; v.sBk = md.l; v.sBj = 1;
             v.M = md.n; v.N = md.l; v.Nvalid = md.l; v.K = md.m;
             v.C = md.Yb; v.ldc = md.l;
             break;

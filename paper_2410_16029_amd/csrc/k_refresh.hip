@@ -123,27 +123,79 @@ hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shi
 }
 
 // ------------------------------------------------------------------ inverse of the Cholesky factor
-// Thread c owns column c of Linv = L^{-1} (forward substitution on e_c); all threads walk the
-// rows together so L[i][p] is one broadcast load and Linv[p][c] is coalesced over c.
-__global__ __launch_bounds__(1024) void k_tri_inverse(const MatDev* __restrict__ mats, int which) {
-    const MatDev& md = mats[blockIdx.x];
+// Linv = L^{-1} (lower triangular, float).  One workgroup owns a block of CB columns of the
+// inverse: forward substitution L X = E on those CB right-hand sides, the block of X kept in LDS
+// (rows above the block's first column are zero and skipped).  Thread (sub, c): column c of the
+// block, rows of the dot product split over the 256/CB values of sub.
+template <int CB>
+__global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ mats, int which) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char tri_smem[];
+    constexpr int S = 256 / CB;
+    const MatDev& md = mats[blockIdx.y];
     const int nn = which == 0 ? md.l : md.r;
+    const int c0 = blockIdx.x * CB;
+    if (c0 >= nn) return;
     const long long ld = md.lp;
     const double* __restrict__ L = md.T;
-    float* __restrict__ X = md.Linv;
-    for (int c = threadIdx.x; c < nn; c += blockDim.x) {
-        // forward substitution L x = e_c; entries above the diagonal come out as exact zeros
-        for (int i = 0; i < nn; ++i) {
-            const double* __restrict__ li = L + (long long)i * ld;
-            double acc = 0.0;
-            for (int p = 0; p < i; ++p) acc += li[p] * (double)X[(long long)p * ld + c];
-            X[(long long)i * ld + c] = (float)(((i == c ? 1.0 : 0.0) - acc) / li[i]);
+    float* __restrict__ Xg = md.Linv;
+    const int rows = nn - c0;                       // rows c0 .. nn-1 are non-trivial
+    double* lrow = reinterpret_cast<double*>(tri_smem);            // [rows]
+    double* red = lrow + ((rows + 1) & ~1);                          // [S][CB]
+    float* Xs = reinterpret_cast<float*>(red + S * CB);             // [rows][CB]
+    const int tid = threadIdx.x, c = tid % CB, sub = tid / CB;
+    const bool col_ok = c0 + c < nn;
+
+    // rows above the block: exact zeros
+    for (int q = tid; q < c0 * CB; q += 256) {
+        const int i = q / CB, cc = q % CB;
+        if (c0 + cc < nn) Xg[(long long)i * ld + c0 + cc] = 0.f;
+    }
+    for (int i = c0; i < nn; ++i) {
+        const int len = i - c0;                    // entries L[i][c0 .. i-1] take part in the dot product
+        for (int p = tid; p <= len; p += 256) lrow[p] = L[(long long)i * ld + c0 + p];
+        __syncthreads();
+        double acc = 0.0;
+        for (int p = sub; p < len; p += S) acc += lrow[p] * (double)Xs[p * CB + c];
+        red[sub * CB + c] = acc;
+        __syncthreads();
+        if (sub == 0) {
+            double tot = 0.0;
+#pragma unroll
+            for (int q = 0; q < S; ++q) tot += red[q * CB + c];
+            const float x = (float)(((i == c0 + c ? 1.0 : 0.0) - tot) / lrow[len]);
+            Xs[len * CB + c] = x;
+            if (col_ok) Xg[(long long)i * ld + c0 + c] = x;
         }
+        __syncthreads();
     }
 }
 
-hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, hipStream_t stream) {
-    hipLaunchKernelGGL(k_tri_inverse, dim3(n_mats), dim3(1024), 0, stream, mats, which);
+hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream) {
+    // column-block width: the widest whose LDS block fits
+    auto lds_for = [&](int cb) {
+        return (size_t)((max_order + 1) & ~1) * 8 + (size_t)256 * 8 + (size_t)max_order * cb * 4;
+    };
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<64>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<32>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<16>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        attr_done = true;
+    }
+    const size_t budget = 150 * 1024;
+    if (lds_for(64) <= budget) {
+        hipLaunchKernelGGL(k_tri_inverse<64>, dim3((max_order + 63) / 64, n_mats), dim3(256), lds_for(64), stream,
+                           mats, which);
+    } else if (lds_for(32) <= budget) {
+        hipLaunchKernelGGL(k_tri_inverse<32>, dim3((max_order + 31) / 32, n_mats), dim3(256), lds_for(32), stream,
+                           mats, which);
+    } else {
+        hipLaunchKernelGGL(k_tri_inverse<16>, dim3((max_order + 15) / 16, n_mats), dim3(256), lds_for(16), stream,
+                           mats, which);
+    }
     return hipGetLastError();
 }
 
@@ -180,78 +232,105 @@ hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t str
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void k_jacobi_round(const MatDev* __restrict__ mats, int round) {
+// One wavefront per row pair (blockDim = 64 * jb): the two rows are held in registers between
+// the three dot products and the rotation (each lane owns SEG columns, lane-contiguous in LDS).
+// JB is the row-block size the kernel is compiled for (matrices with another jb are skipped: the
+// host launches one instance per block size present in the layer set).
+template <int JB>
+__global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restrict__ mats, int round) {
+    constexpr int SEG = JB == 16 ? 9 : (JB == 8 ? 18 : 32);   // ceil(largest lp of the class / 64)
     extern __shared__ __attribute__((aligned(16))) double xs[];   // [2*jb][lp]
     __shared__ int nrot_s;
     const MatDev& md = mats[blockIdx.y];
-    const int lp = md.lp, jb = md.jb;
+    if (md.jb != JB) return;
+    const int lp = md.lp;
+    constexpr int jb = JB;
     const int nb = lp / jb;
     if ((int)blockIdx.x >= nb / 2 || round >= nb - 1) return;
-    if (md.jflag[1] != 0) return;   // converged in an earlier sweep
+    if (md.jflag[1] != 0) return;       // converged in an earlier sweep
     int bp, bq;
     tournament_pair(nb, round, blockIdx.x, &bp, &bq);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, nthr = 64 * jb;
     const int R = 2 * jb;
     double* __restrict__ X = md.T;
-    for (int q = tid; q < jb * lp; q += 256) {
+    for (int q = tid; q < jb * lp; q += nthr) {
         xs[q] = X[(long long)bp * jb * lp + q];
         xs[jb * lp + q] = X[(long long)bq * jb * lp + q];
     }
     if (tid == 0) nrot_s = 0;
     __syncthreads();
 
-    const int tpp = 256 / jb;            // threads per row pair (power of two, <= 64)
-    const int pi = tid / tpp, sub = tid % tpp;
+    const int pi = tid >> 6, lane = tid & 63;
     int nrot = 0;
     for (int ir = 0; ir < R - 1; ++ir) {
         int a, b;
         tournament_pair(R, ir, pi, &a, &b);
         double* xa = xs + a * lp;
         double* xb = xs + b * lp;
+        double va[SEG], vb[SEG];
         double al = 0.0, be = 0.0, ga = 0.0;
-        for (int c = sub; c < lp; c += tpp) {
-            const double va = xa[c], vb = xb[c];
-            al += va * va;
-            be += vb * vb;
-            ga += va * vb;
+#pragma unroll
+        for (int i = 0; i < SEG; ++i) {
+            const int c = lane + 64 * i;
+            va[i] = c < lp ? xa[c] : 0.0;
+            vb[i] = c < lp ? xb[c] : 0.0;
         }
-        for (int off = tpp >> 1; off > 0; off >>= 1) {
+#pragma unroll
+        for (int i = 0; i < SEG; ++i) {
+            al += va[i] * va[i];
+            be += vb[i] * vb[i];
+            ga += va[i] * vb[i];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
             al += __shfl_xor(al, off, 64);
             be += __shfl_xor(be, off, 64);
             ga += __shfl_xor(ga, off, 64);
         }
-        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-24 * al * be);
+        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-20 * al * be);
         if (rot) {
             const double zeta = (be - al) / (2.0 * ga);
             const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
             const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
-            for (int c = sub; c < lp; c += tpp) {
-                const double va = xa[c], vb = xb[c];
-                xa[c] = cs * va - sn * vb;
-                xb[c] = sn * va + cs * vb;
+#pragma unroll
+            for (int i = 0; i < SEG; ++i) {
+                const int c = lane + 64 * i;
+                if (c < lp) {
+                    xa[c] = cs * va[i] - sn * vb[i];
+                    xb[c] = sn * va[i] + cs * vb[i];
+                }
             }
-            if (sub == 0) ++nrot;
+            if (lane == 0) ++nrot;
         }
         __syncthreads();
     }
     if (nrot) atomicAdd(&nrot_s, nrot);
     __syncthreads();
-    for (int q = tid; q < jb * lp; q += 256) {
+    for (int q = tid; q < jb * lp; q += nthr) {
         X[(long long)bp * jb * lp + q] = xs[q];
         X[(long long)bq * jb * lp + q] = xs[jb * lp + q];
     }
     if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
 }
 
-hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
-                               hipStream_t stream) {
+template <int JB>
+static void jacobi_round_launch(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
+                                hipStream_t stream) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kJacobiLdsBudget);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round<JB>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kJacobiLdsBudget);
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_jacobi_round, dim3(max_pairs, n_mats), dim3(256), lds_bytes, stream, mats, round);
+    hipLaunchKernelGGL(k_jacobi_round<JB>, dim3(max_pairs, n_mats), dim3(64 * JB), lds_bytes, stream, mats, round);
+}
+
+// jb_mask: bit log2(jb) set for every row-block size present in the layer set (4, 8, 16).
+hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
+                               int jb_mask, hipStream_t stream) {
+    if (jb_mask & (1 << 4)) jacobi_round_launch<16>(mats, n_mats, max_pairs, round, lds_bytes, stream);
+    if (jb_mask & (1 << 3)) jacobi_round_launch<8>(mats, n_mats, max_pairs, round, lds_bytes, stream);
+    if (jb_mask & (1 << 2)) jacobi_round_launch<4>(mats, n_mats, max_pairs, round, lds_bytes, stream);
     return hipGetLastError();
 }
 

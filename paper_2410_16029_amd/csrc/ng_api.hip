@@ -186,7 +186,7 @@ struct ng_state {
     std::vector<int> dots_begin, patch_begin;   // per matrix: first entry in the tables (+ end sentinel)
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
     int max_ti[OP_COUNT], max_tj[OP_COUNT];
-    int max_jpairs;
+    int max_jpairs, jb_mask;
     size_t jacobi_lds;
     // profiling
     bool profiling;
@@ -263,17 +263,21 @@ int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
     return NG_OK;
 }
 
-// CholeskyQR of the sketch: X <- X L^{-T} twice (second pass repairs the loss of
-// orthogonality of the first).  rows_m: X has m rows (Ya) or n rows (Yb).
-int orthonormalise(ng_state* st, bool is_a, hipStream_t stream, const StepScalars& sc) {
+// CholeskyQR of the sketch X (Ya if is_a, else Yb).
+//   twice = false: one pass with a small diagonal shift, result left in Yc -- enough to keep the
+//                  power iteration from collapsing;
+//   twice = true : a second, unshifted pass repairs the first pass's loss of orthogonality and
+//                  puts the result back in X (the basis handed to the Rayleigh-Ritz step).
+int orthonormalise(ng_state* st, bool is_a, bool twice, hipStream_t stream, const StepScalars& sc) {
     int rc;
     if ((rc = gemm(st, is_a ? OP_GRAM_A : OP_GRAM_B, stream, sc)) != NG_OK) return rc;
-    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 1e-10, st->d_status, stream));
-    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, stream));
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 2e-7, st->d_status, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, st->max_l, stream));
     if ((rc = gemm(st, is_a ? OP_APPLY_A2C : OP_APPLY_B2C, stream, sc)) != NG_OK) return rc;
+    if (!twice) return NG_OK;
     if ((rc = gemm(st, is_a ? OP_GRAM_CA : OP_GRAM_CB, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 0.0, st->d_status, stream));
-    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, st->max_l, stream));
     if ((rc = gemm(st, is_a ? OP_APPLY_C2A : OP_APPLY_C2B, stream, sc)) != NG_OK) return rc;
     return NG_OK;
 }
@@ -399,6 +403,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         const int s_eff = hp->s > 0 ? hp->s : 1;
         st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
         st->max_jpairs = 0;
+        st->jb_mask = 0;
         st->jacobi_lds = 0;
         for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = 1;
         for (int i = 0; i < n_mats; ++i) {
@@ -451,6 +456,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             if (rows > st->max_rows) st->max_rows = rows;
             const int pairs = md.lp / md.jb / 2;
             if (pairs > st->max_jpairs) st->max_jpairs = pairs;
+            st->jb_mask |= md.jb;   // jb is 4, 8 or 16: its own bit
             const size_t jl = (size_t)2 * md.jb * md.lp * sizeof(double);
             if (jl > st->jacobi_lds) st->jacobi_lds = jl;
             for (int op = 0; op < OP_COUNT; ++op) {
@@ -538,13 +544,15 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     // randomised subspace iteration: Ya = orth(G Omega); q times { Yb = orth(G^T Ya); Ya = orth(G Yb) }
     NG_HIP(launch_fill_gaussian(st->d_mats, st->n_mats, st->max_n, st->hp.seed,
                                 (unsigned long long)st->n_refresh[0], stream));
+    const int q = st->hp.refresh_power_iters;
     if ((rc = gemm(st, OP_G_B2A, stream, sc)) != NG_OK) return rc;
-    if ((rc = orthonormalise(st, true, stream, sc)) != NG_OK) return rc;
-    for (int it = 0; it < st->hp.refresh_power_iters; ++it) {
-        if ((rc = gemm(st, OP_GT_A2B, stream, sc)) != NG_OK) return rc;
-        if ((rc = orthonormalise(st, false, stream, sc)) != NG_OK) return rc;
-        if ((rc = gemm(st, OP_G_B2A, stream, sc)) != NG_OK) return rc;
-        if ((rc = orthonormalise(st, true, stream, sc)) != NG_OK) return rc;
+    if ((rc = orthonormalise(st, true, q == 0, stream, sc)) != NG_OK) return rc;
+    for (int it = 0; it < q; ++it) {
+        // intermediate bases live in Yc (single-pass orthonormalisation)
+        if ((rc = gemm(st, OP_GT_C2B, stream, sc)) != NG_OK) return rc;
+        if ((rc = orthonormalise(st, false, false, stream, sc)) != NG_OK) return rc;
+        if ((rc = gemm(st, OP_G_C2A, stream, sc)) != NG_OK) return rc;
+        if ((rc = orthonormalise(st, true, it + 1 == q, stream, sc)) != NG_OK) return rc;
     }
     // Rayleigh-Ritz: B = Q^T G, T = B B^T = U diag(ritz^2) U^T, P = Q U[:, top r]
     if ((rc = gemm(st, OP_QT_G, stream, sc)) != NG_OK) return rc;
@@ -553,7 +561,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     for (int sw = 0; sw < st->hp.refresh_sweeps; ++sw) {
         const int max_rounds = 2 * st->max_jpairs - 1;
         for (int round = 0; round < (max_rounds > 0 ? max_rounds : 1); ++round)
-            NG_HIP(launch_jacobi_round(st->d_mats, st->n_mats, st->max_jpairs, round, st->jacobi_lds, stream));
+            NG_HIP(launch_jacobi_round(st->d_mats, st->n_mats, st->max_jpairs, round, st->jacobi_lds, st->jb_mask, stream));
         NG_HIP(launch_jacobi_sweep_end(st->d_mats, st->n_mats, stream));
     }
     NG_HIP(launch_jacobi_finish(st->d_mats, st->n_mats, st->d_status, stream));
@@ -561,7 +569,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     // one CholeskyQR pass on P (m x r) restores orthonormality to rounding level, then fix signs
     if ((rc = gemm(st, OP_GRAM_P, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 1, 0.0, st->d_status, stream));
-    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 1, stream));
+    NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 1, st->max_r, stream));
     if ((rc = gemm(st, OP_APPLY_P2A, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_sign_fix(st->d_mats, st->n_mats, st->max_r, stream));
 

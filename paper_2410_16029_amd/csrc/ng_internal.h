@@ -93,6 +93,8 @@ enum GemmOp {
     OP_UPDATE_F32,        // W -= lr*(scale * P N + wd W)             (step, NG_F32)
     OP_G_B2A,             // Ya = G Yb     (m x l)
     OP_GT_A2B,            // Yb = G^T Ya   (n x l)
+    OP_G_C2A,             // Ya = G Yc
+    OP_GT_C2B,            // Yb = G^T Yc
     OP_GRAM_A,            // T = Ya^T Ya   (rows m) -> double
     OP_GRAM_B,            // T = Yb^T Yb   (rows n)
     OP_GRAM_CA,           // T = Yc^T Yc   (rows m)
@@ -135,10 +137,10 @@ hipError_t launch_fill_gaussian(const MatDev* mats, int n_mats, int max_rows, un
 // which: 0 -> order l (sketch), 1 -> order r (final P)
 hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shift_rel, int* status,
                            hipStream_t stream);
-hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, hipStream_t stream);
+hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream);
 hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t stream);
 hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
-                               hipStream_t stream);
+                               int jb_mask, hipStream_t stream);
 hipError_t launch_jacobi_sweep_end(const MatDev* mats, int n_mats, hipStream_t stream);
 hipError_t launch_jacobi_finish(const MatDev* mats, int n_mats, int* status, hipStream_t stream);
 hipError_t launch_sign_fix(const MatDev* mats, int n_mats, int max_r, hipStream_t stream);

@@ -4,7 +4,7 @@
 // between them, one launch for all matrices of the layer set:
 //
 //   k_fill_gaussian     random sketch Omega (counter-based generator, Box-Muller)
-//   k_cholesky          T = L L^T in place (fp64, left-looking, one workgroup per matrix)
+//   k_chol_*            T = L L^T in place (fp64, right-looking, panels of 32 columns)
 //   k_tri_inverse       Linv = L^{-1} as float (the GEMM then applies X <- X Linv^T)
 //   k_jacobi_*          blocked one-sided Jacobi on the rows of the l x l Rayleigh-Ritz matrix
 //                       T = (Q^T G)(Q^T G)^T: at convergence row i = ritz_i * u_i^T
@@ -52,73 +52,163 @@ __device__ __forceinline__ double wave_sum_d(double v) {
     return v;
 }
 
-constexpr int kCholThreads = 1024;
-constexpr int kCholMaxOrder = 4096;
+// Right-looking blocked factorisation, panels of kCholNB columns, three launches per panel:
+//   k_chol_diag    factor the kCholNB x kCholNB diagonal block in LDS (one workgroup per matrix)
+//   k_chol_panel   rows below it: X L11^T = A21, one thread per row
+//   k_chol_update  trailing lower triangle -= L21 L21^T, 64 x 64 tiles
+// which: 0 -> order l, 1 -> order r.  T has leading dimension lp.  k_chol_shift first adds
+// shift_rel * trace(T) to the diagonal.  A non-positive pivot sets bit 2 of *status (the pivot is
+// replaced by 1).  Only the lower triangle is read and written.
+constexpr int kCholNB = 32;
 
-// which: 0 -> order l, 1 -> order r.  T has leading dimension lp.  shift_rel * trace(T) is added
-// to the diagonal first.  A non-positive pivot sets bit 2 of *status (the pivot is replaced by 1).
-__global__ __launch_bounds__(kCholThreads) void k_cholesky(const MatDev* __restrict__ mats, int which,
-                                                           double shift_rel, int* status) {
-    __shared__ double rowk[kCholMaxOrder];
-    __shared__ double red[16];
-    __shared__ double piv;
+__global__ __launch_bounds__(256) void k_chol_shift(const MatDev* __restrict__ mats, int which, double shift_rel) {
+    __shared__ double red[4];
     const MatDev& md = mats[blockIdx.x];
     const int nn = which == 0 ? md.l : md.r;
     const long long ld = md.lp;
     double* __restrict__ A = md.T;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    constexpr int NWV = kCholThreads / 64;
+    const int tid = threadIdx.x;
+    double tr = 0.0;
+    for (int i = tid; i < nn; i += 256) tr += A[i * ld + i];
+    tr = wave_sum_d(tr);
+    if ((tid & 63) == 0) red[tid >> 6] = tr;
+    __syncthreads();
+    const double shift = shift_rel * (((red[0] + red[1]) + red[2]) + red[3]);
+    for (int i = tid; i < nn; i += 256) A[i * ld + i] += shift;
+}
 
-    if (shift_rel > 0.0) {
-        double tr = 0.0;
-        for (int i = tid; i < nn; i += kCholThreads) tr += A[i * ld + i];
-        tr = wave_sum_d(tr);
-        if (lane == 0) red[wv] = tr;
-        __syncthreads();
-        double tot = 0.0;
-        for (int w = 0; w < NWV; ++w) tot += red[w];
-        const double shift = shift_rel * tot;
-        __syncthreads();
-        for (int i = tid; i < nn; i += kCholThreads) A[i * ld + i] += shift;
-        __syncthreads();
+__global__ __launch_bounds__(256) void k_chol_diag(const MatDev* __restrict__ mats, int which, int k0, int* status) {
+    __shared__ double D[kCholNB][kCholNB + 1];
+    const MatDev& md = mats[blockIdx.x];
+    const int nn = which == 0 ? md.l : md.r;
+    if (k0 >= nn) return;
+    const long long ld = md.lp;
+    double* __restrict__ A = md.T;
+    const int tid = threadIdx.x;
+    for (int q = tid; q < kCholNB * kCholNB; q += 256) {
+        const int i = q / kCholNB, j = q % kCholNB;
+        double v = i == j ? 1.0 : 0.0;            // identity padding past the matrix order
+        if (k0 + i < nn && j <= i) v = A[(long long)(k0 + i) * ld + k0 + j];
+        D[i][j] = v;
     }
-
+    __syncthreads();
     bool bad = false;
-    for (int k = 0; k < nn; ++k) {
-        for (int j = tid; j < k; j += kCholThreads) rowk[j] = A[(long long)k * ld + j];
-        __syncthreads();
-        // rows i >= k: A[i][k] -= sum_{j<k} L[i][j] L[k][j]
-        for (int i = k + wv; i < nn; i += NWV) {
-            const double* __restrict__ ri = A + (long long)i * ld;
-            double d = 0.0;
-            for (int j = lane; j < k; j += 64) d += ri[j] * rowk[j];
-            d = wave_sum_d(d);
-            if (lane == 0) {
-                const double v = ri[k] - d;
-                A[(long long)i * ld + k] = v;
-                if (i == k) piv = v;
-            }
-        }
-        __syncthreads();
-        double d = piv;
+    for (int k = 0; k < kCholNB; ++k) {
+        double d = D[k][k];
         if (!(d > 0.0) || !(d < 1.0e300)) {
             bad = true;
             d = 1.0;
         }
-        d = sqrt(d);
-        const double inv = 1.0 / d;
-        for (int i = k + tid; i < nn; i += kCholThreads) {
-            if (i == k) A[(long long)k * ld + k] = d;
-            else A[(long long)i * ld + k] *= inv;
+        const double rd = 1.0 / d;
+        // rank-one update of the columns right of k with the still unscaled column k
+        for (int q = tid; q < kCholNB * kCholNB; q += 256) {
+            const int i = q / kCholNB, j = q % kCholNB;
+            if (j > k && i >= j) D[i][j] -= D[i][k] * D[j][k] * rd;
         }
         __syncthreads();
+        // column k is final now and not read again: scale it
+        if (tid < kCholNB) {
+            const double sd = sqrt(d);
+            if (tid == k) D[k][k] = sd;
+            else if (tid > k) D[tid][k] *= 1.0 / sd;
+        }
+    }
+    __syncthreads();
+    for (int q = tid; q < kCholNB * kCholNB; q += 256) {
+        const int i = q / kCholNB, j = q % kCholNB;
+        if (k0 + i < nn && j <= i) A[(long long)(k0 + i) * ld + k0 + j] = D[i][j];
     }
     if (bad && tid == 0) atomicOr(status, 4);
 }
 
-hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shift_rel, int* status,
-                           hipStream_t stream) {
-    hipLaunchKernelGGL(k_cholesky, dim3(n_mats), dim3(kCholThreads), 0, stream, mats, which, shift_rel, status);
+__global__ __launch_bounds__(256) void k_chol_panel(const MatDev* __restrict__ mats, int which, int k0) {
+    __shared__ double Ls[kCholNB][kCholNB + 1];
+    __shared__ double invd[kCholNB];
+    const MatDev& md = mats[blockIdx.y];
+    const int nn = which == 0 ? md.l : md.r;
+    const int row0 = k0 + kCholNB + blockIdx.x * 256;
+    if (row0 >= nn) return;               // (then k0 + kCholNB < nn: all panel columns exist)
+    const long long ld = md.lp;
+    double* __restrict__ A = md.T;
+    const int tid = threadIdx.x;
+    for (int q = tid; q < kCholNB * kCholNB; q += 256) {
+        const int i = q / kCholNB, j = q % kCholNB;
+        Ls[i][j] = j <= i ? A[(long long)(k0 + i) * ld + k0 + j] : 0.0;
+    }
+    __syncthreads();
+    if (tid < kCholNB) invd[tid] = 1.0 / Ls[tid][tid];
+    __syncthreads();
+    const int i = row0 + tid;
+    if (i >= nn) return;
+    double* __restrict__ row = A + (long long)i * ld + k0;
+    double x[kCholNB];
+#pragma unroll
+    for (int j = 0; j < kCholNB; ++j) x[j] = row[j];
+#pragma unroll
+    for (int j = 0; j < kCholNB; ++j) {
+        double acc = x[j];
+#pragma unroll
+        for (int t = 0; t < j; ++t) acc -= x[t] * Ls[j][t];
+        x[j] = acc * invd[j];
+    }
+#pragma unroll
+    for (int j = 0; j < kCholNB; ++j) row[j] = x[j];
+}
+
+__global__ __launch_bounds__(256) void k_chol_update(const MatDev* __restrict__ mats, int which, int k0) {
+    __shared__ double As[64][kCholNB + 1];
+    __shared__ double Bs[64][kCholNB + 1];
+    if (blockIdx.y > blockIdx.x) return;  // lower triangle of tiles only
+    const MatDev& md = mats[blockIdx.z];
+    const int nn = which == 0 ? md.l : md.r;
+    const int base = k0 + kCholNB;
+    const int r0 = base + 64 * blockIdx.x, c0 = base + 64 * blockIdx.y;
+    if (r0 >= nn) return;
+    const long long ld = md.lp;
+    double* __restrict__ A = md.T;
+    const int tid = threadIdx.x;
+    for (int q = tid; q < 64 * kCholNB; q += 256) {
+        const int rr = q / kCholNB, t = q % kCholNB;
+        As[rr][t] = r0 + rr < nn ? A[(long long)(r0 + rr) * ld + k0 + t] : 0.0;
+        Bs[rr][t] = c0 + rr < nn ? A[(long long)(c0 + rr) * ld + k0 + t] : 0.0;
+    }
+    __syncthreads();
+    const int tx = tid & 15, ty = tid >> 4;   // outputs (ty + 16 e, tx + 16 f)
+    double acc[4][4] = {};
+#pragma unroll 4
+    for (int t = 0; t < kCholNB; ++t) {
+        double av[4], bv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            av[e] = As[ty + 16 * e][t];
+            bv[e] = Bs[tx + 16 * e][t];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int f = 0; f < 4; ++f) acc[e][f] += av[e] * bv[f];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const int i = r0 + ty + 16 * e, j = c0 + tx + 16 * f;
+            if (i < nn && j <= i) A[(long long)i * ld + j] -= acc[e][f];
+        }
+}
+
+hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, int max_order, double shift_rel,
+                           int* status, hipStream_t stream) {
+    if (shift_rel > 0.0)
+        hipLaunchKernelGGL(k_chol_shift, dim3(n_mats), dim3(256), 0, stream, mats, which, shift_rel);
+    for (int k0 = 0; k0 < max_order; k0 += kCholNB) {
+        hipLaunchKernelGGL(k_chol_diag, dim3(n_mats), dim3(256), 0, stream, mats, which, k0, status);
+        const int below = max_order - k0 - kCholNB;
+        if (below <= 0) break;
+        hipLaunchKernelGGL(k_chol_panel, dim3((below + 255) / 256, n_mats), dim3(256), 0, stream, mats, which, k0);
+        const int nt = (below + 63) / 64;
+        hipLaunchKernelGGL(k_chol_update, dim3(nt, nt, n_mats), dim3(256), 0, stream, mats, which, k0);
+    }
     return hipGetLastError();
 }
 
@@ -232,6 +322,28 @@ hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t str
     return hipGetLastError();
 }
 
+// v + (v of the partner lane under a DPP lane pattern).  Used with the symmetric patterns below, so
+// both partners form the same sum with the operands swapped and hold bit-identical results.
+template <int CTRL>
+__device__ __forceinline__ double dpp_pair_add(double v) {
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    const int plo = __builtin_amdgcn_mov_dpp(lo, CTRL, 0xf, 0xf, false);
+    const int phi = __builtin_amdgcn_mov_dpp(hi, CTRL, 0xf, 0xf, false);
+    return v + __hiloint2double(phi, plo);
+}
+// All-reduce over the 64 lanes; every lane ends with the same bits.  Lanes 1 and 2 apart are paired by
+// quad permutes, quads and half rows by the mirror patterns (a lane's partner holds the other
+// quad's / half's sum), the four 16-lane rows by two cross-lane exchanges.
+__device__ __forceinline__ double wave_allreduce(double v) {
+    v = dpp_pair_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_pair_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_pair_add<0x141>(v);   // row_half_mirror
+    v = dpp_pair_add<0x140>(v);   // row_mirror
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 // One wavefront per row pair (blockDim = 64 * jb): the two rows are held in registers between
 // the three dot products and the rotation (each lane owns SEG columns, lane-contiguous in LDS).
 // JB is the row-block size the kernel is compiled for (matrices with another jb are skipped: the
@@ -281,12 +393,9 @@ __global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restri
             be += vb[i] * vb[i];
             ga += va[i] * vb[i];
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            al += __shfl_xor(al, off, 64);
-            be += __shfl_xor(be, off, 64);
-            ga += __shfl_xor(ga, off, 64);
-        }
+        al = wave_allreduce(al);
+        be = wave_allreduce(be);
+        ga = wave_allreduce(ga);
         const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-20 * al * be);
         if (rot) {
             const double zeta = (be - al) / (2.0 * ga);

@@ -271,12 +271,12 @@ int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
 int orthonormalise(ng_state* st, bool is_a, bool twice, hipStream_t stream, const StepScalars& sc) {
     int rc;
     if ((rc = gemm(st, is_a ? OP_GRAM_A : OP_GRAM_B, stream, sc)) != NG_OK) return rc;
-    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 2e-7, st->d_status, stream));
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, st->max_l, 2e-7, st->d_status, stream));
     NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, st->max_l, stream));
     if ((rc = gemm(st, is_a ? OP_APPLY_A2C : OP_APPLY_B2C, stream, sc)) != NG_OK) return rc;
     if (!twice) return NG_OK;
     if ((rc = gemm(st, is_a ? OP_GRAM_CA : OP_GRAM_CB, stream, sc)) != NG_OK) return rc;
-    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, 0.0, st->d_status, stream));
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 0, st->max_l, 0.0, st->d_status, stream));
     NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 0, st->max_l, stream));
     if ((rc = gemm(st, is_a ? OP_APPLY_C2A : OP_APPLY_C2B, stream, sc)) != NG_OK) return rc;
     return NG_OK;
@@ -568,7 +568,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     if ((rc = gemm(st, OP_ROTATE, stream, sc)) != NG_OK) return rc;
     // one CholeskyQR pass on P (m x r) restores orthonormality to rounding level, then fix signs
     if ((rc = gemm(st, OP_GRAM_P, stream, sc)) != NG_OK) return rc;
-    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 1, 0.0, st->d_status, stream));
+    NG_HIP(launch_cholesky(st->d_mats, st->n_mats, 1, st->max_r, 0.0, st->d_status, stream));
     NG_HIP(launch_tri_inverse(st->d_mats, st->n_mats, 1, st->max_r, stream));
     if ((rc = gemm(st, OP_APPLY_P2A, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_sign_fix(st->d_mats, st->n_mats, st->max_r, stream));

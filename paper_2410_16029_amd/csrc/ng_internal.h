@@ -135,8 +135,8 @@ hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, in
 hipError_t launch_fill_gaussian(const MatDev* mats, int n_mats, int max_rows, unsigned long long seed,
                                 unsigned long long call_id, hipStream_t stream);   // fills Yb (n x l)
 // which: 0 -> order l (sketch), 1 -> order r (final P)
-hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, double shift_rel, int* status,
-                           hipStream_t stream);
+hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, int max_order, double shift_rel,
+                           int* status, hipStream_t stream);
 hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream);
 hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t stream);
 hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,

@@ -528,32 +528,12 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
 }
 
 // =================================================================== launchers
-// Tile configurations.  Default: 256 x 128 workgroup tiles (128 x 64 per wavefront); the
-// projection falls back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half
-// empty).  NG_GEMM_CFG (environment, read once) forces one configuration for experiments:
-// 0 = 128x128, 2 = 256x128, 6 = 256x256 with two LDS buffers (8 wavefronts).
+// Tile configurations: 256 x 128 workgroup tiles (128 x 64 per wavefront); the projection falls
+// back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half empty).
 typedef Cfg<128, 128, 64, 64, 64> Cfg0;
 typedef Cfg<256, 128, 128, 64, 64> Cfg2;
-typedef Cfg<256, 256, 128, 64, 64, true> Cfg6;
 
-static int forced_cfg() {
-    static int cfg = -2;
-    if (cfg == -2) {
-        const char* e = getenv("NG_GEMM_CFG");
-        cfg = e ? atoi(e) : -1;
-        if (cfg != 0 && cfg != 2 && cfg != 6) cfg = -1;
-    }
-    return cfg;
-}
-static int project_cfg(int max_r) {
-    const int f = forced_cfg();
-    if (f >= 0) return f;
-    return max_r > 128 ? 2 : 0;
-}
-static int update_cfg() {
-    const int f = forced_cfg();
-    return f >= 0 ? f : 2;
-}
+static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
 
 template <class C>
 static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
@@ -584,31 +564,21 @@ static hipError_t run_update(const MatDev* mats, const MatDyn* dyn, const TileRe
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                                int max_r, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    switch (project_cfg(max_r)) {
-        case 0: return run_project<Cfg0>(mats, dyn, tiles, n_tiles, stream);
-        case 6: return run_project<Cfg6>(mats, dyn, tiles, n_tiles, stream);
-        default: return run_project<Cfg2>(mats, dyn, tiles, n_tiles, stream);
-    }
+    if (project_cfg(max_r) == 0) return run_project<Cfg0>(mats, dyn, tiles, n_tiles, stream);
+    return run_project<Cfg2>(mats, dyn, tiles, n_tiles, stream);
 }
 
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    switch (update_cfg()) {
-        case 0: return run_update<Cfg0>(mats, dyn, tiles, n_tiles, sc, stream);
-        case 6: return run_update<Cfg6>(mats, dyn, tiles, n_tiles, sc, stream);
-        default: return run_update<Cfg2>(mats, dyn, tiles, n_tiles, sc, stream);
-    }
+    return run_update<Cfg2>(mats, dyn, tiles, n_tiles, sc, stream);
 }
 
 // which: 0 = projection (needs the largest rank of the layer set), 1 = update
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
-    const int c = which == 0 ? project_cfg(max_r) : update_cfg();
-    switch (c) {
-        case 0: *bm = Cfg0::BM; *bn = Cfg0::BN; break;
-        case 6: *bm = Cfg6::BM; *bn = Cfg6::BN; break;
-        default: *bm = Cfg2::BM; *bn = Cfg2::BN; break;
-    }
+    const bool small = which == 0 && project_cfg(max_r) == 0;
+    *bm = small ? Cfg0::BM : Cfg2::BM;
+    *bn = small ? Cfg0::BN : Cfg2::BN;
 }
 
 }  // namespace ng

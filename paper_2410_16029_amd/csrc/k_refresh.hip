@@ -396,7 +396,7 @@ __global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restri
         al = wave_allreduce(al);
         be = wave_allreduce(be);
         ga = wave_allreduce(ga);
-        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-20 * al * be);
+        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-15 * al * be);
         if (rot) {
             const double zeta = (be - al) / (2.0 * ga);
             const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));

@@ -2,6 +2,8 @@
 the same bytes and report per-tensor errors  max|x - x_oracle| / max|x_oracle|."""
 from __future__ import annotations
 
+import dataclasses
+
 import numpy as np
 import torch
 
@@ -75,9 +77,11 @@ class Lockstep:
         GPU's N against the oracle's direction formula applied to the GPU's own M and V.
         "N" and "N_far_frac" (elements off by more than tol) are reported, not asserted.
         The weight update is pinned by "W" free-running and by the oracle's update formula fed
-        with the GPU's own N: "dW" (fp32 weights) or, for bf16 weights, "W_upd_excess": the
-        difference from that expectation in units of (one bf16 step at the element's
-        magnitude + tol * max|dW|), which must not exceed 1."""
+        with the GPU's own N: "dW" (fp32 weights) or, for bf16 weights, "W_round_viol_frac":
+        with x the unrounded fp64 update and d = tol * max|dW|, the stored bf16 weight must lie
+        between round(x - d) and round(x + d), i.e. be the correct rounding of a value within
+        the GEMM tolerance of x; the fraction of elements outside must be 0.  ("W_upd_excess"
+        and "W_mismatch_frac" -- distance from, and inequality with, round(x) -- are reported.)"""
         ls = self.ls
         slot = {i: ls.counters(i)[1] for i in self.check}
         prev = {i: (self.states[i].M.copy(), self.states[i].V.copy(), to_f64(weights[i])) for i in self.check}
@@ -120,6 +124,10 @@ class Lockstep:
                 dmax = np.max(np.abs(W_expect - Wp))
                 e["W_upd_excess"] = float(np.max(np.abs(Wg - W_expect) / (step_bf16 + self.tol * dmax)))
                 e["W_mismatch_frac"] = float(np.mean(Wg != W_expect))
+                x = oracle.back_project_update(Wp, st.P, Ng, lr, dataclasses.replace(self.ohp, weight_dtype="f32"))
+                d = self.tol * dmax
+                lo, hi = oracle.round_to_bf16(x - d), oracle.round_to_bf16(x + d)
+                e["W_round_viol_frac"] = float(np.mean((Wg < lo) | (Wg > hi)))
             else:
                 e["dW"] = rel_err(Wg - Wp, W_expect - Wp)
             t, head, count, nref = ls.counters(i)

@@ -1,0 +1,118 @@
+"""GPU parity on the degenerate and extreme cases of the step: strided operands, full rank,
+ranks and widths that are not multiples of the tile or vector sizes, the largest history, and
+the full 1.1B layer set in the launch configuration the benchmark times (sampled matrices)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_16029_amd import binding as B
+from paper_2410_16029_amd import workloads
+from parity_harness import Lockstep, summarize, worst
+from test_gpu_parity import DEV, TOL_BF16, TOL_F32, _assert_all
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pad_g=0, **kw):
+    """Free-running lockstep; with pad_w / pad_g the weights / gradients are column slices of
+    wider tensors (leading dimension larger than n) whose remaining columns must stay untouched."""
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    stream = workloads.TorchGradientStream(shapes, k, 0.01, seed, dtype, DEV)
+    W0 = workloads.torch_weights(shapes, seed, dtype, DEV)
+    ld_w = ld_g = None
+    Wfull = None
+    if pad_w:
+        Wfull = [torch.full((m, n + pad_w), 7.0, dtype=w.dtype, device=DEV) for (m, n), w in zip(shapes, W0)]
+        for wf, w, (m, n) in zip(Wfull, W0, shapes):
+            wf[:, :n] = w
+        W = [wf[:, :n] for wf, (m, n) in zip(Wfull, shapes)]
+        ld_w = [n + pad_w for (m, n) in shapes]
+    else:
+        W = W0
+    if pad_g:
+        ld_g = [n + pad_g for (m, n) in shapes]
+    ls = B.LayerSet(shapes, r, s=s, dtype=dtype, device=DEV, ld_w=ld_w, ld_g=ld_g, **kw)
+    lk = Lockstep(ls, check=check, tol=tol)
+    lk.set_weights(W)
+    errs = []
+    for step in range(steps):
+        G = stream.next_set()
+        if pad_g:
+            Gfull = [torch.full((m, n + pad_g), float("nan"), dtype=g.dtype, device=DEV)
+                     for (m, n), g in zip(shapes, G)]
+            for gf, g, (m, n) in zip(Gfull, G, shapes):
+                gf[:, :n] = g
+            G = [gf[:, :n] for gf, (m, n) in zip(Gfull, shapes)]
+        if step == 0:
+            lk.refresh(G)
+            assert ls.status() == B.NG_OK
+        errs.append(lk.step(G, W, lr))
+    assert ls.status() == B.NG_OK
+    if Wfull is not None:
+        for wf, (m, n) in zip(Wfull, shapes):
+            assert bool((wf[:, n:] == 7.0).all()), "columns beyond n of a strided weight were written"
+    return ls, errs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_weights_and_gradients(dtype):
+    # leading dimensions larger than n; the gradient's extra columns hold NaN and must not be read
+    shapes = [(130, 75), (64, 200), (300, 257)]
+    ls, errs = _run(shapes, 16, 3, dtype, 5, seed=41, pad_w=5, pad_g=3)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "strided " + dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_full_rank_projector(dtype):
+    # r = min(m, n): the projector is a full orthogonal basis of the shorter side.  The synthetic
+    # gradient has full rank too, so that no row of R is pure noise (the direction N of such rows
+    # is a sign, which no tolerance covers).
+    shapes = [(48, 80), (72, 40)]
+    descs_r = [48, 40]
+    ls, errs = _run(shapes, descs_r, 2, dtype, 4, seed=43, k=48)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "full rank " + dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_odd_ranks_and_narrow_matrices(dtype):
+    # ranks that are not multiples of 8, fewer columns than one vector, a single row block
+    # (gradient rank above every r: no pure-noise rows in R, see test_full_rank_projector)
+    shapes = [(40, 5), (33, 7), (200, 9), (9, 120), (257, 31)]
+    ranks = [3, 5, 7, 4, 20]
+    ls, errs = _run(shapes, ranks, 3, dtype, 5, seed=47, k=24)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "odd ranks " + dtype)
+
+
+def test_rank_one():
+    ls, errs = _run([(64, 96), (17, 33)], 1, 4, "f32", 6, seed=53, k=2)
+    _assert_all(errs, TOL_F32, "rank one")
+
+
+def test_largest_history_wraps_around():
+    # s = 64 is the largest history the library accepts; 67 steps wrap the ring
+    ls, errs = _run([(64, 96)], 8, 64, "f32", 67, seed=59, k=8)
+    _assert_all(errs, TOL_F32, "s=64")
+    assert ls.counters(0) == (67, 3, 64, 1)
+
+
+def test_mixed_ranks_in_one_layer_set_bf16():
+    # per-matrix ranks across the 128 threshold that selects the projection tile shape
+    shapes = [(384, 520), (256, 300), (520, 384)]
+    ranks = [160, 24, 128]
+    ls, errs = _run(shapes, ranks, 4, "bf16", 6, seed=61, k=16)
+    _assert_all(errs, TOL_BF16, "mixed ranks")
+
+
+def test_full_1b_layer_set_sampled():
+    """All 168 matrices of the 1.1B configuration in one layer set (the grouped launches, tile
+    tables and history size the benchmark times); the oracle follows one matrix of each shape
+    from the first and the last transformer block."""
+    cfg = workloads.CONFIGS["c5"]
+    shapes = cfg.matrices()
+    assert len(shapes) == 168
+    check = [0, 4, 6, 161, 165, 167]
+    assert {shapes[i] for i in check} == set(shapes)
+    ls, errs = _run(shapes, cfg.r, cfg.s, cfg.dtype, 2, seed=cfg.seed, k=cfg.k, check=check, lr=cfg.lr)
+    _assert_all(errs, TOL_BF16, "c5 full")
+    for i in (0, 83, 167):
+        assert ls.counters(i) == (2, 2, 2, 1)

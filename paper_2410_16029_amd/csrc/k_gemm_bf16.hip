@@ -5,18 +5,18 @@
 //                    B = G   [m][ld_g] (caller's gradient: contraction index is the ROW, so the tile
 //                                       is transposed in registers on its way into LDS)
 //                    C -> ring slot `head` of H, float [r][ldn]
-//   k_update_bf16    W <- W - lr (scale P N + wd W)   (paper Sec. 2.2, update equation)
+//   k_update_bf16_dl W <- W - lr (scale P N + wd W)   (paper Sec. 2.2, update equation)
 //                    A = Pb [m][ldr], B = N in the octet layout [r/8][ldn][8] written by the
-//                    transform+Adam kernel (already k-packed: no transpose), epilogue
-//                    read-modify-writes W through an LDS-staged tile so every lane touches 16
-//                    contiguous bytes of a weight row.
+//                    transform+Adam kernel (both k-packed: 16-byte chunks go from memory straight
+//                    into LDS, no register pass), epilogue read-modify-writes W through an
+//                    LDS-staged tile so every lane touches 16 contiguous bytes of a weight row.
 //
 // v_mfma_f32_32x32x16_bf16: lane L supplies 8 bf16 of A row (L%32) and 8 bf16 of B column (L%32),
 // both for the k-slots 8*(L/32)..+7 of the 16-deep step (any k assignment works as long as A and B
 // agree); accumulator index 4*g+e of lane L is D[8*g + 4*(L/32) + e][L%32].
 //
-// LDS tiles are [row][BK + 8] bf16: the 16-byte pad makes the 16-byte fragment reads of 16
-// consecutive rows hit disjoint banks.
+// LDS tiles of the projection are [row][BK + 8] bf16: the 16-byte pad makes the 16-byte fragment
+// reads of 16 consecutive rows hit disjoint banks.
 //
 // Memory access rules followed here (each was measured to matter):
 //   * every pointer read out of a table is cast to the global address space, so loads are
@@ -26,8 +26,6 @@
 //     or a select right after the load, makes the compiler wait for the load before the MFMAs
 //     of the current tile instead of after them;
 //   * offsets are 32-bit (the host checks that every matrix is below 2 GiB).
-#include <stdlib.h>
-
 #include "ng_internal.h"
 
 namespace ng {
@@ -60,23 +58,20 @@ __device__ __forceinline__ u32x4_t zero_unless(bool ok, u32x4_t v) {
     return v;
 }
 
-template <int BM_, int BN_, int WM_, int WN_, int BK_, bool DB_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int BK_>
 struct Cfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_;
-    static constexpr bool DB = DB_;                         // two LDS operand buffers, one barrier per k-step
     static constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN, NT = NW * 64;
     static constexpr int MI = WM / 32, NJ = WN / 32;
     static constexpr int LDS_K = BK + 8;                    // bf16 elements per LDS row
     static constexpr int KC = BK / 8;                       // 16-byte chunks per row
     static constexpr int KG = BK / 4;                       // 4-row groups of the transposed operand
     static constexpr int A_CHUNKS = BM * KC / NT;           // per thread
-    static constexpr int BN8_CHUNKS = BN * KC / NT;         // per thread, octet-layout B
     static constexpr int BT_BLOCKS = KG * (BN / 8) / NT;    // per thread, transposing B: 4k x 8j blocks
     static constexpr int OPER_BYTES = (BM + BN) * LDS_K * 2;
     static constexpr int LDC = BN + 8;                      // floats per staged C row
     static constexpr int STAGE_BYTES = NWM * 32 * LDC * 4;
-    static constexpr int OPER_TOTAL = DB ? 2 * OPER_BYTES : OPER_BYTES;
-    static constexpr int LDS_BYTES = OPER_TOTAL > STAGE_BYTES ? OPER_TOTAL : STAGE_BYTES;
+    static constexpr int LDS_BYTES = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
     static_assert(BM * KC % NT == 0 && BN * KC % NT == 0 && KG * (BN / 8) % NT == 0, "tile/thread mismatch");
     static_assert(NT % KC == 0 && NT % BN == 0 && NT % KG == 0, "per-thread invariants");
 };
@@ -119,47 +114,6 @@ struct ALoader {
             const int c = t + C::NT * p;
             const bool ok = kok && ((rowok >> p) & 1u);
             *reinterpret_cast<u32x4_t*>(As + (c / C::KC) * C::LDS_K + (c % C::KC) * 8) = zero_unless(ok, r[p]);
-        }
-    }
-};
-
-// ------------------------------------------------------------------ B operand, octet layout
-// N8 [k/8][ldn][8].  Chunk c = t + NT*p: column c % BN (the same for every p), octet c / BN.
-template <class C>
-struct B8Loader {
-    gbf16_cptr base;
-    unsigned joff, ldn8;
-    int roct, oct_t;
-    bool jok;
-    unsigned okmask;
-    u32x4_t r[C::BN8_CHUNKS];
-
-    __device__ __forceinline__ void init(const bf16_t* N8, int ldn, int roct_, int j0, int t) {
-        base = (gbf16_cptr)N8;
-        const int j = j0 + t % C::BN;
-        jok = j < ldn;
-        joff = (unsigned)(jok ? j : ldn - 1) * 8u;
-        ldn8 = (unsigned)ldn * 8u;
-        roct = roct_;
-        oct_t = t / C::BN;
-    }
-    __device__ __forceinline__ void load(int k0) {
-        okmask = 0;
-#pragma unroll
-        for (int p = 0; p < C::BN8_CHUNKS; ++p) {
-            const int oct = (k0 >> 3) + oct_t + (C::NT / C::BN) * p;
-            const bool ok = jok && oct < roct;
-            okmask |= ok ? (1u << p) : 0u;
-            const unsigned oc = (unsigned)(oct < roct ? oct : roct - 1);
-            r[p] = *(const NG_AS1 u32x4_t*)(base + (oc * ldn8 + joff));
-        }
-    }
-    __device__ __forceinline__ void store(bf16_t* Bs, int t) const {
-#pragma unroll
-        for (int p = 0; p < C::BN8_CHUNKS; ++p) {
-            const int c = t + C::NT * p;
-            *reinterpret_cast<u32x4_t*>(Bs + (c % C::BN) * C::LDS_K + (c / C::BN) * 8) =
-                zero_unless((okmask >> p) & 1u, r[p]);
         }
     }
 };
@@ -308,63 +262,30 @@ struct BTView {
 };
 
 // Main loop over the contraction.  LA / LB: load(k0) issues the global loads of one BK-deep
-// tile into registers, store(ptr, t) writes them (masked) to LDS.
-//   single buffer: loads of tile kt+1 are in flight during the MFMAs of tile kt; two barriers.
-//   double buffer: registers hold tile kt+1 (loaded one whole step earlier); they are written to
-//   the other LDS buffer while tile kt is multiplied, then the loads of tile kt+2 are issued;
-//   one barrier per step.
+// tile into registers, store(ptr, t) writes them (masked) to LDS.  The loads of tile kt+1 are in
+// flight during the MFMAs of tile kt; two barriers per k-step.
 template <class C, class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(floatx16 (&acc)[C::MI][C::NJ], LA& la, LB& lb, unsigned char* smem,
                                               int nk, int t, int wm, int wn, int li, int h) {
     bf16_t* As0 = reinterpret_cast<bf16_t*>(smem);
     bf16_t* Bs0 = As0 + C::BM * C::LDS_K;
-    if (!C::DB) {
-        la.load(0);
-        lb.load(0);
-        la.store(As0, t);
-        lb.store(Bs0, t);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            if (kt + 1 < nk) {
-                la.load((kt + 1) * C::BK);
-                lb.load((kt + 1) * C::BK);
-            }
-            mma_tile<C>(acc, As0, Bs0, wm, wn, li, h);
-            __syncthreads();
-            if (kt + 1 < nk) {
-                la.store(As0, t);
-                lb.store(Bs0, t);
-            }
-            __syncthreads();
+    la.load(0);
+    lb.load(0);
+    la.store(As0, t);
+    lb.store(Bs0, t);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) {
+            la.load((kt + 1) * C::BK);
+            lb.load((kt + 1) * C::BK);
         }
-    } else {
-        bf16_t* As1 = reinterpret_cast<bf16_t*>(smem + C::OPER_BYTES);
-        bf16_t* Bs1 = As1 + C::BM * C::LDS_K;
-        la.load(0);
-        lb.load(0);
-        la.store(As0, t);
-        lb.store(Bs0, t);
-        if (nk > 1) {
-            la.load(C::BK);
-            lb.load(C::BK);
+        mma_tile<C>(acc, As0, Bs0, wm, wn, li, h);
+        __syncthreads();
+        if (kt + 1 < nk) {
+            la.store(As0, t);
+            lb.store(Bs0, t);
         }
         __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            bf16_t* Ac = (kt & 1) ? As1 : As0;
-            bf16_t* Bc = (kt & 1) ? Bs1 : Bs0;
-            bf16_t* An = (kt & 1) ? As0 : As1;
-            bf16_t* Bn = (kt & 1) ? Bs0 : Bs1;
-            if (kt + 1 < nk) {
-                la.store(An, t);
-                lb.store(Bn, t);
-            }
-            if (kt + 2 < nk) {
-                la.load((kt + 2) * C::BK);
-                lb.load((kt + 2) * C::BK);
-            }
-            mma_tile<C>(acc, Ac, Bc, wm, wn, li, h);
-            __syncthreads();
-        }
     }
 }
 
@@ -418,60 +339,44 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
 }
 
 // =================================================================== update
+// Epilogue of the update: accumulators -> LDS (float), one 32-row block of every wave-row at a
+// time, then each thread read-modify-writes 8 consecutive bf16 of one weight row.
 template <class C>
-__global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict__ mats,
-                                                       const MatDyn* __restrict__ dyn,
-                                                       const TileRef* __restrict__ tiles, StepScalars sc) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float* Cs = reinterpret_cast<float*>(smem);
-
-    const TileRef tr = tiles[blockIdx.x];
-    if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
-    const MatDev& md = mats[tr.mat];
-    const MatDyn dy = dyn[tr.mat];
-    const int i0 = tr.ti * C::BM, j0 = tr.tj * C::BN;
-    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    const int wm = wv / C::NWN, wn = wv % C::NWN, li = lane & 31, h = lane >> 5;
-    const int m = md.m, n = md.n, ldn = md.ldn;
-    const int kdim = md.roct * 8;
-
-    floatx16 acc[C::MI][C::NJ];
-    zero_acc<C>(acc);
-
-    ALoader<C> la;
-    B8Loader<C> lb;
-    la.init(md.Pb, md.ldr, i0, m, md.ldr, t);
-    lb.init(reinterpret_cast<const bf16_t*>(md.N), ldn, md.roct, j0, t);
-    const int nk = (kdim + C::BK - 1) / C::BK;
-    NG_AS1 bf16_t* W = (NG_AS1 bf16_t*)dy.w;
-    const unsigned ld_w = (unsigned)md.ld_w;
-    gemm_mainloop<C>(acc, la, lb, smem, nk, t, wm, wn, li, h);
-    if (C::DB) __syncthreads();   // (the single-buffer loop already ends on a barrier)
-
-    // Epilogue, one 32-row block of every wave-row at a time: accumulators -> LDS (float),
-    // then each thread read-modify-writes 8 consecutive bf16 of one weight row.
-    constexpr int ROWS = C::NWM * 32;
-    constexpr int CH = C::BN / 8;                         // 8-column chunks per row
-    constexpr int PER_T = ROWS * CH / C::NT;
+struct UpdateTile {
+    static constexpr int ROWS = C::NWM * 32;
+    static constexpr int CH = C::BN / 8;                         // 8-column chunks per row
+    static constexpr int PER_T = ROWS * CH / C::NT;
     static_assert(ROWS * CH % C::NT == 0, "epilogue mapping");
-    const bool cols_full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
-    // All weight loads of the tile are issued up front (the main loop's staging registers are
-    // free now), so the HBM latency is paid once per tile, not once per pass.
-    u32x4_t wv4[C::MI][PER_T];
-    if (cols_full) {
+};
+
+// Loads the whole weight tile (8 bf16 per chunk, clamped addresses) -- issued before the main
+// loop, so the HBM latency and bandwidth of the weight read overlap the contraction.
+template <class C>
+__device__ __forceinline__ void update_load_w(u32x4_t (&wv4)[C::MI][UpdateTile<C>::PER_T], const NG_AS1 bf16_t* W,
+                                              unsigned ld_w, int m, int n, int i0, int j0, int t) {
+    constexpr int CH = UpdateTile<C>::CH, PER_T = UpdateTile<C>::PER_T;
 #pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi)
+    for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
-            for (int p = 0; p < PER_T; ++p) {
-                const int q = t + C::NT * p;
-                const int lr = q / CH, cc = q % CH;
-                const int row = i0 + (lr / 32) * C::WM + mi * 32 + (lr % 32);
-                const int col = j0 + cc * 8;
-                const unsigned rc = (unsigned)(row < m ? row : m - 1);
-                const unsigned jc = (unsigned)((col + 8 <= n) ? col : n - 8);
-                wv4[mi][p] = *(const NG_AS1 u32x4_a2*)(W + (rc * ld_w + jc));
-            }
-    }
+        for (int p = 0; p < PER_T; ++p) {
+            const int q = t + C::NT * p;
+            const int lr = q / CH, cc = q % CH;
+            const int row = i0 + (lr / 32) * C::WM + mi * 32 + (lr % 32);
+            const int col = j0 + cc * 8;
+            const unsigned rc = (unsigned)(row < m ? row : m - 1);
+            const unsigned jc = (unsigned)((col + 8 <= n) ? col : n - 8);
+            // read once, written once: streamed through the L2 so it does not evict the operand panels
+            wv4[mi][p] = __builtin_nontemporal_load((const NG_AS1 u32x4_a2*)(W + (rc * ld_w + jc)));
+        }
+}
+
+template <class C>
+__device__ __forceinline__ void update_epilogue(floatx16 (&acc)[C::MI][C::NJ],
+                                                u32x4_t (&wv4)[C::MI][UpdateTile<C>::PER_T], bool cols_full,
+                                                float* Cs, NG_AS1 bf16_t* W, unsigned ld_w, int m, int n, int i0,
+                                                int j0, int t, int wm, int wn, int li, int h,
+                                                const StepScalars& sc) {
+    constexpr int CH = UpdateTile<C>::CH, PER_T = UpdateTile<C>::PER_T;
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi) {
 #pragma unroll
@@ -502,7 +407,8 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
                     const float n1 = w1 - (sc.lr_scale * cv[2 * d + 1] + sc.lr_wd * w1);
                     ov[d] = pack_bf16x2(n0, n1);
                 }
-                if (row < m && col + 8 <= n) *(NG_AS1 u32x4_a2*)(W + ((unsigned)row * ld_w + (unsigned)col)) = ov;
+                if (row < m && col + 8 <= n)
+                    __builtin_nontemporal_store(ov, (NG_AS1 u32x4_a2*)(W + ((unsigned)row * ld_w + (unsigned)col)));
             }
         } else {
 #pragma unroll
@@ -527,6 +433,167 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16(const MatDev* __restrict_
     }
 }
 
+// =================================================================== update, operands loaded straight into LDS
+// Both operands of the update are stored k-packed (Pb rows, the octet layout of N), so a 16-byte
+// chunk in memory is exactly one MFMA fragment and no register pass is needed:
+// global_load_lds_dwordx4 moves 16 bytes per lane into LDS (lane L of a wavefront writes at
+// wave base + 16 L; M0 carries the base).  DBK-deep stages in a ring of NST: the loads of the next
+// NST-1 stages are in flight while one stage is multiplied; one barrier per stage.
+//   A stage: slot(row, kc) = row * KC + (kc ^ swz(row)), 16 bytes per slot, KC = DBK/8 chunks per
+//            row; the XOR spreads the fragment reads of consecutive rows over the banks while the
+//            global side stays coalesced (KC lanes cover the contiguous bytes of one row)
+//   B stage: slot(kc, col) = kc * BN + col  (64 consecutive columns of one octet per instruction)
+// A chunk outside the matrix (row >= m, k >= ldr, octet >= roct, column >= ldn) is fetched from a
+// 16-byte block of zeros instead.  The stage ring (NST * (BM + BN) * DBK * 2 bytes) is sized so that
+// two workgroups share a CU: one is in its HBM-bound epilogue while the other multiplies.
+#define NG_AS3 __attribute__((address_space(3)))
+
+template <class C, int DBK, int NST>
+struct DlCfg {
+    static constexpr int KC = DBK / 8;
+    static constexpr int A_BYTES = C::BM * DBK * 2, B_BYTES = C::BN * DBK * 2, STAGE = A_BYTES + B_BYTES;
+    static constexpr int A_INSTR = C::BM * KC / C::NT, B_INSTR = C::BN * KC / C::NT;
+    static constexpr int RING = NST * STAGE;
+    static constexpr int LDS_BYTES = RING > C::STAGE_BYTES ? RING : C::STAGE_BYTES;
+    static_assert(DBK == 32 || DBK == 64, "4 or 8 chunks per row");
+    static_assert(C::BM * KC % C::NT == 0 && C::BN * KC % C::NT == 0 && C::BN % 64 == 0, "chunk mapping");
+    static_assert(A_INSTR + B_INSTR <= 15, "the wait count of one stage must fit the counter");
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // at most N vector-memory loads still in flight
+    static_assert(N >= 0 && N <= 15, "low counter bits only");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);       // expcnt 7, lgkmcnt 15: not waited for
+}
+
+template <class C, int DBK, int NST>
+__global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restrict__ mats,
+                                                          const MatDyn* __restrict__ dyn,
+                                                          const TileRef* __restrict__ tiles, StepScalars sc,
+                                                          const void* zero16) {
+    typedef DlCfg<C, DBK, NST> D;
+    constexpr int KC = D::KC, KK = DBK / 16;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const TileRef tr = tiles[blockIdx.x];
+    if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
+    const MatDev& md = mats[tr.mat];
+    const MatDyn dy = dyn[tr.mat];
+    const int i0 = tr.ti * C::BM, j0 = tr.tj * C::BN;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wv / C::NWN, wn = wv % C::NWN, li = lane & 31, h = lane >> 5;
+    const int m = md.m, n = md.n, ldn = md.ldn, ldr = md.ldr, roct = md.roct;
+    const int nk = (roct * 8 + DBK - 1) / DBK;
+
+    floatx16 acc[C::MI][C::NJ];
+    zero_acc<C>(acc);
+
+    const NG_AS1 unsigned char* zp = (const NG_AS1 unsigned char*)zero16;
+    // A chunks: wave-instruction q = p * NW + wv covers slots 64 q .. 64 q + 63 = 64 / KC rows
+    constexpr int RPI = 64 / KC;                              // rows per wave-instruction
+    const int lrow = lane / KC;                               // row within the instruction
+    const int kcA = KC == 8 ? ((lane & 7) ^ (lrow & 7)) : ((lane & 3) ^ ((lrow >> 2) & 3));
+    const NG_AS1 unsigned char* a_ptr[D::A_INSTR];
+    unsigned a_ok = 0;
+#pragma unroll
+    for (int p = 0; p < D::A_INSTR; ++p) {
+        const int row = i0 + (p * C::NW + wv) * RPI + lrow;
+        const bool ok = row < m;
+        a_ok |= ok ? (1u << p) : 0u;
+        a_ptr[p] = (const NG_AS1 unsigned char*)md.Pb + ((long long)(ok ? row : 0) * ldr + kcA * 8) * 2;
+    }
+    // B chunks: wave-instruction q covers octet q / (BN/64), columns (q % (BN/64)) * 64 + lane
+    const NG_AS1 unsigned char* b_ptr[D::B_INSTR];
+    int b_oct[D::B_INSTR];
+    bool b_colok[D::B_INSTR];
+#pragma unroll
+    for (int p = 0; p < D::B_INSTR; ++p) {
+        const int q = p * C::NW + wv;
+        const int col = j0 + (q % (C::BN / 64)) * 64 + lane;
+        b_oct[p] = q / (C::BN / 64);
+        b_colok[p] = col < ldn;
+        b_ptr[p] = (const NG_AS1 unsigned char*)md.N + ((long long)b_oct[p] * ldn + (b_colok[p] ? col : 0)) * 16;
+    }
+    const long long b_step = (long long)ldn * KC * 16;   // KC octets per stage
+
+    auto issue = [&](int kt) {
+        unsigned char* stage = smem + (kt % NST) * D::STAGE;
+        const bool kokA = kt * DBK + kcA * 8 < ldr;
+#pragma unroll
+        for (int p = 0; p < D::A_INSTR; ++p) {
+            const bool ok = kokA && ((a_ok >> p) & 1u);
+            const NG_AS1 unsigned char* g = ok ? a_ptr[p] + (long long)kt * (DBK * 2) : zp;
+            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g,
+                                             (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int p = 0; p < D::B_INSTR; ++p) {
+            const bool ok = b_colok[p] && (kt * KC + b_oct[p] < roct);
+            const NG_AS1 unsigned char* g = ok ? b_ptr[p] + kt * b_step : zp;
+            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g,
+                                             (NG_AS3 void*)(stage + D::A_BYTES + (p * C::NW + wv) * 1024), 16, 0, 0);
+        }
+    };
+
+    // fragment addresses inside a stage
+    const int a_row = wm * C::WM + li;                       // + 32 mi
+    const int a_sw = KC == 8 ? (li & 7) : ((li >> 2) & 3);
+    const int b_col = wn * C::WN + li;                       // + 32 nj
+
+    // Ring: stage kt lives in buffer kt % NST.  Before stage kt is multiplied, the loads of the
+    // stages up to kt + NST - 2 have been issued; waiting until at most (NST - 2) stages' worth of
+    // this lane's loads are in flight means stage kt has landed (loads complete in order).  The
+    // barrier that follows also tells everyone that buffer (kt - 1) % NST is free, which is where
+    // stage kt + NST - 1 goes.
+    constexpr int PER_STAGE = D::A_INSTR + D::B_INSTR;
+    static_assert(NST == 2 || NST == 3, "ring depth");
+    for (int q = 0; q < NST - 1; ++q)
+        if (q < nk) issue(q);
+    for (int kt = 0; kt < nk; ++kt) {
+        if (NST == 3 && kt + 1 < nk) wait_vmcnt<PER_STAGE>();
+        else wait_vmcnt<0>();
+        // A bare barrier: __syncthreads() would also fence, i.e. wait for the loads just issued.
+        // Each wave's fragment reads of the previous stage were consumed by its MFMAs before it
+        // arrives here, so the buffer that is refilled next is no longer being read.
+        asm volatile("s_barrier" ::: "memory");
+        if (kt + NST - 1 < nk) issue(kt + NST - 1);
+        const unsigned char* cur = smem + (kt % NST) * D::STAGE;
+        u32x4_t a[KK][C::MI], b[KK][C::NJ];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const int ks = 2 * kk + h;
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+                a[kk][mi] = *reinterpret_cast<const u32x4_t*>(cur + ((a_row + 32 * mi) * KC + (ks ^ a_sw)) * 16);
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj)
+                b[kk][nj] = *reinterpret_cast<const u32x4_t*>(cur + D::A_BYTES + (ks * C::BN + b_col + 32 * nj) * 16);
+        }
+        // all fragment reads of the stage are issued before the first MFMA (left alone, the
+        // scheduler reuses a few registers and alternates 4 reads - full wait - 4 MFMAs)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+                for (int nj = 0; nj < C::NJ; ++nj)
+                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8_t*>(&a[kk][mi]), *reinterpret_cast<const bf16x8_t*>(&b[kk][nj]),
+                        acc[mi][nj], 0, 0, 0);
+    }
+    __syncthreads();   // every wave is done with the ring: the epilogue stages C through the same LDS
+
+    NG_AS1 bf16_t* W = (NG_AS1 bf16_t*)dy.w;
+    const unsigned ld_w = (unsigned)md.ld_w;
+    const bool cols_full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
+    u32x4_t wv4[C::MI][UpdateTile<C>::PER_T];
+    if (cols_full) update_load_w<C>(wv4, W, ld_w, m, n, i0, j0, t);
+    update_epilogue<C>(acc, wv4, cols_full, reinterpret_cast<float*>(smem), W, ld_w, m, n, i0, j0, t, wm, wn, li, h,
+                       sc);
+}
+
 // =================================================================== launchers
 // Tile configurations: 256 x 128 workgroup tiles (128 x 64 per wavefront); the projection falls
 // back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half empty).
@@ -548,19 +615,6 @@ static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileR
     return hipGetLastError();
 }
 
-template <class C>
-static hipError_t run_update(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                             StepScalars sc, hipStream_t stream) {
-    static bool attr = false;
-    if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_bf16<C>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        attr = true;
-    }
-    hipLaunchKernelGGL(k_update_bf16<C>, dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn, tiles, sc);
-    return hipGetLastError();
-}
-
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                                int max_r, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
@@ -569,9 +623,20 @@ hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const Tile
 }
 
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                              StepScalars sc, hipStream_t stream) {
+                              StepScalars sc, const void* zero16, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    return run_update<Cfg2>(mats, dyn, tiles, n_tiles, sc, stream);
+    typedef Cfg2 C;
+    constexpr int DBK = 32, NST = 3;   // 72 KiB of LDS: two workgroups per CU
+    constexpr int lds = DlCfg<C, DBK, NST>::LDS_BYTES;
+    static bool attr = false;
+    if (!attr) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_bf16_dl<C, DBK, NST>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr = true;
+    }
+    hipLaunchKernelGGL((k_update_bf16_dl<C, DBK, NST>), dim3(n_tiles), dim3(C::NT), lds, stream, mats, dyn, tiles, sc,
+                       zero16);
+    return hipGetLastError();
 }
 
 // which: 0 = projection (needs the largest rank of the layer set), 1 = update
@@ -582,3 +647,4 @@ void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
 }
 
 }  // namespace ng
+

@@ -478,8 +478,10 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
 
         // upload the tables (synchronous copies; init is not a hot path)
         hipError_t e = hipSuccess;
-        int zero = 0;
-        e = hipMemcpy(st->d_status, &zero, sizeof(int), hipMemcpyHostToDevice);
+        // the status word, and behind it (bytes 64..127) a block of zeros the update GEMM fetches
+        // in place of out-of-range operand chunks
+        const char zeros[256] = {0};
+        e = hipMemcpy(st->d_status, zeros, sizeof(zeros), hipMemcpyHostToDevice);
         if (e == hipSuccess) e = hipMemcpy(st->d_mats, st->mats.data(), sizeof(MatDev) * n_mats, hipMemcpyHostToDevice);
         if (e == hipSuccess && !pl.proj.empty())
             e = hipMemcpy(st->d_proj, pl.proj.data(), sizeof(TileRef) * pl.proj.size(), hipMemcpyHostToDevice);
@@ -616,7 +618,8 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
                                  st->hp.grad_dtype, st->d_status, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
-    if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc, stream));
+    if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc,
+                                      (const char*)st->d_status + 64, stream));
     else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) {

@@ -119,8 +119,9 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                                int max_r, hipStream_t stream);
+// zero16: 16 bytes of zeros in device memory (fetched in place of out-of-range operand chunks)
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                              StepScalars sc, hipStream_t stream);
+                              StepScalars sc, const void* zero16, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,

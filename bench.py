@@ -22,18 +22,19 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def algorithmic_work(cfg, mats):
+def algorithmic_work(cfg, mats, hist_dtype="f32"):
     """Bytes and flops per step and phase (algorithmic: every operand moved once)."""
     s, r = cfg.s, cfg.r
     e = 2 if cfg.dtype == "bf16" else 4          # gradient / weight / GEMM-operand element size
+    hb = 2.0 if hist_dtype == "bf16" else 4.0    # history element size
     w = {k: {"bytes": 0.0, "flops": 0.0} for k in ("project", "gram", "solve", "adam", "update")}
     for (m, n) in mats:
         rn, mn, mr = r * n, m * n, m * r
-        w["project"]["bytes"] += e * mn + e * mr + 4 * rn
+        w["project"]["bytes"] += e * mn + e * mr + hb * rn
         w["project"]["flops"] += 2.0 * mn * r
-        w["gram"]["bytes"] += 4.0 * s * rn
+        w["gram"]["bytes"] += hb * s * rn
         w["gram"]["flops"] += 2.0 * s * rn
-        w["adam"]["bytes"] += 4.0 * s * rn + 16 * rn + e * rn
+        w["adam"]["bytes"] += hb * s * rn + 16 * rn + e * rn
         w["adam"]["flops"] += 2.0 * s * rn + 12 * rn
         w["update"]["bytes"] += e * mr + e * rn + 2 * e * mn
         w["update"]["flops"] += 2.0 * mn * r
@@ -91,6 +92,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c5")
     ap.add_argument("--pool", type=int, default=4, help="pre-generated gradient sets cycled through")
+    ap.add_argument("--hist-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the history ring (the benchmark configurations fix f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true")
     ap.add_argument("--refresh-in-loop", type=int, default=0, help="refresh every this many timed steps (0 = never)")
@@ -127,7 +130,7 @@ def main() -> int:
     pool = [stream.next_set() for _ in range(max(1, args.pool))]
     weights = workloads.torch_weights(mats, cfg.seed, cfg.dtype, dev)
     ls = B.LayerSet(mats, cfg.r, s=cfg.s, lam=cfg.lam, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
-                    dtype=cfg.dtype, device=dev)
+                    dtype=cfg.dtype, device=dev, hist_dtype=args.hist_dtype)
     torch.cuda.synchronize()
 
     # projector refresh at step 0 (timed separately, not part of `value`)
@@ -161,7 +164,7 @@ def main() -> int:
     assert ls.status() == B.NG_OK, "a step reported a numeric failure"
 
     ms_per_step = elapsed * 1e3 / args.steps
-    work = algorithmic_work(cfg, mats)
+    work = algorithmic_work(cfg, mats, args.hist_dtype)
     phases = {}
     if not args.no_phase_events:
         ms, nsteps = B.ng_get_phase_ms(st, reset=True)
@@ -180,6 +183,8 @@ def main() -> int:
     def measured_traffic(kernel):
         """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
         path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, args.config))
+        if args.hist_dtype != "f32":
+            return None   # the committed counter summaries cover the f32-history configuration
         try:
             for line in open(path):
                 if line.startswith("traffic_bytes_per_launch:"):
@@ -209,8 +214,8 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype if cfg.dtype != "f32" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d matrices, rank %d, history s=%d, %s gradients/weights, fp32 states"
-                               % (cfg.name, len(mats), cfg.r, cfg.s, cfg.dtype),
+        "config": {"workload": "%s: %d matrices, rank %d, history s=%d, %s gradients/weights, fp32 moments, %s history"
+                               % (cfg.name, len(mats), cfg.r, cfg.s, cfg.dtype, args.hist_dtype),
                    "config_key": args.config, "refreshes_in_timed_region": n_refresh,
                    "gradient_pool": len(pool)},
         "roofline": roofline,

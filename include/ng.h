@@ -64,7 +64,7 @@ enum {
     NG_BUF_P = 0,   /* float  [m][r]                      projector                                   */
     NG_BUF_M,       /* float  [r][ldn]                    first moment                                */
     NG_BUF_V,       /* float  [r][ldn]                    second moment                               */
-    NG_BUF_H,       /* float  [max(s,1)][r][ldn]          history ring (one scratch slot when s = 0)  */
+    NG_BUF_H,       /* float or bf16 (hist_dtype) [max(s,1)][r][ldn]  history ring (one scratch slot when s = 0) */
     NG_BUF_K,       /* double [s*s] Gram, double [s] w, then float [s] w  (see ng_matrix_layout)      */
     NG_BUF_N,       /* update direction: float [r][ldn] (NG_F32) or bf16 [ceil(r/8)][ldn][8] (NG_BF16) */
     NG_BUF_AUX,     /* NG_BF16 only: bf16 copies of P; 0 bytes for NG_F32 (pointer may be NULL)       */
@@ -88,6 +88,11 @@ typedef struct ng_hparams {
     int32_t refresh_power_iters;  /* subspace-iteration passes q >= 0 of the refresh               */
     int32_t refresh_oversample;   /* extra sketch columns p >= 0; sketch width l = min(r+p, m, n)  */
     int32_t refresh_sweeps;       /* maximum Jacobi sweeps of the l x l eigen-solve, >= 1          */
+    int32_t hist_dtype;           /* storage type of the history slots: NG_F32 (default) or NG_BF16
+                                     (NG_BF16 gradients only).  bf16 slots halve the ring's memory and
+                                     the two passes over it that bound the step; M and V are float in
+                                     every mode                                                      */
+    int32_t reserved;             /* must be 0                                                       */
     uint64_t seed;                /* seed of the refresh's random sketch                            */
 } ng_hparams;
 
@@ -103,7 +108,8 @@ typedef struct ng_matrix_layout {
 } ng_matrix_layout;
 
 /* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
- * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps, seed 0. */
+ * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps,
+ * hist_dtype NG_F32, seed 0. */
 int ng_default_hparams(ng_hparams* hp);
 
 /* Bytes the caller must allocate.  bytes[i*NG_NBUF + b] = size of buffer b of

@@ -42,7 +42,8 @@ class ng_hparams(C.Structure):
                 ("eps", C.c_float), ("scale", C.c_float), ("weight_decay", C.c_float),
                 ("grad_dtype", C.c_int32), ("adam_mode", C.c_int32),
                 ("refresh_power_iters", C.c_int32), ("refresh_oversample", C.c_int32),
-                ("refresh_sweeps", C.c_int32), ("seed", C.c_uint64)]
+                ("refresh_sweeps", C.c_int32), ("hist_dtype", C.c_int32), ("reserved", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 class ng_matrix_buffers(C.Structure):
@@ -188,7 +189,7 @@ class LayerSet:
 
     def __init__(self, shapes: Sequence, r, *, s=4, lam=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                  weight_decay=0.0, dtype="f32", adam_mode="standard", power_iters=None, oversample=None,
-                 sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False):
+                 sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False, hist_dtype=None):
         self.device = torch.device(device)
         self.shapes = [tuple(x) for x in shapes]
         self.r = r
@@ -204,6 +205,9 @@ class LayerSet:
         if sweeps is not None:
             hp.refresh_sweeps = sweeps
         hp.seed = seed
+        if hist_dtype is not None:
+            hp.hist_dtype = {"f32": NG_F32, "bf16": NG_BF16}[hist_dtype]
+        self.hist_dtype = hist_dtype if hist_dtype is not None else "f32"
         self.hp = hp
         self.dtype = dtype
         self.descs = make_descs(self.shapes, r, ld_w, ld_g)
@@ -274,7 +278,8 @@ class LayerSet:
     def H(self, i):
         r, ldn = self.descs[i].r, self.layouts[i].ldn
         s = max(self.hp.s, 1)
-        return self._view(i, NG_BUF_H, torch.float32, s * r * ldn).view(s, r, ldn)
+        ht = torch.bfloat16 if self.hist_dtype == "bf16" else torch.float32
+        return self._view(i, NG_BUF_H, ht, s * r * ldn).view(s, r, ldn)
 
     def K(self, i):
         s = self.hp.s

@@ -18,6 +18,7 @@ namespace ng {
 #define NG_AS1 __attribute__((address_space(1)))
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------ helpers
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -72,20 +73,21 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
 // ------------------------------------------------------------------ Gram row
 // One workgroup = one contiguous part of the flat r*ldn range of one matrix.
 // Products and 4-term sums in fp32, running sums in fp64, fixed reduction order.
-template <int SMAX>
+// HB: the slots hold bf16 (8 elements per 16-byte vector) instead of float (4 per vector).
+template <int SMAX, bool HB>
 __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn,
                                                   const TileRef* __restrict__ chunks, int s) {
     const TileRef c = chunks[blockIdx.x];
     const MatDev& md = mats[c.mat];
     const int head = dyn[c.mat].head;
-    const long long total4 = md.slot_elems >> 2;
+    const long long totalv = md.slot_elems >> (HB ? 3 : 2);   // 16-byte vectors per slot
     const long long span = (long long)md.dot_iters * 256;
     const long long q0 = (long long)c.ti * span;
     long long q1 = q0 + span;
-    if (q1 > total4) q1 = total4;
-    const NG_AS1 f32x4_t* __restrict__ R = (const NG_AS1 f32x4_t*)(md.H + (long long)head * md.slot_elems);
-    const NG_AS1 f32x4_t* __restrict__ H = (const NG_AS1 f32x4_t*)md.H;
+    if (q1 > totalv) q1 = totalv;
+    const NG_AS1 u32x4_t* __restrict__ H = (const NG_AS1 u32x4_t*)md.H;
+    const NG_AS1 u32x4_t* __restrict__ R = H + (long long)head * totalv;
 
     double acc[SMAX];
 #pragma unroll
@@ -95,19 +97,38 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
     // written out), so all SMAX loads of one position are issued back to back.
     long long slot_off[SMAX];
 #pragma unroll
-    for (int j = 0; j < SMAX; ++j) slot_off[j] = (long long)(j < s ? j : s - 1) * total4;
+    for (int j = 0; j < SMAX; ++j) slot_off[j] = (long long)(j < s ? j : s - 1) * totalv;
     for (long long q = q0 + threadIdx.x; q < q1; q += 256) {
-        const f32x4_t rv = R[q];
-        f32x4_t hv[SMAX];
+        const u32x4_t rv = R[q];
+        u32x4_t hv[SMAX];
 #pragma unroll
         for (int j = 0; j < SMAX; ++j) hv[j] = H[slot_off[j] + q];
+        if (HB) {
+            float rf[8];
 #pragma unroll
-        for (int j = 0; j < SMAX; ++j) {
-            float p = hv[j].x * rv.x;
-            p = fmaf(hv[j].y, rv.y, p);
-            p = fmaf(hv[j].z, rv.z, p);
-            p = fmaf(hv[j].w, rv.w, p);
-            acc[j] += (double)p;
+            for (int d = 0; d < 4; ++d) {
+                rf[2 * d] = __uint_as_float(rv[d] << 16);
+                rf[2 * d + 1] = __uint_as_float(rv[d] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int j = 0; j < SMAX; ++j) {
+                float p = 0.f;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    p = fmaf(__uint_as_float(hv[j][d] << 16), rf[2 * d], p);
+                    p = fmaf(__uint_as_float(hv[j][d] & 0xffff0000u), rf[2 * d + 1], p);
+                }
+                acc[j] += (double)p;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < SMAX; ++j) {
+                float p = __uint_as_float(hv[j].x) * __uint_as_float(rv.x);
+                p = fmaf(__uint_as_float(hv[j].y), __uint_as_float(rv.y), p);
+                p = fmaf(__uint_as_float(hv[j].z), __uint_as_float(rv.z), p);
+                p = fmaf(__uint_as_float(hv[j].w), __uint_as_float(rv.w), p);
+                acc[j] += (double)p;
+            }
         }
     }
 
@@ -126,10 +147,14 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
 }
 
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks, int s,
-                           hipStream_t stream) {
+                           int hist_bf16, hipStream_t stream) {
     if (n_chunks == 0) return hipSuccess;
     dim3 g(n_chunks), b(256);
-#define NG_GRAM_CASE(S) hipLaunchKernelGGL(k_gram_row<S>, g, b, 0, stream, mats, dyn, chunks, s)
+#define NG_GRAM_CASE(S)                                                                          \
+    do {                                                                                         \
+        if (hist_bf16) hipLaunchKernelGGL((k_gram_row<S, true>), g, b, 0, stream, mats, dyn, chunks, s);  \
+        else hipLaunchKernelGGL((k_gram_row<S, false>), g, b, 0, stream, mats, dyn, chunks, s);           \
+    } while (0)
     if (s <= 1) NG_GRAM_CASE(1);
     else if (s <= 2) NG_GRAM_CASE(2);
     else if (s <= 3) NG_GRAM_CASE(3);
@@ -252,7 +277,22 @@ hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_
 // N is stored either as float [r][ldn] or as bf16 [r/8][ldn][8] (eight
 // consecutive rows of one column adjacent: the k-packing the update GEMM's MFMA
 // operand wants, so that kernel needs no transpose).
-template <bool BF16_N>
+// Four consecutive history elements of one row: a float4, or 4 bf16 (8 bytes) widened to float.
+template <bool HB>
+__device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 void* base, long long elem) {
+    if (HB) {
+        const u32x2_t v = *(const NG_AS1 u32x2_t*)((const NG_AS1 unsigned short*)base + elem);
+        f32x4_t o;
+        o.x = __uint_as_float(v.x << 16);
+        o.y = __uint_as_float(v.x & 0xffff0000u);
+        o.z = __uint_as_float(v.y << 16);
+        o.w = __uint_as_float(v.y & 0xffff0000u);
+        return o;
+    }
+    return *(const NG_AS1 f32x4_t*)((const NG_AS1 float*)base + elem);
+}
+
+template <bool BF16_N, bool HB>
 __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict__ mats,
                                                         const MatDyn* __restrict__ dyn,
                                                         const TileRef* __restrict__ patches, StepScalars sc,
@@ -277,15 +317,15 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     for (int e = 0; e < 8; ++e) g[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     const int s = sc.s;
-    const NG_AS1 float* __restrict__ Hb = (const NG_AS1 float*)md.H + base;
+    const NG_AS1 void* __restrict__ Hv = (const NG_AS1 void*)md.H;
     if (sc.use_fisher) {
         const NG_AS1 float* __restrict__ w = (const NG_AS1 float*)md.w32;
         for (int j = 0; j < s; ++j) {
             const float wj = w[j];
-            const NG_AS1 float* __restrict__ Hj = Hb + (long long)j * md.slot_elems;
+            const long long slot = base + (long long)j * md.slot_elems;
             f32x4_t h[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = *(const NG_AS1 f32x4_t*)(Hj + rowoff[e]);
+            for (int e = 0; e < 8; ++e) h[e] = load_hist4<HB>(Hv, slot + rowoff[e]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 g[e].x = fmaf(wj, h[e].x, g[e].x);
@@ -297,7 +337,7 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     } else {
         // the single scratch slot holds R
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = *(const NG_AS1 f32x4_t*)(Hb + rowoff[e]);
+        for (int e = 0; e < 8; ++e) g[e] = load_hist4<HB>(Hv, base + rowoff[e]);
     }
 
     const float b1 = sc.beta1, b2 = sc.beta2, ob1 = 1.0f - sc.beta1, ob2 = 1.0f - sc.beta2;
@@ -373,12 +413,15 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
 hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,
                                  StepScalars sc, int grad_dtype, int* status, hipStream_t stream) {
     if (n_patches == 0) return hipSuccess;
-    if (grad_dtype == NG_BF16)
-        hipLaunchKernelGGL(k_transform_adam<true>, dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches, sc,
-                           status);
+    if (grad_dtype == NG_BF16 && sc.hist_bf16)
+        hipLaunchKernelGGL((k_transform_adam<true, true>), dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches,
+                           sc, status);
+    else if (grad_dtype == NG_BF16)
+        hipLaunchKernelGGL((k_transform_adam<true, false>), dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches,
+                           sc, status);
     else
-        hipLaunchKernelGGL(k_transform_adam<false>, dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches, sc,
-                           status);
+        hipLaunchKernelGGL((k_transform_adam<false, false>), dim3(n_patches), dim3(256), 0, stream, mats, dyn, patches,
+                           sc, status);
     return hipGetLastError();
 }
 

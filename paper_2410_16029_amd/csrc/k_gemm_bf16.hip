@@ -289,7 +289,8 @@ __device__ __forceinline__ void gemm_mainloop(floatx16 (&acc)[C::MI][C::NJ], LA&
     }
 }
 
-template <class C>
+// HB: the ring slot receives bf16 instead of float.
+template <class C, bool HB>
 __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict__ mats,
                                                         const MatDyn* __restrict__ dyn,
                                                         const TileRef* __restrict__ tiles) {
@@ -322,20 +323,61 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
         gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
     }
 
-    NG_AS1 float* R = (NG_AS1 float*)(md.H + (long long)dy.head * md.slot_elems);
+    if (!HB) {
+        NG_AS1 float* R = (NG_AS1 float*)md.H + (long long)dy.head * md.slot_elems;
 #pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
+        for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
-        for (int nj = 0; nj < C::NJ; ++nj) {
-            const int col = j0 + wn * C::WN + nj * 32 + li;
+            for (int nj = 0; nj < C::NJ; ++nj) {
+                const int col = j0 + wn * C::WN + nj * 32 + li;
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
+                for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int row = i0 + wm * C::WM + mi * 32 + 8 * g + 4 * h + e;
-                    if (row < r && col < ldn) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = acc[mi][nj][4 * g + e];
+                    for (int e = 0; e < 4; ++e) {
+                        const int row = i0 + wm * C::WM + mi * 32 + 8 * g + 4 * h + e;
+                        if (row < r && col < ldn) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = acc[mi][nj][4 * g + e];
+                    }
+            }
+    } else {
+        // bf16 slot: the tile goes through LDS (float), one 32-row block of every wave-row at a
+        // time, so that each thread converts and stores 8 consecutive columns (16 bytes) of a row
+        // (the main loop ended on a barrier; ldn % 32 == 0, so a chunk that starts inside a row
+        // ends inside it)
+        constexpr int ROWS = C::NWM * 32, CH = C::BN / 8, PER_T = ROWS * CH / C::NT;
+        static_assert(ROWS * CH % C::NT == 0, "epilogue mapping");
+        float* Cs = reinterpret_cast<float*>(smem);
+        NG_AS1 bf16_t* Rb = (NG_AS1 bf16_t*)md.H + (long long)dy.head * md.slot_elems;
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        Cs[(wm * 32 + 8 * g + 4 * h + e) * C::LDC + wn * C::WN + nj * 32 + li] = acc[mi][nj][4 * g + e];
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PER_T; ++p) {
+                const int q = t + C::NT * p;
+                const int lr = q / CH, cc = q % CH;
+                const int row = i0 + (lr / 32) * C::WM + mi * 32 + (lr % 32);
+                const int col = j0 + cc * 8;
+                if (row < r && col < ldn) {
+                    const float* cp = Cs + lr * C::LDC + cc * 8;
+                    const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(cp);
+                    const f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(cp + 4);
+                    u32x4_t ov;
+                    ov.x = pack_bf16x2(c0.x, c0.y);
+                    ov.y = pack_bf16x2(c0.z, c0.w);
+                    ov.z = pack_bf16x2(c1.x, c1.y);
+                    ov.w = pack_bf16x2(c1.z, c1.w);
+                    *(NG_AS1 u32x4_t*)(Rb + ((unsigned)row * (unsigned)ldn + (unsigned)col)) = ov;
                 }
+            }
+            __syncthreads();
         }
+    }
 }
 
 // =================================================================== update
@@ -602,24 +644,27 @@ typedef Cfg<256, 128, 128, 64, 64> Cfg2;
 
 static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
 
-template <class C>
+template <class C, bool HB>
 static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               hipStream_t stream) {
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         attr = true;
     }
-    hipLaunchKernelGGL(k_project_bf16<C>, dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn, tiles);
+    hipLaunchKernelGGL((k_project_bf16<C, HB>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn, tiles);
     return hipGetLastError();
 }
 
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, hipStream_t stream) {
+                               int max_r, int hist_bf16, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    if (project_cfg(max_r) == 0) return run_project<Cfg0>(mats, dyn, tiles, n_tiles, stream);
-    return run_project<Cfg2>(mats, dyn, tiles, n_tiles, stream);
+    if (project_cfg(max_r) == 0)
+        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_tiles, stream)
+                         : run_project<Cfg0, false>(mats, dyn, tiles, n_tiles, stream);
+    return hist_bf16 ? run_project<Cfg2, true>(mats, dyn, tiles, n_tiles, stream)
+                     : run_project<Cfg2, false>(mats, dyn, tiles, n_tiles, stream);
 }
 
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,

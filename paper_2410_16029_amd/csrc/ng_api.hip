@@ -30,6 +30,9 @@ struct Sizes {   // per-matrix derived sizes
 int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
     if (!d || !hp || n_mats <= 0) return NG_ERR_INVALID_ARG;
     if (hp->grad_dtype != NG_F32 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
+    if (hp->hist_dtype != NG_F32 && hp->hist_dtype != NG_BF16) return NG_ERR_DTYPE;
+    if (hp->hist_dtype == NG_BF16 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
+    if (hp->reserved != 0) return NG_ERR_HPARAM;
     if (hp->adam_mode != NG_ADAM_STANDARD && hp->adam_mode != NG_ADAM_PRINTED) return NG_ERR_DTYPE;
     if (hp->s < 0 || hp->s > kMaxS) return NG_ERR_SHAPE;
     if (!(hp->lambda > 0.f) || !isfinite(hp->lambda)) return NG_ERR_HPARAM;
@@ -54,6 +57,8 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
     return NG_OK;
 }
 
+bool hist_is_bf16(const ng_hparams& hp) { return hp.hist_dtype == NG_BF16; }
+
 void derive(const ng_matrix_desc& d, const ng_hparams& hp, Sizes* z) {
     memset(z, 0, sizeof(*z));
     const int s = hp.s;
@@ -76,7 +81,7 @@ void derive(const ng_matrix_desc& d, const ng_hparams& hp, Sizes* z) {
     z->bytes[NG_BUF_P] = align_up((size_t)d.m * d.r * 4, 256);
     z->bytes[NG_BUF_M] = align_up(rn * 4, 256);
     z->bytes[NG_BUF_V] = align_up(rn * 4, 256);
-    z->bytes[NG_BUF_H] = align_up(rn * 4 * (size_t)(s > 0 ? s : 1), 256);
+    z->bytes[NG_BUF_H] = align_up(rn * (hist_is_bf16(hp) ? 2 : 4) * (size_t)(s > 0 ? s : 1), 256);
     z->k_gram_off = 0;
     z->k_w64_off = align_up((size_t)s * s * 8, 16);
     z->k_w32_off = z->k_w64_off + align_up((size_t)s * 8, 16);
@@ -246,6 +251,7 @@ StepScalars make_scalars(const ng_state* st, float lr) {
     sc.adam_mode = st->hp.adam_mode;
     sc.s = st->hp.s > 0 ? st->hp.s : 1;
     sc.use_fisher = st->hp.s > 0 ? 1 : 0;
+    sc.hist_bf16 = hist_is_bf16(st->hp) ? 1 : 0;
     return sc;
 }
 
@@ -322,6 +328,8 @@ int ng_default_hparams(ng_hparams* hp) {
     hp->scale = 1.0f;
     hp->weight_decay = 0.0f;
     hp->grad_dtype = NG_F32;
+    hp->hist_dtype = NG_F32;
+    hp->reserved = 0;
     hp->adam_mode = NG_ADAM_STANDARD;
     hp->refresh_power_iters = 2;
     hp->refresh_oversample = 8;
@@ -439,7 +447,8 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.order = (int*)(ws + off); off += z.ws_order;
             md.jflag = (int*)(ws + off); off += z.ws_flag;
             md.lp = z.lp; md.jb = z.jb;
-            const long long total4 = md.slot_elems / 4;
+            // units of the Gram-row reduction: 16-byte vectors of a slot
+            const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
             long long iters = (total4 + 256LL * kDotPartsMax - 1) / (256LL * kDotPartsMax);
             if (iters < 1) iters = 1;
             md.dot_iters = (int)iters;
@@ -604,11 +613,11 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, stream));
+    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, sc.hist_bf16, stream));
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
-    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, stream));
+    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
     if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, st->d_status, stream));

@@ -28,7 +28,7 @@ struct MatDev {
     float* P;
     float* M;
     float* V;
-    float* H;
+    float* H;         // history ring; bf16 elements when StepScalars::hist_bf16 (same element offsets)
     double* K;        // s*s Gram
     double* w64;      // s
     float* w32;       // s
@@ -71,6 +71,7 @@ struct StepScalars {
     int adam_mode;
     int s;               // slots read by the kernels (>= 1; the s = 0 case uses one scratch slot)
     int use_fisher;      // 0 when hparams.s == 0
+    int hist_bf16;       // history slots are bf16 (else float)
 };
 
 // Grouped-launch work item: which matrix and which tile / part of it a workgroup takes.
@@ -118,14 +119,14 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, hipStream_t stream);
+                               int max_r, int hist_bf16, hipStream_t stream);
 // zero16: 16 bytes of zeros in device memory (fetched in place of out-of-range operand chunks)
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, const void* zero16, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,
-                           int s, hipStream_t stream);
+                           int s, int hist_bf16, hipStream_t stream);
 hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_mats, StepScalars sc,
                         int* status, hipStream_t stream);
 hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,

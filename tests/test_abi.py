@@ -47,6 +47,11 @@ def test_query_sizes_c1_and_bf16_layout():
     assert sizes[0][B.NG_BUF_M] == 512 * ldn * 4
     assert sizes[0][B.NG_BUF_H] == 16 * 512 * ldn * 4
     assert sizes[0][B.NG_BUF_N] == (512 // 8) * ldn * 8 * 2
+    hp.hist_dtype = B.NG_BF16                               # opt-in: bf16 history slots
+    sizes16, _ = B.ng_query_sizes(descs, hp)
+    assert sizes16[0][B.NG_BUF_H] == 16 * 512 * ldn * 2
+    assert sizes16[0][B.NG_BUF_M] == 512 * ldn * 4
+    hp.hist_dtype = B.NG_F32
     assert sizes[0][B.NG_BUF_AUX] >= 2 * 2048 * 512 * 2
     # s = 0 keeps one scratch slot for the projected gradient
     hp.s = 0
@@ -63,6 +68,9 @@ def test_query_sizes_c1_and_bf16_layout():
     (lambda d, hp: setattr(hp, "s", -1), B.NG_ERR_SHAPE),
     (lambda d, hp: setattr(hp, "s", 65), B.NG_ERR_SHAPE),
     (lambda d, hp: setattr(hp, "grad_dtype", 7), B.NG_ERR_DTYPE),
+    (lambda d, hp: setattr(hp, "hist_dtype", 5), B.NG_ERR_DTYPE),
+    (lambda d, hp: setattr(hp, "hist_dtype", B.NG_BF16), B.NG_ERR_DTYPE),   # bf16 history needs bf16 gradients
+    (lambda d, hp: setattr(hp, "reserved", 1), B.NG_ERR_HPARAM),
     (lambda d, hp: setattr(hp, "adam_mode", 2), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "refresh_sweeps", 0), B.NG_ERR_HPARAM),
     (lambda d, hp: setattr(d[0], "r", 0), B.NG_ERR_SHAPE),

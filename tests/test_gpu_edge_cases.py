@@ -103,6 +103,24 @@ def test_mixed_ranks_in_one_layer_set_bf16():
     _assert_all(errs, TOL_BF16, "mixed ranks")
 
 
+def test_bf16_history_slots_ragged_shapes():
+    # opt-in bf16 storage of the history ring: same tolerances; ring wrap-around (steps > s)
+    shapes = [(384, 520), (200, 333), (520, 384), (128, 128)]
+    ls, errs = _run(shapes, 64, 4, "bf16", 7, seed=23, k=16, hist_dtype="bf16")
+    assert ls.H(0).dtype == torch.bfloat16
+    _assert_all(errs, TOL_BF16, "bf16 history, ragged")
+
+
+def test_bf16_history_slots_1b_shapes_and_no_fisher():
+    cfg = workloads.CONFIGS["c5"]
+    shapes = cfg.matrices()[:7]
+    ls, errs = _run(shapes, cfg.r, cfg.s, "bf16", 3, seed=cfg.seed, k=cfg.k, check=[0, 4, 6], hist_dtype="bf16")
+    _assert_all(errs, TOL_BF16, "bf16 history, c5 block")
+    # s = 0: the single scratch slot is bf16 too
+    ls, errs = _run([(200, 333), (130, 64)], 24, 0, "bf16", 3, seed=29, k=24, hist_dtype="bf16")
+    _assert_all(errs, TOL_BF16, "bf16 history, s=0")
+
+
 def test_full_1b_layer_set_sampled():
     """All 168 matrices of the 1.1B configuration in one layer set (the grouped launches, tile
     tables and history size the benchmark times); the oracle follows one matrix of each shape

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
         const u32x4_t rv = R[q];
         u32x4_t hv[SMAX];
 #pragma unroll
-        for (int j = 0; j < SMAX; ++j) hv[j] = H[slot_off[j] + q];
+        for (int j = 0; j < SMAX; ++j) hv[j] = __builtin_nontemporal_load(H + (slot_off[j] + q));
         if (HB) {
             float rf[8];
 #pragma unroll
@@ -281,7 +281,7 @@ hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_
 template <bool HB>
 __device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 void* base, long long elem) {
     if (HB) {
-        const u32x2_t v = *(const NG_AS1 u32x2_t*)((const NG_AS1 unsigned short*)base + elem);
+        const u32x2_t v = __builtin_nontemporal_load((const NG_AS1 u32x2_t*)((const NG_AS1 unsigned short*)base + elem));
         f32x4_t o;
         o.x = __uint_as_float(v.x << 16);
         o.y = __uint_as_float(v.x & 0xffff0000u);
@@ -289,7 +289,7 @@ __device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 void* base, long long
         o.w = __uint_as_float(v.y & 0xffff0000u);
         return o;
     }
-    return *(const NG_AS1 f32x4_t*)((const NG_AS1 float*)base + elem);
+    return __builtin_nontemporal_load((const NG_AS1 f32x4_t*)((const NG_AS1 float*)base + elem));
 }
 
 template <bool BF16_N, bool HB>
@@ -347,8 +347,8 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     f32x4_t mv[8], vv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        mv[e] = *(const NG_AS1 f32x4_t*)(Mb + rowoff[e]);
-        vv[e] = *(const NG_AS1 f32x4_t*)(Vb + rowoff[e]);
+        mv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + rowoff[e]));
+        vv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + rowoff[e]));
     }
     f32x4_t nv[8];
     bool bad = false;
@@ -378,8 +378,8 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
         }
         const bool live = e < nrow;
         if (live) {
-            *(NG_AS1 f32x4_t*)(Mb + rowoff[e]) = m;
-            *(NG_AS1 f32x4_t*)(Vb + rowoff[e]) = v;
+            __builtin_nontemporal_store(m, (NG_AS1 f32x4_t*)(Mb + rowoff[e]));
+            __builtin_nontemporal_store(v, (NG_AS1 f32x4_t*)(Vb + rowoff[e]));
         }
         bad |= live && (!(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
                         !(fabsf(o.w) <= 3.0e38f));
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
             o.y = pack_bf16x2(nv[2][c], nv[3][c]);
             o.z = pack_bf16x2(nv[4][c], nv[5][c]);
             o.w = pack_bf16x2(nv[6][c], nv[7][c]);
-            Np[c] = o;
+            Np[c] = o;   // (a nontemporal store is slower here: measured)
         }
     } else {
         NG_AS1 float* Nf = (NG_AS1 float*)md.N + base;

@@ -278,10 +278,13 @@ hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_
 // consecutive rows of one column adjacent: the k-packing the update GEMM's MFMA
 // operand wants, so that kernel needs no transpose).
 // Four consecutive history elements of one row: a float4, or 4 bf16 (8 bytes) widened to float.
+// `slot` is uniform over the workgroup and `off` a 32-bit byte offset, so the load takes its base
+// from scalar registers and needs one address register per row (the host checks that a slot is
+// below 2 GiB).
 template <bool HB>
-__device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 void* base, long long elem) {
+__device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 unsigned char* slot, unsigned off) {
     if (HB) {
-        const u32x2_t v = __builtin_nontemporal_load((const NG_AS1 u32x2_t*)((const NG_AS1 unsigned short*)base + elem));
+        const u32x2_t v = __builtin_nontemporal_load((const NG_AS1 u32x2_t*)(slot + off));
         f32x4_t o;
         o.x = __uint_as_float(v.x << 16);
         o.y = __uint_as_float(v.x & 0xffff0000u);
@@ -289,7 +292,7 @@ __device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 void* base, long long
         o.w = __uint_as_float(v.y & 0xffff0000u);
         return o;
     }
-    return __builtin_nontemporal_load((const NG_AS1 f32x4_t*)((const NG_AS1 float*)base + elem));
+    return __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(slot + off));
 }
 
 template <bool BF16_N, bool HB>
@@ -306,26 +309,28 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     const int ldn = md.ldn, r = md.r;
     if (row0 >= r || col0 >= ldn) return;
     const int nrow = (r - row0 < 8) ? (r - row0) : 8;
-    const long long base = (long long)row0 * ldn + col0;
     // Branch-free loads: a row beyond nrow re-reads row nrow-1 and its result is dropped.
-    long long rowoff[8];
+    // Element offsets of this thread's 8 row segments inside a slot / inside M, V (32-bit).
+    unsigned eoff[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) rowoff[e] = (long long)(e < nrow ? e : nrow - 1) * ldn;
+    for (int e = 0; e < 8; ++e) eoff[e] = (unsigned)(row0 + (e < nrow ? e : nrow - 1)) * (unsigned)ldn + (unsigned)col0;
+    constexpr unsigned HS = HB ? 2u : 4u;   // bytes per history element
 
     f32x4_t g[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) g[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     const int s = sc.s;
-    const NG_AS1 void* __restrict__ Hv = (const NG_AS1 void*)md.H;
+    const NG_AS1 unsigned char* __restrict__ Hbase = (const NG_AS1 unsigned char*)md.H;
+    const long long slot_bytes = md.slot_elems * (long long)HS;
     if (sc.use_fisher) {
         const NG_AS1 float* __restrict__ w = (const NG_AS1 float*)md.w32;
         for (int j = 0; j < s; ++j) {
             const float wj = w[j];
-            const long long slot = base + (long long)j * md.slot_elems;
+            const NG_AS1 unsigned char* slot = Hbase + (long long)j * slot_bytes;
             f32x4_t h[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = load_hist4<HB>(Hv, slot + rowoff[e]);
+            for (int e = 0; e < 8; ++e) h[e] = load_hist4<HB>(slot, eoff[e] * HS);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 g[e].x = fmaf(wj, h[e].x, g[e].x);
@@ -337,18 +342,18 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     } else {
         // the single scratch slot holds R
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = load_hist4<HB>(Hv, base + rowoff[e]);
+        for (int e = 0; e < 8; ++e) g[e] = load_hist4<HB>(Hbase, eoff[e] * HS);
     }
 
     const float b1 = sc.beta1, b2 = sc.beta2, ob1 = 1.0f - sc.beta1, ob2 = 1.0f - sc.beta2;
     const float bc1 = dyn[pr.mat].bc1, bc2 = dyn[pr.mat].bc2;
-    NG_AS1 float* Mb = (NG_AS1 float*)md.M + base;
-    NG_AS1 float* Vb = (NG_AS1 float*)md.V + base;
+    NG_AS1 unsigned char* Mb = (NG_AS1 unsigned char*)md.M;
+    NG_AS1 unsigned char* Vb = (NG_AS1 unsigned char*)md.V;
     f32x4_t mv[8], vv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        mv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + rowoff[e]));
-        vv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + rowoff[e]));
+        mv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
+        vv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
     }
     f32x4_t nv[8];
     bool bad = false;
@@ -378,8 +383,8 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
         }
         const bool live = e < nrow;
         if (live) {
-            __builtin_nontemporal_store(m, (NG_AS1 f32x4_t*)(Mb + rowoff[e]));
-            __builtin_nontemporal_store(v, (NG_AS1 f32x4_t*)(Vb + rowoff[e]));
+            __builtin_nontemporal_store(m, (NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
+            __builtin_nontemporal_store(v, (NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
         }
         bad |= live && (!(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
                         !(fabsf(o.w) <= 3.0e38f));
@@ -402,10 +407,10 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
             Np[c] = o;   // (a nontemporal store is slower here: measured)
         }
     } else {
-        NG_AS1 float* Nf = (NG_AS1 float*)md.N + base;
+        NG_AS1 unsigned char* Nf = (NG_AS1 unsigned char*)md.N;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (e < nrow) *(NG_AS1 f32x4_t*)(Nf + rowoff[e]) = nv[e];
+            if (e < nrow) *(NG_AS1 f32x4_t*)(Nf + eoff[e] * 4u) = nv[e];
     }
     if (bad) atomicOr(status, 2);
 }

@@ -92,6 +92,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c5")
     ap.add_argument("--pool", type=int, default=4, help="pre-generated gradient sets cycled through")
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
+                    help="override the configuration's gradient / weight type")
     ap.add_argument("--hist-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the history ring (the benchmark configurations fix f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -124,6 +126,9 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4, "copies": 10}))
         return 0
     cfg = workloads.CONFIGS[args.config]
+    if args.dtype is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, dtype=args.dtype)
     mats = cfg.matrices()
 
     stream = workloads.TorchGradientStream(mats, cfg.k, cfg.noise, cfg.seed, cfg.dtype, dev)

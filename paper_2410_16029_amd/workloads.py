@@ -65,6 +65,13 @@ CONFIGS = {
     "c3": _llama("llama-130m", 768, 2048, 12, 256, 8, 64, 2),
     "c4": _llama("llama-350m", 1024, 2736, 24, 256, 16, 64, 3),
     "c5": _llama("llama-1.1b", 2048, 5461, 24, 512, 16, 128, 4),
+    # Fine-tuning-shaped sets (paper Sec. 3.2: RoBERTa-Base, ranks 4 and 8, learning rate from its
+    # grid): 12 blocks x {4 attention 768x768, 768x3072, 3072x768}.  Ranks far below an MFMA tile:
+    # both GEMMs are pure bandwidth here.
+    "ft4": LayerSetConfig(name="roberta-base-rank4", shapes=((768, 768, 4), (768, 3072, 1), (3072, 768, 1)),
+                          blocks=12, r=4, s=4, k=8, noise=0.01, dtype="bf16", seed=5, lr=2e-5),
+    "ft8": LayerSetConfig(name="roberta-base-rank8", shapes=((768, 768, 4), (768, 3072, 1), (3072, 768, 1)),
+                          blocks=12, r=8, s=4, k=8, noise=0.01, dtype="bf16", seed=6, lr=2e-5),
 }
 
 

@@ -77,11 +77,13 @@ class Lockstep:
         GPU's N against the oracle's direction formula applied to the GPU's own M and V.
         "N" and "N_far_frac" (elements off by more than tol) are reported, not asserted.
         The weight update is pinned by "W" free-running and by the oracle's update formula fed
-        with the GPU's own N: "dW" (fp32 weights) or, for bf16 weights, "W_round_viol_frac":
-        with x the unrounded fp64 update and d = tol * max|dW|, the stored bf16 weight must lie
-        between round(x - d) and round(x + d), i.e. be the correct rounding of a value within
-        the GEMM tolerance of x; the fraction of elements outside must be 0.  ("W_upd_excess"
-        and "W_mismatch_frac" -- distance from, and inequality with, round(x) -- are reported.)"""
+        with the GPU's own N, "W_round_viol_frac": with x the unrounded fp64 update and
+        d = tol * max|dW|, the stored weight (bf16 or fp32) must lie between round(x - d) and
+        round(x + d) in its storage type, i.e. be the correct rounding of a value within the GEMM
+        tolerance of x; the fraction of elements outside must be 0.  "dW" (fp32 weights: the
+        applied update against the expected one, relative) is asserted by the callers only
+        where the update is large against the weights' own rounding step; "W_upd_excess" and
+        "W_mismatch_frac" (bf16) are reported."""
         ls = self.ls
         slot = {i: ls.counters(i)[1] for i in self.check}
         prev = {i: (self.states[i].M.copy(), self.states[i].V.copy(), to_f64(weights[i])) for i in self.check}
@@ -118,18 +120,20 @@ class Lockstep:
             Wg = to_f64(weights[i])
             e["W"] = rel_err(Wg, self.Wo[i])
             W_expect = oracle.back_project_update(Wp, st.P, Ng, lr, self.ohp)
+            dmax = np.max(np.abs(W_expect - Wp))
+            x = oracle.back_project_update(Wp, st.P, Ng, lr, dataclasses.replace(self.ohp, weight_dtype="f32"))
+            d = self.tol * dmax
             if ls.dtype == "bf16":
                 big = np.maximum(np.maximum(np.abs(W_expect), np.abs(Wg)), 1e-30)
                 step_bf16 = 2.0 ** (np.floor(np.log2(big)) - 7)
-                dmax = np.max(np.abs(W_expect - Wp))
                 e["W_upd_excess"] = float(np.max(np.abs(Wg - W_expect) / (step_bf16 + self.tol * dmax)))
                 e["W_mismatch_frac"] = float(np.mean(Wg != W_expect))
-                x = oracle.back_project_update(Wp, st.P, Ng, lr, dataclasses.replace(self.ohp, weight_dtype="f32"))
-                d = self.tol * dmax
                 lo, hi = oracle.round_to_bf16(x - d), oracle.round_to_bf16(x + d)
-                e["W_round_viol_frac"] = float(np.mean((Wg < lo) | (Wg > hi)))
             else:
                 e["dW"] = rel_err(Wg - Wp, W_expect - Wp)
+                lo = (x - d).astype(np.float32).astype(np.float64)   # IEEE round-to-nearest-even
+                hi = (x + d).astype(np.float32).astype(np.float64)
+            e["W_round_viol_frac"] = float(np.mean((Wg < lo) | (Wg > hi)))
             t, head, count, nref = ls.counters(i)
             assert (t, head, count, nref) == (st.t, st.head if ls.hp.s > 0 else 0, st.count, st.n_refresh), \
                 ((t, head, count, nref), (st.t, st.head, st.count, st.n_refresh))

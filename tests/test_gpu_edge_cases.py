@@ -121,6 +121,18 @@ def test_bf16_history_slots_1b_shapes_and_no_fisher():
     _assert_all(errs, TOL_BF16, "bf16 history, s=0")
 
 
+@pytest.mark.parametrize("name,dtype", [("ft4", "f32"), ("ft4", "bf16"), ("ft8", "f32"), ("ft8", "bf16")])
+def test_fine_tuning_shaped_block(name, dtype):
+    # one block of the RoBERTa-Base-shaped sets: rank 4 / 8, far below a GEMM tile
+    cfg = workloads.CONFIGS[name]
+    shapes = cfg.matrices()[:6]
+    ls, errs = _run(shapes, cfg.r, cfg.s, dtype, cfg.s + 2, seed=cfg.seed, k=cfg.k, check=[0, 4, 5], lr=cfg.lr)
+    # lr = 2e-5 and rank 4: the update is ~1e-6, a few hundred fp32 steps of a weight, so "dW"
+    # (relative to the update) is bounded by the weights' rounding, not by the GEMM; the
+    # rounding-interval check still applies to every element
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "%s %s" % (name, dtype), skip=("dW",))
+
+
 def test_full_1b_layer_set_sampled():
     """All 168 matrices of the 1.1B configuration in one layer set (the grouped launches, tile
     tables and history size the benchmark times); the oracle follows one matrix of each shape

@@ -17,13 +17,15 @@ TOL_BF16 = 2e-2
 FLOAT_KEYS = ("R", "K_row", "K", "w", "M", "V", "N_formula", "W", "dW")
 
 
-def _assert_all(errs, tol, label):
+def _assert_all(errs, tol, label, skip=()):
     print(label, {k: float("%.3g" % v) for k, v in summarize(errs).items()})
     if any("W_round_viol_frac" in e for step in errs for e in step.values()):
-        # bf16 weights: every stored weight is the bf16 rounding of a value within the GEMM
+        # every stored weight is the rounding (to its storage type) of a value within the GEMM
         # tolerance of the oracle's unrounded update of the GPU's own N
         assert worst(errs, "W_round_viol_frac") == 0.0, label
     for k in FLOAT_KEYS:
+        if k in skip:
+            continue
         vals = [e[k] for step in errs for e in step.values() if k in e]
         if vals:
             assert max(vals) <= tol, "%s: %s rel err %.3e > %.1e" % (label, k, max(vals), tol)

@@ -422,6 +422,240 @@ __global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restri
     if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
 }
 
+// ------------------------------------------------------------------ block rotation through the Gram matrix
+// The 16-row class.  One visit of a block pair (32 rows of length lp, held in LDS):
+//   S = X X^T          32 x 32 Gram of the rows, fp64 MFMA (16x16x4), K split over two wavefront groups
+//   small sweep        the 31 x 16 rotations of one cyclic sweep over the 32 rows, applied two-sidedly to
+//                      S (S <- J S J^T) and accumulated in V (V <- J V): the same rotations, in the same
+//                      order, that the row-by-row kernel would apply, decided from S instead of fresh dots
+//   X <- V X           fp64 MFMA, each wavefront owns 16-column tiles, written straight back to memory
+// so the 32 rows are read from LDS twice per visit instead of 2 x 31 times.
+// v_mfma_f64_16x16x4_f64: lane L supplies A[L%16][L/16] and B[L/16][L%16]; element e of its result is
+// D[4e + L/16][L%16] (checked on the device).
+typedef double double4_t __attribute__((ext_vector_type(4)));
+constexpr int kJgPad = 4;      // doubles of padding per LDS row of X: 16 rows land on distinct banks
+constexpr int kJgLdS = 36;     // row length of S and V in LDS (32 + 4, same reason)
+constexpr int kJgSeg = 9;      // ceil(544 / 64): 64-column segments of a row
+
+// cs, sn of the rotation that orthogonalises two rows with squared norms al, be and inner product ga
+// (the same angle as the row-by-row kernel).  Reciprocal and reciprocal square root start from the
+// hardware approximations and take Newton steps to full precision; cs^2 + sn^2 = 1 to rounding
+// whatever the error of the angle.
+__device__ __forceinline__ double rsq_nr(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y * (1.5 - 0.5 * x * y * y);
+}
+__device__ __forceinline__ void rotation_params(double al, double be, double ga, double* cs, double* sn) {
+    const double d = be - al, g2 = 2.0 * ga;
+    const double q = d * d + g2 * g2;
+    // (the angle only has to be good enough to shrink the coupling quadratically: one Newton step)
+    double y = __builtin_amdgcn_rsq(q);
+    y = y * (1.5 - 0.5 * q * y * y);
+    const double h = q * y;                                          // sqrt(d^2 + 4 ga^2)
+    const double den = fabs(d) + h;
+    double rd = __builtin_amdgcn_rcp(den);
+    rd = rd * (2.0 - den * rd);
+    const double tn = (d >= 0.0 ? g2 : -g2) * rd;                    // tan of the angle
+    const double c = rsq_nr(1.0 + tn * tn);
+    *cs = c;
+    *sn = c * tn;
+}
+
+// State of one row index in the 32-player tournament, advanced round by round without divisions:
+// in round ir the pairs are (31, ir) and ((ir + k) % 31, (ir - k) % 31), k = 1..15.
+struct TournamentRow {
+    int i, q, k;     // q = (2 ir - i) mod 31, k = (i - ir) mod 31
+    __device__ __forceinline__ void init(int row) {
+        i = row;
+        q = (62 - row) % 31;
+        k = row % 31;
+    }
+    __device__ __forceinline__ int partner(int ir) const { return i == 31 ? ir : (q == i ? 31 : q); }
+    __device__ __forceinline__ void advance() {
+        q += 2;
+        if (q >= 31) q -= 31;
+        k = k == 0 ? 30 : k - 1;
+    }
+};
+
+__global__ __launch_bounds__(1024) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
+    extern __shared__ __attribute__((aligned(16))) double smem_d[];
+    __shared__ double cc[32], tt[32];
+    __shared__ int nrot_s;
+    __shared__ double smax_s;
+    const MatDev& md = mats[blockIdx.y];
+    if (md.jb != 16) return;
+    const int lp = md.lp;
+    const int nb = lp / 16;
+    if ((int)blockIdx.x >= nb / 2 || round >= nb - 1) return;
+    if (md.jflag[1] != 0) return;       // converged in an earlier sweep
+    int bp, bq;
+    tournament_pair(nb, round, blockIdx.x, &bp, &bq);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int ldx = lp + kJgPad;
+    double* xs = smem_d;                    // [32][ldx]
+    double* Ss = xs + 32 * ldx;             // [32][kJgLdS]
+    double* Vs = Ss + 32 * kJgLdS;          // [32][kJgLdS]; first the Gram partials of the second K half
+    double* __restrict__ X = md.T;
+
+    // rows 2 wv, 2 wv + 1 of the pair (rows 0..15 from block bp, 16..31 from block bq); all loads of
+    // both rows are in flight together
+    {
+        double v[2][kJgSeg];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int row = 2 * wv + u;
+            const double* src = X + ((long long)(row < 16 ? bp : bq) * 16 + (row & 15)) * lp;
+#pragma unroll
+            for (int g = 0; g < kJgSeg; ++g) {
+                const int c = lane + 64 * g;
+                v[u][g] = src[c < lp ? c : lp - 1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int g = 0; g < kJgSeg; ++g) {
+                const int c = lane + 64 * g;
+                if (c < lp) xs[(2 * wv + u) * ldx + c] = v[u][g];
+            }
+    }
+    if (tid == 0) nrot_s = 0;
+    __syncthreads();
+
+    // ---- Gram: wavefronts 0..3 take a quarter of the columns each and compute the tiles (0,0), (1,0),
+    // (1,1) from the same two operands per k-step; (0,1) is the transpose of (1,0).  The partials of
+    // wavefronts 1..3 go through the S / V area (3 x 768 doubles) and are added by wavefront 0.
+    const int l16 = lane & 15, lq = lane >> 4;
+    double* part = Ss;                      // [3][3][256] while the Gram is reduced
+    double4_t g00 = {0.0, 0.0, 0.0, 0.0}, g10 = {0.0, 0.0, 0.0, 0.0}, g11 = {0.0, 0.0, 0.0, 0.0};
+    if (wv < 4) {
+        const int quarter = lp / 4;            // lp % 32 == 0: quarter % 8 == 0
+        const double* p0 = xs + l16 * ldx + wv * quarter + lq;
+        const double* p1 = xs + (16 + l16) * ldx + wv * quarter + lq;
+        for (int k = 0; k < quarter; k += 8) {
+            const double x0 = p0[k], x1 = p1[k], y0 = p0[k + 4], y1 = p1[k + 4];
+            g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(x0, x0, g00, 0, 0, 0);
+            g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, x0, g10, 0, 0, 0);
+            g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, x1, g11, 0, 0, 0);
+            g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(y0, y0, g00, 0, 0, 0);
+            g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(y1, y0, g10, 0, 0, 0);
+            g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(y1, y1, g11, 0, 0, 0);
+        }
+        if (wv > 0) {
+            double* dst = part + (wv - 1) * 768;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dst[e * 64 + lane] = g00[e];
+                dst[256 + e * 64 + lane] = g10[e];
+                dst[512 + e * 64 + lane] = g11[e];
+            }
+        }
+    }
+    __syncthreads();
+    if (wv == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                g00[e] += part[w * 768 + e * 64 + lane];
+                g10[e] += part[w * 768 + 256 + e * 64 + lane];
+                g11[e] += part[w * 768 + 512 + e * 64 + lane];
+            }
+    }
+    __syncthreads();
+    if (wv == 0) {
+        // element e of lane L is entry (4e + L/16, L%16) of its tile
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int ii = 4 * e + lq;
+            Ss[ii * kJgLdS + l16] = g00[e];
+            Ss[(16 + ii) * kJgLdS + l16] = g10[e];
+            Ss[l16 * kJgLdS + 16 + ii] = g10[e];
+            Ss[(16 + ii) * kJgLdS + 16 + l16] = g11[e];
+        }
+    }
+    __syncthreads();
+
+    // ---- V = I; largest diagonal entry of S (scale of the rounding noise inside this visit)
+    const int vi = tid >> 5, vj = tid & 31;
+    Vs[vi * kJgLdS + vj] = vi == vj ? 1.0 : 0.0;
+    if (wv == 0) {
+        double d = lane < 32 ? Ss[lane * kJgLdS + lane] : 0.0;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) d = fmax(d, __shfl_xor(d, off, 64));
+        if (lane == 0) smax_s = d;
+    }
+    __syncthreads();
+
+    // ---- one cyclic sweep over the 32 rows on S, accumulated in V; thread (vi, vj) owns S[vi][vj], V[vi][vj]
+    TournamentRow ri, rj;
+    ri.init(vi);
+    rj.init(vj);
+    int nrot = 0;
+    for (int ir = 0; ir < 31; ++ir) {
+        // old values first (their addresses depend on the round only), rotation parameters meanwhile
+        const int pi = ri.partner(ir), pj = rj.partner(ir);
+        const double s00 = Ss[vi * kJgLdS + vj], s10 = Ss[pi * kJgLdS + vj];
+        const double s01 = Ss[vi * kJgLdS + pj], s11 = Ss[pi * kJgLdS + pj];
+        const double v0 = Vs[vi * kJgLdS + vj], v1 = Vs[pi * kJgLdS + vj];
+        if (tid < 16) {
+            int a, b;
+            tournament_pair(32, ir, tid, &a, &b);
+            const double al = Ss[a * kJgLdS + a], be = Ss[b * kJgLdS + b], ga = Ss[a * kJgLdS + b];
+            double cs = 1.0, sn = 0.0;
+            if ((al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-15 * al * be)) {
+                rotation_params(al, be, ga, &cs, &sn);
+                // a coupling below the visit's own rounding noise (entries that went through
+                // rotations with much larger rows) is rotated but does not keep the sweep loop alive
+                if (fabs(ga) > 8.0e-15 * smax_s) ++nrot;
+            }
+            cc[a] = cs;
+            cc[b] = cs;
+            tt[a] = -sn;     // row a <- cs * a - sn * b
+            tt[b] = sn;      // row b <- sn * a + cs * b
+        }
+        __syncthreads();     // every old value has been read; the parameters are published
+        const double ci = cc[vi], ti_ = tt[vi], cj = cc[vj], tj_ = tt[vj];
+        Ss[vi * kJgLdS + vj] = cj * (ci * s00 + ti_ * s10) + tj_ * (ci * s01 + ti_ * s11);
+        Vs[vi * kJgLdS + vj] = ci * v0 + ti_ * v1;
+        ri.advance();
+        rj.advance();
+        __syncthreads();
+    }
+    if (nrot) atomicAdd(&nrot_s, nrot);
+
+    // ---- X <- V X: wavefront wv takes the 16-column tiles wv, wv + 16, ...; both 16-row halves
+    const int nct = lp / 16;
+    double a0[8], a1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        a0[u] = Vs[l16 * kJgLdS + 4 * u + lq];                 // A[L%16][k + L/16] = V[L%16][k + L/16]
+        a1[u] = Vs[(16 + l16) * kJgLdS + 4 * u + lq];
+    }
+    for (int ct = wv; ct < nct; ct += 16) {
+        const int c0 = 16 * ct;
+        double bx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) bx[u] = xs[(4 * u + lq) * ldx + c0 + l16];   // B[k + L/16][L%16] = X[k + L/16][c0 + L%16]
+        double4_t o0 = {0.0, 0.0, 0.0, 0.0}, o1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            o0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], bx[u], o0, 0, 0, 0);
+            o1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], bx[u], o1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r0 = 4 * e + lq;                          // row inside a 16-row half
+            X[((long long)bp * 16 + r0) * lp + c0 + l16] = o0[e];
+            X[((long long)bq * 16 + r0) * lp + c0 + l16] = o1[e];
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
+}
+
 template <int JB>
 static void jacobi_round_launch(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
                                 hipStream_t stream) {
@@ -437,7 +671,16 @@ static void jacobi_round_launch(const MatDev* mats, int n_mats, int max_pairs, i
 // jb_mask: bit log2(jb) set for every row-block size present in the layer set (4, 8, 16).
 hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
                                int jb_mask, hipStream_t stream) {
-    if (jb_mask & (1 << 4)) jacobi_round_launch<16>(mats, n_mats, max_pairs, round, lds_bytes, stream);
+    if (jb_mask & (1 << 4)) {
+        static bool attr_done = false;
+        constexpr int lds16 = (32 * (544 + kJgPad) + 2 * 32 * kJgLdS) * (int)sizeof(double);
+        if (!attr_done) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(k_jacobi_round_gram, dim3(max_pairs, n_mats), dim3(1024), lds16, stream, mats, round);
+    }
     if (jb_mask & (1 << 3)) jacobi_round_launch<8>(mats, n_mats, max_pairs, round, lds_bytes, stream);
     if (jb_mask & (1 << 2)) jacobi_round_launch<4>(mats, n_mats, max_pairs, round, lds_bytes, stream);
     return hipGetLastError();

@@ -5,7 +5,7 @@
 // strided views A(i,k), B(k,j) so one kernel covers all transpositions; an
 // operand may be stored as float or bf16 (gradients).
 //
-// Tile 64 x 64 per workgroup (4 wavefronts, one 32 x 32 MFMA block each), BK = 16.
+// Tile 128 x 128 per workgroup (4 wavefronts of 64 x 64), BK = 16.
 // MFMA 32x32x2 f32 operand layout: lane L supplies A[i = L%32][k = L/32] and
 // B[k = L/32][j = L%32]; the 16 accumulators of lane L are
 // D[8*g + 4*(L/32) + e][L%32], index 4*g + e.
@@ -122,29 +122,67 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
     return v;
 }
 
-void gemm_f32_dims(int op, const MatDev& md, int* M, int* N) {
+void gemm_f32_dims(int op, const MatDev& md, int* M, int* N, int* K) {
     GemmView v = gemm_view(op, md, nullptr, NG_F32);
     *M = v.M;
     *N = v.N;
+    *K = v.K;
 }
 
-__device__ __forceinline__ float load_elem(const void* p, long long idx, int is_bf16) {
+#define NG_AS1 __attribute__((address_space(1)))
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef f32x4_t __attribute__((aligned(4))) f32x4_a4;          // 16-byte access at 4-byte alignment
+typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
+typedef u16x4_t __attribute__((aligned(2))) u16x4_a2;          // 8-byte access at 2-byte alignment
+
+__device__ __forceinline__ float load_elem(const NG_AS1 void* p, long long idx, int is_bf16) {
     if (is_bf16) {
-        unsigned int u = (unsigned int)reinterpret_cast<const unsigned short*>(p)[idx];
+        unsigned int u = (unsigned int)reinterpret_cast<const NG_AS1 unsigned short*>(p)[idx];
         return __uint_as_float(u << 16);
     }
-    return reinterpret_cast<const float*>(p)[idx];
+    return reinterpret_cast<const NG_AS1 float*>(p)[idx];
 }
 
-constexpr int TS = 64;   // tile side
-constexpr int BK = 16;
-constexpr int LDT = TS + 4;
+// Four operand elements along the operand's contiguous dimension, starting at (fast index f, slow
+// index s): one vector load when all four exist, element loads with zero fill at the edges.
+__device__ __forceinline__ f32x4_t load_vec4(const NG_AS1 void* p, long long base, int f, int f_lim, bool s_ok,
+                                             int is_bf16) {
+    f32x4_t o = {0.f, 0.f, 0.f, 0.f};
+    if (!s_ok || f >= f_lim) return o;
+    if (f + 4 <= f_lim) {
+        if (is_bf16) {
+            const u16x4_t v = *reinterpret_cast<const NG_AS1 u16x4_a2*>(reinterpret_cast<const NG_AS1 unsigned short*>(p) + base);
+            o.x = __uint_as_float((unsigned int)v.x << 16);
+            o.y = __uint_as_float((unsigned int)v.y << 16);
+            o.z = __uint_as_float((unsigned int)v.z << 16);
+            o.w = __uint_as_float((unsigned int)v.w << 16);
+        } else {
+            o = *reinterpret_cast<const NG_AS1 f32x4_a4*>(reinterpret_cast<const NG_AS1 float*>(p) + base);
+        }
+        return o;
+    }
+    o.x = load_elem(p, base, is_bf16);
+    if (f + 1 < f_lim) o.y = load_elem(p, base + 1, is_bf16);
+    if (f + 2 < f_lim) o.z = load_elem(p, base + 2, is_bf16);
+    return o;
+}
 
+// Tile TS x TS per workgroup (128: four wavefronts of 64 x 64 = 2 x 2 MFMA blocks of 32 x 32; 64: one
+// block per wavefront, for products with a short side or a short contraction), BK = 16.  Each
+// thread moves 4-element vectors per operand and k-step, taken along the operand's contiguous
+// dimension (tile index or contraction index, whichever has stride 1).
+constexpr int BK = 16;
+
+template <int TS>
 __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn, int grad_dtype,
                                                   StepScalars sc) {
-    __shared__ float As[BK][LDT];
-    __shared__ float Bs[BK][LDT];
+    constexpr int LDT = TS + 4;
+    constexpr int NB = TS / 64;          // 32 x 32 blocks per wavefront and dimension
+    constexpr int NV = TS / 64;          // vectors per thread, operand and k-step
+    constexpr int TPR = TS / 4;          // threads along the tile index (tile-fast mapping)
+    __shared__ __attribute__((aligned(16))) float As[BK][LDT];
+    __shared__ __attribute__((aligned(16))) float Bs[BK][LDT];
     const MatDev& md = mats[blockIdx.z];
     const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype);
     const int i0 = blockIdx.y * TS, j0 = blockIdx.x * TS;
@@ -154,38 +192,65 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     const int lane = t & 63, wv = t >> 6;
     const int wm = wv >> 1, wn = wv & 1;
     const int li = lane & 31, h = lane >> 5;
+    const NG_AS1 void* Ap = (const NG_AS1 void*)v.A;
+    const NG_AS1 void* Bp = (const NG_AS1 void*)v.B;
 
-    // loader mappings: 4 elements per thread for each operand
+    // loader mappings: vector q of this thread covers 4 consecutive positions of the stride-1
+    // dimension.  tile-fast: positions 4 (t % TPR) of the tile index at k = t / TPR + (256 / TPR) q;
+    // k-fast: k = 4 (t % 4) at tile index t / 4 + 64 q.
     const bool a_i_fast = (v.sAi == 1);
     const bool b_j_fast = (v.sBj == 1);
-    int ai[4], ak[4], bk[4], bj[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        if (a_i_fast) { ai[p] = t & 63; ak[p] = (t >> 6) + 4 * p; }
-        else          { ak[p] = t & 15; ai[p] = (t >> 4) + 16 * p; }
-        if (b_j_fast) { bj[p] = t & 63; bk[p] = (t >> 6) + 4 * p; }
-        else          { bk[p] = t & 15; bj[p] = (t >> 4) + 16 * p; }
-    }
+    constexpr int KSTEP = 256 / TPR;
+    const int tf = 4 * (t % TPR), tk = t / TPR;    // tile-fast mapping
+    const int kf = 4 * (t & 3), kt_ = t >> 2;      // k-fast mapping
 
-    floatx16 acc;
+    floatx16 acc[NB][NB];
 #pragma unroll
-    for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc[a][b][x] = 0.f;
 
-    float ra[4], rb[4];
+    f32x4_t ra[NV], rb[NV];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int i = i0 + ai[p], k = k0 + ak[p];
-            ra[p] = (i < v.M && k < v.K) ? load_elem(v.A, (long long)i * v.sAi + (long long)k * v.sAk, v.a_bf16) : 0.f;
-            const int kb = k0 + bk[p], j = j0 + bj[p];
-            rb[p] = (kb < v.K && j < v.Nvalid) ? load_elem(v.B, (long long)kb * v.sBk + (long long)j * v.sBj, v.b_bf16) : 0.f;
+        for (int q = 0; q < NV; ++q) {
+            if (a_i_fast) {
+                const int i = i0 + tf, k = k0 + tk + KSTEP * q;
+                ra[q] = load_vec4(Ap, (long long)i + (long long)k * v.sAk, i, v.M, k < v.K, v.a_bf16);
+            } else {
+                const int i = i0 + kt_ + 64 * q, k = k0 + kf;
+                ra[q] = load_vec4(Ap, (long long)i * v.sAi + (long long)k, k, v.K, i < v.M, v.a_bf16);
+            }
+            if (b_j_fast) {
+                const int j = j0 + tf, k = k0 + tk + KSTEP * q;
+                rb[q] = load_vec4(Bp, (long long)k * v.sBk + (long long)j, j, v.Nvalid, k < v.K, v.b_bf16);
+            } else {
+                const int j = j0 + kt_ + 64 * q, k = k0 + kf;
+                rb[q] = load_vec4(Bp, (long long)k + (long long)j * v.sBj, k, v.K, j < v.Nvalid, v.b_bf16);
+            }
         }
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            As[ak[p]][ai[p]] = ra[p];
-            Bs[bk[p]][bj[p]] = rb[p];
+        for (int q = 0; q < NV; ++q) {
+            if (a_i_fast) {
+                *reinterpret_cast<f32x4_t*>(&As[tk + KSTEP * q][tf]) = ra[q];
+            } else {
+                As[kf][kt_ + 64 * q] = ra[q].x;
+                As[kf + 1][kt_ + 64 * q] = ra[q].y;
+                As[kf + 2][kt_ + 64 * q] = ra[q].z;
+                As[kf + 3][kt_ + 64 * q] = ra[q].w;
+            }
+            if (b_j_fast) {
+                *reinterpret_cast<f32x4_t*>(&Bs[tk + KSTEP * q][tf]) = rb[q];
+            } else {
+                Bs[kf][kt_ + 64 * q] = rb[q].x;
+                Bs[kf + 1][kt_ + 64 * q] = rb[q].y;
+                Bs[kf + 2][kt_ + 64 * q] = rb[q].z;
+                Bs[kf + 3][kt_ + 64 * q] = rb[q].w;
+            }
         }
     };
 
@@ -197,43 +262,62 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
         if (kt + 1 < nk) fetch((kt + 1) * BK);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            const float a = As[kk + h][wm * 32 + li];
-            const float b = Bs[kk + h][wn * 32 + li];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            float a[NB], b[NB];
+#pragma unroll
+            for (int x = 0; x < NB; ++x) {
+                a[x] = As[kk + h][wm * (TS / 2) + 32 * x + li];
+                b[x] = Bs[kk + h][wn * (TS / 2) + 32 * x + li];
+            }
+#pragma unroll
+            for (int x = 0; x < NB; ++x)
+#pragma unroll
+                for (int y = 0; y < NB; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
         }
         __syncthreads();
         if (kt + 1 < nk) stage();
         __syncthreads();
     }
 
-    const int col = j0 + wn * 32 + li;
-    if (col >= v.N) return;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
+    for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int row = i0 + wm * 32 + 8 * g + 4 * h + e;
-            if (row < v.M) {
-                const float x = acc[4 * g + e];
-                const long long idx = (long long)row * v.ldc + col;
-                if (v.epi == EPI_F32) {
-                    reinterpret_cast<float*>(v.C)[idx] = x;
-                } else if (v.epi == EPI_F64) {
-                    reinterpret_cast<double*>(v.C)[idx] = (double)x;
-                } else {
-                    float* W = reinterpret_cast<float*>(v.C);
-                    const float w = W[idx];
-                    W[idx] = w - (sc.lr_scale * x + sc.lr_wd * w);
+        for (int bj = 0; bj < NB; ++bj) {
+            const int col = j0 + wn * (TS / 2) + bj * 32 + li;
+            if (col >= v.N) continue;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int row = i0 + wm * (TS / 2) + bi * 32 + 8 * g + 4 * h + e;
+                    if (row < v.M) {
+                        const float x = acc[bi][bj][4 * g + e];
+                        const long long idx = (long long)row * v.ldc + col;
+                        if (v.epi == EPI_F32) {
+                            reinterpret_cast<float*>(v.C)[idx] = x;
+                        } else if (v.epi == EPI_F64) {
+                            reinterpret_cast<double*>(v.C)[idx] = (double)x;
+                        } else {
+                            float* W = reinterpret_cast<float*>(v.C);
+                            const float w = W[idx];
+                            W[idx] = w - (sc.lr_scale * x + sc.lr_wd * w);
+                        }
+                    }
                 }
             }
         }
-    }
 }
 
-hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_tiles_i,
-                           int max_tiles_j, int grad_dtype, StepScalars sc, hipStream_t stream) {
-    dim3 g(max_tiles_j, max_tiles_i, n_mats);
-    hipLaunchKernelGGL(k_gemm_f32, g, dim3(256), 0, stream, (int)op, mats, dyn, grad_dtype, sc);
+// max_m, max_n, max_k: the largest dimensions of this product over the layer set.  The 128 tile is used
+// when neither side nor the contraction is short (a short side wastes most of a big tile, a short
+// contraction leaves only the read-modify-write of the output, which wants many small workgroups).
+hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m, int max_n,
+                           int max_k, int grad_dtype, StepScalars sc, hipStream_t stream) {
+    const bool big = max_m >= 128 && max_n >= 128 && max_k >= 64;
+    const int ts = big ? 128 : 64;
+    dim3 g((max_n + ts - 1) / ts, (max_m + ts - 1) / ts, n_mats);
+    if (big) hipLaunchKernelGGL(k_gemm_f32<128>, g, dim3(256), 0, stream, (int)op, mats, dyn, grad_dtype, sc);
+    else hipLaunchKernelGGL(k_gemm_f32<64>, g, dim3(256), 0, stream, (int)op, mats, dyn, grad_dtype, sc);
     return hipGetLastError();
 }
 

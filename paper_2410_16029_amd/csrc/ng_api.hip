@@ -190,7 +190,7 @@ struct ng_state {
     int n_dots;
     std::vector<int> dots_begin, patch_begin;   // per matrix: first entry in the tables (+ end sentinel)
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
-    int max_ti[OP_COUNT], max_tj[OP_COUNT];
+    int max_ti[OP_COUNT], max_tj[OP_COUNT], max_tk[OP_COUNT];   // largest M, N, K of each fp32 product
     int max_jpairs, jb_mask;
     size_t jacobi_lds;
     // profiling
@@ -264,7 +264,7 @@ int clear_history(ng_state* st, hipStream_t stream) {
 }
 
 int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
-    NG_HIP(launch_gemm_f32(op, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op],
+    NG_HIP(launch_gemm_f32(op, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], st->max_tk[op],
                            st->hp.grad_dtype, sc, stream));
     return NG_OK;
 }
@@ -413,7 +413,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         st->max_jpairs = 0;
         st->jb_mask = 0;
         st->jacobi_lds = 0;
-        for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = 1;
+        for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = st->max_tk[op] = 1;
         for (int i = 0; i < n_mats; ++i) {
             const Sizes& z = pl.sz[i];
             MatDev& md = st->mats[i];
@@ -469,10 +469,11 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             const size_t jl = (size_t)2 * md.jb * md.lp * sizeof(double);
             if (jl > st->jacobi_lds) st->jacobi_lds = jl;
             for (int op = 0; op < OP_COUNT; ++op) {
-                int M, N;
-                gemm_f32_dims(op, md, &M, &N);
-                if (ceil_div(M, 64) > st->max_ti[op]) st->max_ti[op] = ceil_div(M, 64);
-                if (ceil_div(N, 64) > st->max_tj[op]) st->max_tj[op] = ceil_div(N, 64);
+                int M, N, K;
+                gemm_f32_dims(op, md, &M, &N, &K);
+                if (M > st->max_ti[op]) st->max_ti[op] = M;
+                if (N > st->max_tj[op]) st->max_tj[op] = N;
+                if (K > st->max_tk[op]) st->max_tk[op] = K;
             }
             (void)s_eff;
         }

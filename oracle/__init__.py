@@ -10,13 +10,16 @@ from .natural_galore import (  # noqa: F401
     adam_direction,
     adam_moments,
     back_project_update,
+    back_project_update_right,
     fisher_history_matrix,
     init_state,
     natural_gradient_transform,
     project,
+    project_right,
     push_history,
     refresh_projector,
     round_to_bf16,
     step,
     top_r_left_singular_vectors,
+    top_r_right_singular_vectors,
 )

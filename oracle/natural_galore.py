@@ -29,7 +29,11 @@ Readings of the paper taken here (the paper is silent or inconsistent):
   * update  W <- W - lr * (scale * P N + weight_decay * W)  (Sec. 2.2, update
     equation; scale and weight_decay default to 1 and 0);
   * a refresh keeps M, V and the step counter and clears the history (its slots
-    are coordinates in the old basis).
+    are coordinates in the old basis);
+  * ``side="right"`` projects with the other factor of the compact SVD
+    g = P Sigma Q^T of Sec. 1: R = G Q (m x r) with Q n x r, moments and history
+    m x r, update W - lr * (scale * N Q^T + weight_decay * W).  The paper writes only
+    the left form; the right form is the same method applied to G^T.
 
 Pins (tests/test_oracle_pins.py): the Woodbury route against the explicit
 rn x rn damped-Fisher solve, closed forms for one slot and for orthogonal
@@ -63,7 +67,7 @@ class HParams:
 
 @dataclass
 class OracleState:
-    P: np.ndarray                    # m x r
+    P: np.ndarray                    # m x r (side "left") or n x r (side "right": the Q factor)
     M: np.ndarray                    # r x n
     V: np.ndarray                    # r x n
     H: np.ndarray                    # s x r x n ring buffer
@@ -72,12 +76,19 @@ class OracleState:
     count: int = 0                   # valid slots, min(pushes since clear, s)
     n_refresh: int = 0
     trace: dict = field(default_factory=dict)   # intermediates of the last step
+    side: str = "left"
 
 
-def init_state(m: int, n: int, r: int, s: int) -> OracleState:
-    return OracleState(
-        P=np.zeros((m, r)), M=np.zeros((r, n)), V=np.zeros((r, n)),
-        H=np.zeros((max(s, 0), r, n)))
+def init_state(m: int, n: int, r: int, s: int, side: str = "left") -> OracleState:
+    if side == "left":
+        return OracleState(
+            P=np.zeros((m, r)), M=np.zeros((r, n)), V=np.zeros((r, n)),
+            H=np.zeros((max(s, 0), r, n)))
+    if side == "right":
+        return OracleState(
+            P=np.zeros((n, r)), M=np.zeros((m, r)), V=np.zeros((m, r)),
+            H=np.zeros((max(s, 0), m, r)), side="right")
+    raise ValueError(side)
 
 
 # --------------------------------------------------------------------------
@@ -97,9 +108,24 @@ def top_r_left_singular_vectors(G: np.ndarray, r: int) -> np.ndarray:
     return P * signs
 
 
+def top_r_right_singular_vectors(G: np.ndarray, r: int) -> np.ndarray:
+    """Q of the compact SVD G = P Sigma Q^T, first r columns (Sec. 1), same sign rule."""
+    _, _, Vt = np.linalg.svd(np.asarray(G, dtype=np.float64), full_matrices=False)
+    Q = Vt[:r].T.copy()
+    rows = np.argmax(np.abs(Q), axis=0)
+    signs = np.sign(Q[rows, np.arange(Q.shape[1])])
+    signs[signs == 0] = 1.0
+    return Q * signs
+
+
 def project(P: np.ndarray, G: np.ndarray) -> np.ndarray:
     """Low-rank gradient R = P^T G (Sec. 1, projection equation)."""
     return P.T @ np.asarray(G, dtype=np.float64)
+
+
+def project_right(Q: np.ndarray, G: np.ndarray) -> np.ndarray:
+    """Low-rank gradient from the right factor: R = G Q (m x r)."""
+    return np.asarray(G, dtype=np.float64) @ Q
 
 
 # --------------------------------------------------------------------------
@@ -190,13 +216,25 @@ def back_project_update(W, P, N, lr: float, hp: HParams):
     return W_new
 
 
+def back_project_update_right(W, Q, N, lr: float, hp: HParams):
+    """W <- W - lr * (scale * N Q^T + weight_decay * W): the update of the right-side form."""
+    W = np.asarray(W, dtype=np.float64)
+    W_new = W - lr * (hp.scale * (N @ Q.T) + hp.weight_decay * W)
+    if hp.weight_dtype == "bf16":
+        W_new = round_to_bf16(W_new)
+    return W_new
+
+
 # --------------------------------------------------------------------------
 # The step and the refresh
 # --------------------------------------------------------------------------
 def refresh_projector(state: OracleState, G: np.ndarray) -> None:
-    """P <- top-r left singular vectors of the current gradient; clear history."""
+    """P <- top-r left (right, for side "right") singular vectors of the current gradient; clear history."""
     r = state.P.shape[1]
-    state.P = top_r_left_singular_vectors(G, r)
+    if state.side == "right":
+        state.P = top_r_right_singular_vectors(G, r)
+    else:
+        state.P = top_r_left_singular_vectors(G, r)
     state.H[...] = 0.0
     state.head = 0
     state.count = 0
@@ -210,7 +248,8 @@ def step(state: OracleState, G: np.ndarray, W: np.ndarray, lr: float, hp: HParam
     history, natural-gradient transform, Adam, back-project and update.
     """
     state.t += 1
-    R = project(state.P, G)
+    right = state.side == "right"
+    R = project_right(state.P, G) if right else project(state.P, G)
     tr = {"R": R}
     if hp.s > 0:
         slot = push_history(state, R)
@@ -223,4 +262,6 @@ def step(state: OracleState, G: np.ndarray, W: np.ndarray, lr: float, hp: HParam
     state.M, state.V, N = adam_moments(state.M, state.V, g_nat, state.t, hp)
     tr["N"] = N
     state.trace = tr
+    if right:
+        return back_project_update_right(W, state.P, N, lr, hp)
     return back_project_update(W, state.P, N, lr, hp)

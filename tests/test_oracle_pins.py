@@ -234,6 +234,74 @@ def test_project_is_transpose_product_not_its_transpose():
 
 
 # ------------------------------------------------------------------ integers
+# ------------------------------------------------------------------ right-side form (Q factor of the compact SVD)
+def test_right_projector_orthonormal_lossless_and_eckart_young():
+    rng = np.random.default_rng(21)
+    G = rng.normal(size=(9, 6))
+    sig = np.linalg.svd(G, compute_uv=False)
+    for r in (1, 3, 6):
+        Q = oracle.top_r_right_singular_vectors(G, r)
+        assert Q.shape == (6, r)
+        assert np.allclose(Q.T @ Q, np.eye(r), atol=1e-12)
+        resid = np.linalg.norm(G - oracle.project_right(Q, G) @ Q.T) ** 2
+        assert abs(resid - np.sum(sig[r:] ** 2)) < 1e-10          # Eckart-Young from the right
+        assert np.all(Q[np.argmax(np.abs(Q), axis=0), np.arange(r)] > 0)
+    # the same subspace as the left vectors of the transpose
+    Q = oracle.top_r_right_singular_vectors(G, 3)
+    Pt = oracle.top_r_left_singular_vectors(G.T, 3)
+    assert np.allclose(Q, Pt, atol=1e-10)
+
+
+def test_right_s0_step_is_adam_on_the_projected_variable():
+    # With Q fixed and s = 0: Z = W Q follows torch.optim.Adam driven by R = G Q, and the part of
+    # W outside the span of Q never moves (Q^T Q = I).
+    rng = np.random.default_rng(22)
+    m, n, r = 7, 5, 2
+    Q, _ = np.linalg.qr(rng.normal(size=(n, r)))
+    hp = HParams(s=0)
+    st = oracle.init_state(m, n, r, 0, side="right")
+    st.P = Q
+    W0 = rng.normal(size=(m, n))
+    W = W0.copy()
+    Z = torch.tensor(W0 @ Q, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([Z], lr=1e-2, betas=(hp.beta1, hp.beta2), eps=hp.eps)
+    for _ in range(5):
+        G = rng.normal(size=(m, n))
+        W = oracle.step(st, G, W, 1e-2, hp)
+        Z.grad = torch.tensor(G @ Q)
+        opt.step()
+    assert np.allclose(W @ Q, Z.detach().numpy(), atol=1e-12)
+    comp = np.eye(n) - Q @ Q.T
+    assert np.allclose(W @ comp, W0 @ comp, atol=1e-12)
+
+
+def test_right_step_is_the_left_step_of_the_transposed_problem_and_matches_explicit_fisher():
+    rng = np.random.default_rng(23)
+    m, n, r, s = 6, 4, 2, 3
+    hp = HParams(s=s, lam=0.05, scale=0.5, weight_decay=0.01)
+    Q, _ = np.linalg.qr(rng.normal(size=(n, r)))
+    sr = oracle.init_state(m, n, r, s, side="right")
+    sl = oracle.init_state(n, m, r, s)
+    sr.P = Q.copy()
+    sl.P = Q.copy()
+    Wr = rng.normal(size=(m, n))
+    Wl = Wr.T.copy()
+    slots = collections.deque(maxlen=s)
+    for _ in range(5):
+        G = rng.normal(size=(m, n))
+        Wr = oracle.step(sr, G, Wr, 1e-2, hp)
+        Wl = oracle.step(sl, G.T, Wl, 1e-2, hp)
+        assert np.allclose(Wr, Wl.T, atol=1e-12)
+        assert np.allclose(sr.M, sl.M.T, atol=1e-12) and np.allclose(sr.V, sl.V.T, atol=1e-12)
+        # the transformed gradient against the explicit damped-Fisher solve over the m x r slots
+        R = G @ Q
+        slots.append(R)
+        F = explicit_fisher(list(slots), hp.lam, s, m * r)
+        expect = np.linalg.solve(F, R.reshape(-1)).reshape(m, r)
+        assert np.allclose(sr.trace["g_nat"], expect, rtol=1e-9, atol=1e-12)
+    assert (sr.t, sr.head, sr.count) == (5, 5 % s, s)
+
+
 def test_integer_bookkeeping_across_refresh():
     m, n, r, s = 6, 5, 2, 3
     hp = HParams(s=s)

@@ -71,9 +71,18 @@ enum {
     NG_NBUF
 };
 
+/* Which factor of the gradient's compact SVD g = P Sigma Q^T (paper Sec. 1) projects.
+ * NG_SIDE_LEFT:  R = P^T G (r x n), P is m x r, update W - lr (scale P N + wd W): the form the
+ *                paper writes out.
+ * NG_SIDE_RIGHT: R = G Q (m x r), Q is n x r, update W - lr (scale N Q^T + wd W): the same method
+ *                applied to G^T (the usual choice for m > n: the projector is n x r).  Internally
+ *                the state is that of the transposed problem: every "m" in the buffer shapes below
+ *                reads n and every "n" reads m (P is [n][r]; M, V, H, N are r x ldm). */
+enum { NG_SIDE_LEFT = 0, NG_SIDE_RIGHT = 1 };
+
 typedef struct ng_matrix_desc {
-    int32_t m, n, r;       /* weight is m x n, rank r, 1 <= r <= min(m, n)            */
-    int32_t reserved;      /* must be 0                                               */
+    int32_t m, n, r;       /* weight is m x n (row-major), rank r, 1 <= r <= min(m, n) */
+    int32_t side;          /* NG_SIDE_LEFT | NG_SIDE_RIGHT                            */
     int64_t ld_w, ld_g;    /* leading dimensions of weight and gradient, >= n         */
 } ng_matrix_desc;
 

@@ -22,6 +22,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 NG_F32, NG_BF16 = 0, 1
+NG_SIDE_LEFT, NG_SIDE_RIGHT = 0, 1
 NG_ADAM_STANDARD, NG_ADAM_PRINTED = 0, 1
 NG_OK = 0
 NG_ERR_INVALID_ARG, NG_ERR_SHAPE, NG_ERR_DTYPE, NG_ERR_HPARAM = -1, -2, -3, -4
@@ -33,7 +34,7 @@ PHASE_NAMES = ("project", "gram", "solve", "adam", "update")
 
 
 class ng_matrix_desc(C.Structure):
-    _fields_ = [("m", C.c_int32), ("n", C.c_int32), ("r", C.c_int32), ("reserved", C.c_int32),
+    _fields_ = [("m", C.c_int32), ("n", C.c_int32), ("r", C.c_int32), ("side", C.c_int32),
                 ("ld_w", C.c_int64), ("ld_g", C.c_int64)]
 
 
@@ -100,12 +101,19 @@ def ng_default_hparams() -> ng_hparams:
     return hp
 
 
-def make_descs(shapes: Sequence, r, ld_w=None, ld_g=None):
+def make_descs(shapes: Sequence, r, ld_w=None, ld_g=None, sides=None):
+    """sides: None (all left), "auto" (right where m > n), or one NG_SIDE_* per matrix."""
     n = len(shapes)
     arr = (ng_matrix_desc * n)()
     for i, (m, nn) in enumerate(shapes):
         ri = r[i] if isinstance(r, (list, tuple)) else r
-        arr[i] = ng_matrix_desc(m, nn, ri, 0, (ld_w[i] if ld_w else nn), (ld_g[i] if ld_g else nn))
+        if sides is None:
+            side = NG_SIDE_LEFT
+        elif isinstance(sides, str):
+            side = NG_SIDE_RIGHT if (sides == "auto" and m > nn) or sides == "right" else NG_SIDE_LEFT
+        else:
+            side = sides[i]
+        arr[i] = ng_matrix_desc(m, nn, ri, side, (ld_w[i] if ld_w else nn), (ld_g[i] if ld_g else nn))
     return arr
 
 
@@ -189,7 +197,8 @@ class LayerSet:
 
     def __init__(self, shapes: Sequence, r, *, s=4, lam=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                  weight_decay=0.0, dtype="f32", adam_mode="standard", power_iters=None, oversample=None,
-                 sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False, hist_dtype=None):
+                 sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False, hist_dtype=None,
+                 sides=None):
         self.device = torch.device(device)
         self.shapes = [tuple(x) for x in shapes]
         self.r = r
@@ -210,7 +219,7 @@ class LayerSet:
         self.hist_dtype = hist_dtype if hist_dtype is not None else "f32"
         self.hp = hp
         self.dtype = dtype
-        self.descs = make_descs(self.shapes, r, ld_w, ld_g)
+        self.descs = make_descs(self.shapes, r, ld_w, ld_g, sides)
         self.sizes, self.workspace_bytes = ng_query_sizes(self.descs, hp)
         n = len(self.shapes)
         self.buffers: List[List[torch.Tensor]] = []
@@ -262,8 +271,16 @@ class LayerSet:
         esz = torch.empty((), dtype=dtype).element_size()
         return t[offset:offset + count * esz].view(dtype)
 
+    def side(self, i) -> int:
+        return self.descs[i].side
+
+    def eff_shape(self, i):
+        """(m, n) of the problem the library works on: the weight's shape, swapped on the right side."""
+        m, n = self.shapes[i]
+        return (n, m) if self.descs[i].side == NG_SIDE_RIGHT else (m, n)
+
     def P(self, i):
-        m, _ = self.shapes[i]
+        m, _ = self.eff_shape(i)
         r = self.descs[i].r
         return self._view(i, NG_BUF_P, torch.float32, m * r).view(m, r)
 
@@ -291,7 +308,7 @@ class LayerSet:
     def N(self, i):
         """Update direction as a float32 [r][n] tensor (decodes the octet layout for bf16)."""
         r, ldn = self.descs[i].r, self.layouts[i].ldn
-        n = self.shapes[i][1]
+        n = self.eff_shape(i)[1]
         if self.dtype == "f32":
             return self._view(i, NG_BUF_N, torch.float32, r * ldn).view(r, ldn)[:, :n]
         roct = (r + 7) // 8

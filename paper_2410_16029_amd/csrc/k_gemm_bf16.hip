@@ -208,6 +208,75 @@ struct BTLoader {
     }
 };
 
+// ------------------------------------------------------------------ B operand = rows of G, contraction contiguous
+// Right-side projection: B(k, j) = G[j][k], so a tile column is a row of the caller's gradient and
+// needs no transpose.  Chunk c = t + NT*p: column c / KC, k-chunk c % KC (the same for every p).
+// Columns >= j_lim and k >= k_lim are zero.  K8: k_lim % 8 == 0 (every chunk whole or empty);
+// otherwise the one chunk that straddles k_lim is read element by element.
+template <class C>
+struct BKLoader {
+    static constexpr int CH = C::BN * C::KC / C::NT;
+    gbf16_cptr base;
+    unsigned coloff[CH];
+    unsigned colok;    // bit p
+    int kofs, k_lim;
+    int nvalid;        // elements of the current chunk inside k_lim (0..8), set by load
+    u32x4_t r[CH];
+
+    __device__ __forceinline__ void init(const void* G, long long ld, int j0, int j_lim, int k_lim_, int t) {
+        base = (gbf16_cptr)G;
+        kofs = (t % C::KC) * 8;
+        k_lim = k_lim_;
+        colok = 0;
+#pragma unroll
+        for (int p = 0; p < CH; ++p) {
+            const int j = j0 + (t + C::NT * p) / C::KC;
+            const bool ok = j < j_lim;
+            colok |= ok ? (1u << p) : 0u;
+            coloff[p] = (unsigned)(ok ? j : j_lim - 1) * (unsigned)ld;
+        }
+    }
+    template <bool K8>
+    __device__ __forceinline__ void load(int k0) {
+        const int k = k0 + kofs;
+        nvalid = k_lim - k;
+        nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
+        if (K8 || nvalid == 8 || nvalid == 0) {
+            const unsigned kc = (unsigned)(nvalid == 8 ? k : (k_lim >= 8 ? k_lim - 8 : 0));
+            if (K8 || k_lim >= 8) {
+#pragma unroll
+                for (int p = 0; p < CH; ++p) r[p] = *(const NG_AS1 u32x4_a2*)(base + (coloff[p] + kc));
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < CH; ++p) {
+                unsigned int e[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) e[x] = x < nvalid ? (unsigned int)base[coloff[p] + (unsigned)(k + x)] : 0u;
+                r[p].x = e[0] | (e[1] << 16);
+                r[p].y = e[2] | (e[3] << 16);
+                r[p].z = e[4] | (e[5] << 16);
+                r[p].w = e[6] | (e[7] << 16);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(bf16_t* Bs, int t) const {
+#pragma unroll
+        for (int p = 0; p < CH; ++p) {
+            const int c = t + C::NT * p;
+            const bool ok = nvalid > 0 && ((colok >> p) & 1u);
+            *reinterpret_cast<u32x4_t*>(Bs + (c / C::KC) * C::LDS_K + (c % C::KC) * 8) = zero_unless(ok, r[p]);
+        }
+    }
+};
+
+template <class C, bool K8>
+struct BKView {
+    BKLoader<C>& l;
+    __device__ __forceinline__ void load(int k0) { l.template load<K8>(k0); }
+    __device__ __forceinline__ void store(bf16_t* Bs, int t) const { l.store(Bs, t); }
+};
+
 // ------------------------------------------------------------------ one BK-deep MFMA sweep
 // Fragments of step kk+1 are read from LDS while the MFMAs of step kk run.
 template <class C>
@@ -289,8 +358,9 @@ __device__ __forceinline__ void gemm_mainloop(floatx16 (&acc)[C::MI][C::NJ], LA&
     }
 }
 
-// HB: the ring slot receives bf16 instead of float.
-template <class C, bool HB>
+// HB: the ring slot receives bf16 instead of float.  RIGHT: the right-side form (the kernel's m x n
+// problem is the transpose of the caller's gradient: its columns are the gradient's rows).
+template <class C, bool HB, bool RIGHT>
 __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict__ mats,
                                                         const MatDyn* __restrict__ dyn,
                                                         const TileRef* __restrict__ tiles) {
@@ -299,6 +369,7 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
     const TileRef tr = tiles[blockIdx.x];
     if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
     const MatDev& md = mats[tr.mat];
+    if ((md.side == NG_SIDE_RIGHT) != RIGHT) return;   // the other instance of the launch pair takes it
     const MatDyn dy = dyn[tr.mat];
     const int i0 = tr.ti * C::BM, j0 = tr.tj * C::BN;
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
@@ -309,18 +380,30 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
     zero_acc<C>(acc);
 
     ALoader<C> la;
-    BTLoader<C> lb;
     la.init(md.PbT, md.ldk, i0, r, md.ldk, t);
-    lb.init(dy.g, md.ld_g, m, n, j0, t);
     const int nk = (m + C::BK - 1) / C::BK;
-    // uniform per workgroup: are all 8-column chunks of this tile whole?
-    const bool full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
-    if (full) {
-        BTView<C, true> v{lb};
-        gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+    if (!RIGHT) {
+        BTLoader<C> lb;
+        lb.init(dy.g, md.ld_g, m, n, j0, t);
+        // uniform per workgroup: are all 8-column chunks of this tile whole?
+        const bool full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
+        if (full) {
+            BTView<C, true> v{lb};
+            gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+        } else {
+            BTView<C, false> v{lb};
+            gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+        }
     } else {
-        BTView<C, false> v{lb};
-        gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+        BKLoader<C> lb;
+        lb.init(dy.g, md.ld_g, j0, n, m, t);
+        if ((m & 7) == 0) {
+            BKView<C, true> v{lb};
+            gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+        } else {
+            BKView<C, false> v{lb};
+            gemm_mainloop<C>(acc, la, v, smem, nk, t, wm, wn, li, h);
+        }
     }
 
     if (!HB) {
@@ -508,80 +591,136 @@ __device__ __forceinline__ void wait_vmcnt() {   // at most N vector-memory load
     __builtin_amdgcn_s_waitcnt(0x0F70 | N);       // expcnt 7, lgkmcnt 15: not waited for
 }
 
-template <class C, int DBK, int NST>
+// One operand of the update as a source of 16-byte chunks, R tile rows (of A) or columns (of B):
+//   RowMajorSrc: bf16 [rows][ldr], contraction contiguous (Pb).  A wave-instruction covers 64 / KC
+//                rows; chunk kc of a row sits at slot row * KC + (kc ^ swz(row)).
+//   OctetSrc:    the octet layout [r/8][ldn][8] of N.  A wave-instruction covers 64 consecutive
+//                rows of one octet; slot kc * R + row.
+template <class C, int DBK, int R>
+struct RowMajorSrc {
+    static constexpr int KC = DBK / 8, INSTR = R * KC / C::NT, RPI = 64 / KC;
+    const NG_AS1 unsigned char* ptr[INSTR];
+    unsigned ok;
+    int kc, ldr;
+    __device__ __forceinline__ void init(const bf16_t* base, int ldr_, int row0, int row_lim, int lane, int wv) {
+        const int lrow = lane / KC;
+        kc = KC == 8 ? ((lane & 7) ^ (lrow & 7)) : ((lane & 3) ^ ((lrow >> 2) & 3));
+        ldr = ldr_;
+        ok = 0;
+#pragma unroll
+        for (int p = 0; p < INSTR; ++p) {
+            const int row = row0 + (p * C::NW + wv) * RPI + lrow;
+            const bool in = row < row_lim;
+            ok |= in ? (1u << p) : 0u;
+            ptr[p] = (const NG_AS1 unsigned char*)base + ((long long)(in ? row : 0) * ldr + kc * 8) * 2;
+        }
+    }
+    __device__ __forceinline__ void issue(int kt, unsigned char* stage, const NG_AS1 unsigned char* zp, int wv) const {
+        const bool kok = kt * DBK + kc * 8 < ldr;
+#pragma unroll
+        for (int p = 0; p < INSTR; ++p) {
+            const bool in = kok && ((ok >> p) & 1u);
+            const NG_AS1 unsigned char* g = in ? ptr[p] + (long long)kt * (DBK * 2) : zp;
+            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g, (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16,
+                                             0, 0);
+        }
+    }
+    // byte offset of the fragment (tile row `row`, k-slot ks) inside the operand's stage
+    static __device__ __forceinline__ int frag(int row, int sw, int ks) { return (row * KC + (ks ^ sw)) * 16; }
+    static __device__ __forceinline__ int swz(int li) { return KC == 8 ? (li & 7) : ((li >> 2) & 3); }
+};
+
+template <class C, int DBK, int R>
+struct OctetSrc {
+    static constexpr int KC = DBK / 8, INSTR = R * KC / C::NT, GR = R / 64;
+    const NG_AS1 unsigned char* ptr[INSTR];
+    int oct[INSTR];
+    bool rowok[INSTR];
+    int roct;
+    long long step;
+    __device__ __forceinline__ void init(const void* base, int ldn, int roct_, int row0, int lane, int wv) {
+        roct = roct_;
+        step = (long long)ldn * KC * 16;   // KC octets per stage
+#pragma unroll
+        for (int p = 0; p < INSTR; ++p) {
+            const int q = p * C::NW + wv;
+            const int row = row0 + (q % GR) * 64 + lane;
+            oct[p] = q / GR;
+            rowok[p] = row < ldn;
+            ptr[p] = (const NG_AS1 unsigned char*)base + ((long long)oct[p] * ldn + (rowok[p] ? row : 0)) * 16;
+        }
+    }
+    __device__ __forceinline__ void issue(int kt, unsigned char* stage, const NG_AS1 unsigned char* zp, int wv) const {
+#pragma unroll
+        for (int p = 0; p < INSTR; ++p) {
+            const bool in = rowok[p] && (kt * KC + oct[p] < roct);
+            const NG_AS1 unsigned char* g = in ? ptr[p] + kt * step : zp;
+            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g, (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16,
+                                             0, 0);
+        }
+    }
+    static __device__ __forceinline__ int frag(int row, int, int ks) { return (ks * R + row) * 16; }
+    static __device__ __forceinline__ int swz(int) { return 0; }
+};
+
+// RIGHT: the right-side form.  The tile still covers the caller's weight in its own orientation
+// (rows = the weight's rows); the roles of the two stored operands swap: A rows come from the octet
+// layout of N (r x ldn with n = the weight's row count), B columns from Pb (one row per weight column).
+template <class C, int DBK, int NST, bool RIGHT>
 __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restrict__ mats,
                                                           const MatDyn* __restrict__ dyn,
                                                           const TileRef* __restrict__ tiles, StepScalars sc,
                                                           const void* zero16) {
     typedef DlCfg<C, DBK, NST> D;
-    constexpr int KC = D::KC, KK = DBK / 16;
+    constexpr int KK = DBK / 16;
+    typedef RowMajorSrc<C, DBK, C::BM> ARows;
+    typedef OctetSrc<C, DBK, C::BM> AOct;
+    typedef RowMajorSrc<C, DBK, C::BN> BRows;
+    typedef OctetSrc<C, DBK, C::BN> BOct;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const TileRef tr = tiles[blockIdx.x];
     if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
     const MatDev& md = mats[tr.mat];
+    if ((md.side == NG_SIDE_RIGHT) != RIGHT) return;   // the other instance of the launch pair takes it
     const MatDyn dy = dyn[tr.mat];
     const int i0 = tr.ti * C::BM, j0 = tr.tj * C::BN;
     const int t = threadIdx.x, lane = t & 63;
     const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wv / C::NWN, wn = wv % C::NWN, li = lane & 31, h = lane >> 5;
-    const int m = md.m, n = md.n, ldn = md.ldn, ldr = md.ldr, roct = md.roct;
-    const int nk = (roct * 8 + DBK - 1) / DBK;
+    const int m = RIGHT ? md.n : md.m, n = RIGHT ? md.m : md.n;   // the weight's rows and columns
+    const int nk = (md.roct * 8 + DBK - 1) / DBK;
 
     floatx16 acc[C::MI][C::NJ];
     zero_acc<C>(acc);
 
     const NG_AS1 unsigned char* zp = (const NG_AS1 unsigned char*)zero16;
-    // A chunks: wave-instruction q = p * NW + wv covers slots 64 q .. 64 q + 63 = 64 / KC rows
-    constexpr int RPI = 64 / KC;                              // rows per wave-instruction
-    const int lrow = lane / KC;                               // row within the instruction
-    const int kcA = KC == 8 ? ((lane & 7) ^ (lrow & 7)) : ((lane & 3) ^ ((lrow >> 2) & 3));
-    const NG_AS1 unsigned char* a_ptr[D::A_INSTR];
-    unsigned a_ok = 0;
-#pragma unroll
-    for (int p = 0; p < D::A_INSTR; ++p) {
-        const int row = i0 + (p * C::NW + wv) * RPI + lrow;
-        const bool ok = row < m;
-        a_ok |= ok ? (1u << p) : 0u;
-        a_ptr[p] = (const NG_AS1 unsigned char*)md.Pb + ((long long)(ok ? row : 0) * ldr + kcA * 8) * 2;
+    ARows a_rm;
+    AOct a_oc;
+    BRows b_rm;
+    BOct b_oc;
+    if (!RIGHT) {
+        a_rm.init(md.Pb, md.ldr, i0, m, lane, wv);
+        b_oc.init(md.N, md.ldn, md.roct, j0, lane, wv);
+    } else {
+        a_oc.init(md.N, md.ldn, md.roct, i0, lane, wv);
+        b_rm.init(md.Pb, md.ldr, j0, n, lane, wv);
     }
-    // B chunks: wave-instruction q covers octet q / (BN/64), columns (q % (BN/64)) * 64 + lane
-    const NG_AS1 unsigned char* b_ptr[D::B_INSTR];
-    int b_oct[D::B_INSTR];
-    bool b_colok[D::B_INSTR];
-#pragma unroll
-    for (int p = 0; p < D::B_INSTR; ++p) {
-        const int q = p * C::NW + wv;
-        const int col = j0 + (q % (C::BN / 64)) * 64 + lane;
-        b_oct[p] = q / (C::BN / 64);
-        b_colok[p] = col < ldn;
-        b_ptr[p] = (const NG_AS1 unsigned char*)md.N + ((long long)b_oct[p] * ldn + (b_colok[p] ? col : 0)) * 16;
-    }
-    const long long b_step = (long long)ldn * KC * 16;   // KC octets per stage
-
     auto issue = [&](int kt) {
         unsigned char* stage = smem + (kt % NST) * D::STAGE;
-        const bool kokA = kt * DBK + kcA * 8 < ldr;
-#pragma unroll
-        for (int p = 0; p < D::A_INSTR; ++p) {
-            const bool ok = kokA && ((a_ok >> p) & 1u);
-            const NG_AS1 unsigned char* g = ok ? a_ptr[p] + (long long)kt * (DBK * 2) : zp;
-            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g,
-                                             (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16, 0, 0);
-        }
-#pragma unroll
-        for (int p = 0; p < D::B_INSTR; ++p) {
-            const bool ok = b_colok[p] && (kt * KC + b_oct[p] < roct);
-            const NG_AS1 unsigned char* g = ok ? b_ptr[p] + kt * b_step : zp;
-            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g,
-                                             (NG_AS3 void*)(stage + D::A_BYTES + (p * C::NW + wv) * 1024), 16, 0, 0);
+        if (!RIGHT) {
+            a_rm.issue(kt, stage, zp, wv);
+            b_oc.issue(kt, stage + D::A_BYTES, zp, wv);
+        } else {
+            a_oc.issue(kt, stage, zp, wv);
+            b_rm.issue(kt, stage + D::A_BYTES, zp, wv);
         }
     };
 
     // fragment addresses inside a stage
     const int a_row = wm * C::WM + li;                       // + 32 mi
-    const int a_sw = KC == 8 ? (li & 7) : ((li >> 2) & 3);
     const int b_col = wn * C::WN + li;                       // + 32 nj
+    const int a_sw = RIGHT ? 0 : ARows::swz(li), b_sw = RIGHT ? BRows::swz(li) : 0;
 
     // Ring: stage kt lives in buffer kt % NST.  Before stage kt is multiplied, the loads of the
     // stages up to kt + NST - 2 have been issued; waiting until at most (NST - 2) stages' worth of
@@ -607,10 +746,13 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restri
             const int ks = 2 * kk + h;
 #pragma unroll
             for (int mi = 0; mi < C::MI; ++mi)
-                a[kk][mi] = *reinterpret_cast<const u32x4_t*>(cur + ((a_row + 32 * mi) * KC + (ks ^ a_sw)) * 16);
+                a[kk][mi] = *reinterpret_cast<const u32x4_t*>(
+                    cur + (RIGHT ? AOct::frag(a_row + 32 * mi, 0, ks) : ARows::frag(a_row + 32 * mi, a_sw, ks)));
 #pragma unroll
             for (int nj = 0; nj < C::NJ; ++nj)
-                b[kk][nj] = *reinterpret_cast<const u32x4_t*>(cur + D::A_BYTES + (ks * C::BN + b_col + 32 * nj) * 16);
+                b[kk][nj] = *reinterpret_cast<const u32x4_t*>(
+                    cur + D::A_BYTES +
+                    (RIGHT ? BRows::frag(b_col + 32 * nj, b_sw, ks) : BOct::frag(b_col + 32 * nj, 0, ks)));
         }
         // all fragment reads of the stage are issued before the first MFMA (left alone, the
         // scheduler reuses a few registers and alternates 4 reads - full wait - 4 MFMAs)
@@ -645,42 +787,58 @@ typedef Cfg<256, 128, 128, 64, 64> Cfg2;
 static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
 
 template <class C, bool HB>
-static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
+static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles, int sides,
                               hipStream_t stream) {
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         attr = true;
     }
-    hipLaunchKernelGGL((k_project_bf16<C, HB>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn, tiles);
+    if (sides & 1)
+        hipLaunchKernelGGL((k_project_bf16<C, HB, false>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
+                           tiles);
+    if (sides & 2)
+        hipLaunchKernelGGL((k_project_bf16<C, HB, true>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
+                           tiles);
     return hipGetLastError();
 }
 
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, int hist_bf16, hipStream_t stream) {
+                               int max_r, int hist_bf16, int sides, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
     if (project_cfg(max_r) == 0)
-        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_tiles, stream)
-                         : run_project<Cfg0, false>(mats, dyn, tiles, n_tiles, stream);
-    return hist_bf16 ? run_project<Cfg2, true>(mats, dyn, tiles, n_tiles, stream)
-                     : run_project<Cfg2, false>(mats, dyn, tiles, n_tiles, stream);
+        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_tiles, sides, stream)
+                         : run_project<Cfg0, false>(mats, dyn, tiles, n_tiles, sides, stream);
+    return hist_bf16 ? run_project<Cfg2, true>(mats, dyn, tiles, n_tiles, sides, stream)
+                     : run_project<Cfg2, false>(mats, dyn, tiles, n_tiles, sides, stream);
 }
 
+// sides: bit 0 = the layer set has left-side matrices, bit 1 = right-side ones.  Each side has its own
+// instance of the kernel over the same tile table; a workgroup whose matrix belongs to the other
+// side exits at once.
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                              StepScalars sc, const void* zero16, hipStream_t stream) {
+                              StepScalars sc, const void* zero16, int sides, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
     typedef Cfg2 C;
     constexpr int DBK = 32, NST = 3;   // 72 KiB of LDS: two workgroups per CU
     constexpr int lds = DlCfg<C, DBK, NST>::LDS_BYTES;
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_bf16_dl<C, DBK, NST>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_bf16_dl<C, DBK, NST, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_bf16_dl<C, DBK, NST, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr = true;
     }
-    hipLaunchKernelGGL((k_update_bf16_dl<C, DBK, NST>), dim3(n_tiles), dim3(C::NT), lds, stream, mats, dyn, tiles, sc,
-                       zero16);
+    if (sides & 1)
+        hipLaunchKernelGGL((k_update_bf16_dl<C, DBK, NST, false>), dim3(n_tiles), dim3(C::NT), lds, stream, mats, dyn,
+                           tiles, sc, zero16);
+    if (sides & 2)
+        hipLaunchKernelGGL((k_update_bf16_dl<C, DBK, NST, true>), dim3(n_tiles), dim3(C::NT), lds, stream, mats, dyn,
+                           tiles, sc, zero16);
     return hipGetLastError();
 }
 

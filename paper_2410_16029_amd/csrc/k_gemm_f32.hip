@@ -21,7 +21,7 @@ struct GemmView {
     const void* A;
     const void* B;
     void* C;
-    long long sAi, sAk, sBk, sBj, ldc;
+    long long sAi, sAk, sBk, sBj, ldc;     // C is always row-major with leading dimension ldc
     int M, N, K;      // C is M x N, contraction length K
     int Nvalid;       // columns j >= Nvalid of B read as zero (padding columns of the r x ldn space)
     int a_bf16, b_bf16;
@@ -35,29 +35,40 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
     v.epi = EPI_F32;
     const int gb = (grad_dtype == NG_BF16) ? 1 : 0;
     const void* G = dy ? dy->g : nullptr;
+    // Strides of the m x n matrix the kernels see inside the caller's row-major gradient: for the
+    // right side that matrix is the transpose of the caller's.
+    const bool right = md.side == NG_SIDE_RIGHT;
+    const long long g_row = right ? 1 : md.ld_g, g_col = right ? md.ld_g : 1;
     switch (op) {
         case OP_PROJECT_F32:
             v.A = md.P; v.sAi = 1; v.sAk = md.r;
-            v.B = G; v.sBk = md.ld_g; v.sBj = 1; v.b_bf16 = gb;
+            v.B = G; v.sBk = g_row; v.sBj = g_col; v.b_bf16 = gb;
             v.M = md.r; v.N = md.ldn; v.Nvalid = md.n; v.K = md.m;
             v.C = md.H + (long long)(dy ? dy->head : 0) * md.slot_elems; v.ldc = md.ldn;
             break;
         case OP_UPDATE_F32:
-            v.A = md.P; v.sAi = md.r; v.sAk = 1;
-            v.B = md.N; v.sBk = md.ldn; v.sBj = 1;
-            v.M = md.m; v.N = md.n; v.Nvalid = md.n; v.K = md.r;
+            if (!right) {       // W (m x n) -= P N
+                v.A = md.P; v.sAi = md.r; v.sAk = 1;
+                v.B = md.N; v.sBk = md.ldn; v.sBj = 1;
+                v.M = md.m; v.N = md.n; v.Nvalid = md.n;
+            } else {            // the caller's W is n x m here: W -= N^T P^T, in W's own orientation
+                v.A = md.N; v.sAi = 1; v.sAk = md.ldn;
+                v.B = md.P; v.sBk = 1; v.sBj = md.r;
+                v.M = md.n; v.N = md.m; v.Nvalid = md.m;
+            }
+            v.K = md.r;
             v.C = dy ? dy->w : nullptr; v.ldc = md.ld_w; v.epi = EPI_W_F32;
             break;
         case OP_G_B2A:
         case OP_G_C2A:
-            v.A = G; v.sAi = md.ld_g; v.sAk = 1; v.a_bf16 = gb;
+            v.A = G; v.sAi = g_row; v.sAk = g_col; v.a_bf16 = gb;
             v.B = (op == OP_G_B2A) ? md.Yb : md.Yc; v.sBk = md.l; v.sBj = 1;
             v.M = md.m; v.N = md.l; v.Nvalid = md.l; v.K = md.n;
             v.C = md.Ya; v.ldc = md.l;
             break;
         case OP_GT_A2B:
         case OP_GT_C2B:
-            v.A = G; v.sAi = 1; v.sAk = md.ld_g; v.a_bf16 = gb;
+            v.A = G; v.sAi = g_col; v.sAk = g_row; v.a_bf16 = gb;
             v.B = (op == OP_GT_A2B) ? md.Ya : md.Yc; v.sBk = md.l; v.sBj = 1;
             v.M = md.n; v.N = md.l; v.Nvalid = md.l; v.K = md.m;
             v.C = md.Yb; v.ldc = md.l;
@@ -89,7 +100,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
         }
         case OP_QT_G:
             v.A = md.Ya; v.sAi = 1; v.sAk = md.l;
-            v.B = G; v.sBk = md.ld_g; v.sBj = 1; v.b_bf16 = gb;
+            v.B = G; v.sBk = g_row; v.sBj = g_col; v.b_bf16 = gb;
             v.M = md.l; v.N = md.ldn; v.Nvalid = md.n; v.K = md.m;
             v.C = md.Bm; v.ldc = md.ldn;
             break;

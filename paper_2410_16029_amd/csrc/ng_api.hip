@@ -46,20 +46,32 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
         if (x.m <= 0 || x.n <= 0 || x.r <= 0) return NG_ERR_SHAPE;
         if (x.r > x.m || x.r > x.n) return NG_ERR_SHAPE;
         if (x.ld_w < x.n || x.ld_g < x.n) return NG_ERR_SHAPE;
-        if (x.reserved != 0) return NG_ERR_INVALID_ARG;
+        if (x.side != NG_SIDE_LEFT && x.side != NG_SIDE_RIGHT) return NG_ERR_INVALID_ARG;
         if ((long long)x.m > (1 << 24) || (long long)x.n > (1 << 24)) return NG_ERR_SHAPE;
         if ((long long)x.r + hp->refresh_oversample > 2048) return NG_ERR_SHAPE;   // LDS budget of the Jacobi blocks
         // the kernels address one matrix with 32-bit offsets
         const long long ldmax = x.ld_w > x.ld_g ? x.ld_w : x.ld_g;
         if ((long long)x.m * ldmax * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
-        if ((long long)x.r * (x.n + 32) * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
+        if ((long long)x.r * ((x.m > x.n ? x.m : x.n) + 32) * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
     }
     return NG_OK;
 }
 
 bool hist_is_bf16(const ng_hparams& hp) { return hp.hist_dtype == NG_BF16; }
 
-void derive(const ng_matrix_desc& d, const ng_hparams& hp, Sizes* z) {
+// The descriptor of the problem the kernels see: the right-side form is the left-side form of the
+// transposed matrix (m and n swapped; the leading dimensions still describe the caller's arrays).
+ng_matrix_desc effective(const ng_matrix_desc& u) {
+    ng_matrix_desc d = u;
+    if (u.side == NG_SIDE_RIGHT) {
+        d.m = u.n;
+        d.n = u.m;
+    }
+    return d;
+}
+
+void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
+    const ng_matrix_desc d = effective(user);
     memset(z, 0, sizeof(*z));
     const int s = hp.s;
     z->ldn = (int)align_up((size_t)d.n, 32);
@@ -143,6 +155,7 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         if (hp.grad_dtype == NG_BF16) {
             for (int tj = 0; tj < ceil_div(z.ldn, pbn); ++tj)
                 for (int ti = 0; ti < ceil_div(d[i].r, pbm); ++ti) proj.push_back(TileRef{i, ti, tj, 0});
+            // update tiles cover the weight in the caller's orientation on either side
             for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
                 for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
         }
@@ -192,6 +205,7 @@ struct ng_state {
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
     int max_ti[OP_COUNT], max_tj[OP_COUNT], max_tk[OP_COUNT];   // largest M, N, K of each fp32 product
     int max_jpairs, jb_mask;
+    int sides;       // bit 0: left-side matrices present, bit 1: right-side ones
     size_t jacobi_lds;
     // profiling
     bool profiling;
@@ -412,13 +426,17 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
         st->max_jpairs = 0;
         st->jb_mask = 0;
+        st->sides = 0;
         st->jacobi_lds = 0;
         for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = st->max_tk[op] = 1;
         for (int i = 0; i < n_mats; ++i) {
             const Sizes& z = pl.sz[i];
             MatDev& md = st->mats[i];
             memset(&md, 0, sizeof(md));
-            md.m = descs[i].m; md.n = descs[i].n; md.r = descs[i].r; md.ldn = z.ldn;
+            const ng_matrix_desc ed = effective(descs[i]);
+            md.m = ed.m; md.n = ed.n; md.r = ed.r; md.ldn = z.ldn;
+            md.side = descs[i].side;
+            st->sides |= descs[i].side == NG_SIDE_RIGHT ? 2 : 1;
             md.l = z.l; md.ldk = z.ldk; md.ldr = z.ldr; md.roct = z.roct;
             md.ld_w = descs[i].ld_w; md.ld_g = descs[i].ld_g;
             md.slot_elems = (long long)md.r * z.ldn;
@@ -614,7 +632,7 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, sc.hist_bf16, stream));
+    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, sc.hist_bf16, st->sides, stream));
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
@@ -629,7 +647,7 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
     if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc,
-                                      (const char*)st->d_status + 64, stream));
+                                      (const char*)st->d_status + 64, st->sides, stream));
     else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) {

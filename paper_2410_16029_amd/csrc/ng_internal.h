@@ -19,7 +19,10 @@ constexpr int kJacobiLdsBudget = 139264;   // bytes of LDS the blocked Jacobi ma
 
 // Static per-matrix description, lives in the workspace (device) and in the handle (host).
 struct MatDev {
+    // m, n: dimensions of the problem the kernels see: the weight's for NG_SIDE_LEFT, swapped for
+    // NG_SIDE_RIGHT (the transposed problem); ld_w / ld_g always describe the caller's row-major arrays
     int m, n, r, ldn;
+    int side;
     int l;            // refresh sketch width
     int ldk;          // row length of PbT (m rounded up to 8)
     int ldr;          // row length of Pb (r rounded up to 8)
@@ -120,11 +123,12 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
 
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
+// sides: bit 0 = left-side matrices present, bit 1 = right-side ones (one kernel instance each)
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, int hist_bf16, hipStream_t stream);
+                               int max_r, int hist_bf16, int sides, hipStream_t stream);
 // zero16: 16 bytes of zeros in device memory (fetched in place of out-of-range operand chunks)
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                              StepScalars sc, const void* zero16, hipStream_t stream);
+                              StepScalars sc, const void* zero16, int sides, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,

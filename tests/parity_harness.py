@@ -43,7 +43,8 @@ class Lockstep:
         self.states = {}
         for i in self.check:
             m, n = ls.shapes[i]
-            self.states[i] = oracle.init_state(m, n, ls.descs[i].r, ls.hp.s)
+            side = "right" if ls.side(i) == B.NG_SIDE_RIGHT else "left"
+            self.states[i] = oracle.init_state(m, n, ls.descs[i].r, ls.hp.s, side)
         self.Wo = {}
 
     def adopt_gpu_projector(self):
@@ -92,12 +93,16 @@ class Lockstep:
         out = {}
         for i in self.check:
             st = self.states[i]
-            n = ls.shapes[i][1]
+            # The library holds the r x n state of the problem it works on; on the right side that
+            # is the transposed problem, so the oracle's m x r tensors are compared transposed.
+            right = st.side == "right"
+            n = ls.eff_shape(i)[1]
+            T = (lambda x: x.T) if right else (lambda x: x)
             self.Wo[i] = oracle.step(st, to_f64(grads[i]), self.Wo[i], lr, self.ohp)
             tr = st.trace
             e = {}
             H = ls.H(i)
-            e["R"] = rel_err(to_f64(H[slot[i] if ls.hp.s > 0 else 0][:, :n]), tr["R"])
+            e["R"] = rel_err(to_f64(H[slot[i] if ls.hp.s > 0 else 0][:, :n]), T(tr["R"]))
             if ls.hp.s > 0:
                 assert tr["slot"] == slot[i]
                 e["K_row"] = rel_err(to_f64(ls.K(i)[slot[i]]), tr["K"][slot[i]])
@@ -107,10 +112,10 @@ class Lockstep:
                 w_ref = np.linalg.solve(self.ohp.lam * np.eye(s) + tr["K"] / s, np.eye(s)[slot[i]])
                 e["w"] = rel_err(to_f64(ls.w(i)), w_ref)
                 e["pad"] = float(H[:, :, n:].abs().max().item()) if H.shape[2] > n else 0.0
-            e["M"] = rel_err(to_f64(ls.M(i)[:, :n]), st.M)
-            e["V"] = rel_err(to_f64(ls.V(i)[:, :n]), st.V)
+            e["M"] = rel_err(to_f64(ls.M(i)[:, :n]), T(st.M))
+            e["V"] = rel_err(to_f64(ls.V(i)[:, :n]), T(st.V))
             Ng = to_f64(ls.N(i))
-            N0 = tr["N"]
+            N0 = T(tr["N"])
             e["N"] = rel_err(Ng, N0)
             nmax = np.max(np.abs(N0))
             Nf = oracle.adam_direction(to_f64(ls.M(i)[:, :n]), to_f64(ls.V(i)[:, :n]), st.t, self.ohp)
@@ -119,9 +124,11 @@ class Lockstep:
             Wp = prev[i][2]
             Wg = to_f64(weights[i])
             e["W"] = rel_err(Wg, self.Wo[i])
-            W_expect = oracle.back_project_update(Wp, st.P, Ng, lr, self.ohp)
+            upd = (lambda hp_: oracle.back_project_update_right(Wp, st.P, Ng.T, lr, hp_)) if right else \
+                  (lambda hp_: oracle.back_project_update(Wp, st.P, Ng, lr, hp_))
+            W_expect = upd(self.ohp)
             dmax = np.max(np.abs(W_expect - Wp))
-            x = oracle.back_project_update(Wp, st.P, Ng, lr, dataclasses.replace(self.ohp, weight_dtype="f32"))
+            x = upd(dataclasses.replace(self.ohp, weight_dtype="f32"))
             d = self.tol * dmax
             if ls.dtype == "bf16":
                 big = np.maximum(np.maximum(np.abs(W_expect), np.abs(Wg)), 1e-30)

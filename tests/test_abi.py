@@ -53,6 +53,14 @@ def test_query_sizes_c1_and_bf16_layout():
     assert sizes16[0][B.NG_BUF_M] == 512 * ldn * 4
     hp.hist_dtype = B.NG_F32
     assert sizes[0][B.NG_BUF_AUX] >= 2 * 2048 * 512 * 2
+    # right side: the projector is n x r and the r-space state is r x ldm
+    hp.hist_dtype = B.NG_F32
+    descs = B.make_descs([(5461, 2048)], 512, sides="auto")
+    assert descs[0].side == B.NG_SIDE_RIGHT
+    right, _ = B.ng_query_sizes(descs, hp)
+    assert right[0][B.NG_BUF_P] == 2048 * 512 * 4
+    assert right[0][B.NG_BUF_M] == 512 * 5472 * 4
+    descs = B.make_descs([(2048, 5461)], 512)
     # s = 0 keeps one scratch slot for the projected gradient
     hp.s = 0
     sizes, _ = B.ng_query_sizes(descs, hp)
@@ -78,7 +86,7 @@ def test_query_sizes_c1_and_bf16_layout():
     (lambda d, hp: setattr(d[0], "m", 0), B.NG_ERR_SHAPE),
     (lambda d, hp: setattr(d[0], "ld_w", 100), B.NG_ERR_SHAPE),   # ld < n
     (lambda d, hp: setattr(d[0], "ld_g", 511), B.NG_ERR_SHAPE),
-    (lambda d, hp: setattr(d[0], "reserved", 1), B.NG_ERR_INVALID_ARG),
+    (lambda d, hp: setattr(d[0], "side", 2), B.NG_ERR_INVALID_ARG),
 ])
 def test_argument_validation(mutate, code):
     hp = B.ng_default_hparams()

@@ -133,6 +133,17 @@ def test_fine_tuning_shaped_block(name, dtype):
     _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "%s %s" % (name, dtype), skip=("dW",))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_right_side_projection(dtype):
+    # R = G Q with the n x r factor (the usual choice for m > n), mixed with left-side matrices in
+    # one layer set; ragged sizes, strided operands, GPU refresh of both kinds
+    shapes = [(520, 384), (200, 333), (333, 200), (384, 520), (130, 64)]
+    sides = [B.NG_SIDE_RIGHT, B.NG_SIDE_RIGHT, B.NG_SIDE_RIGHT, B.NG_SIDE_LEFT, B.NG_SIDE_RIGHT]
+    ls, errs = _run(shapes, [64, 24, 40, 64, 20], 4, dtype, 7, seed=67, k=64, sides=sides, pad_w=3, pad_g=5)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "right side " + dtype)
+    assert ls.P(0).shape == (384, 64) and ls.M(0).shape[0] == 64
+
+
 def test_full_1b_layer_set_sampled():
     """All 168 matrices of the 1.1B configuration in one layer set (the grouped launches, tile
     tables and history size the benchmark times); the oracle follows one matrix of each shape

@@ -63,7 +63,7 @@ def cpu_baseline(cfg, ls, grads_pool, weights, per_shape_s=5.0):
     parts = []
     for (m, n, mult) in cfg.distinct_shapes():
         i = mats.index((m, n))
-        st = oracle.init_state(m, n, cfg.r, cfg.s)
+        st = oracle.init_state(m, n, cfg.r, cfg.s, "right" if ls.descs[i].side == 1 else "left")
         st.P = to_f64(ls.P(i))
         W = to_f64(weights[i])
         G0 = to_f64(grads_pool[0][i])
@@ -96,6 +96,8 @@ def main() -> int:
                     help="override the configuration's gradient / weight type")
     ap.add_argument("--hist-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the history ring (the benchmark configurations fix f32)")
+    ap.add_argument("--sides", default="left", choices=["left", "auto"],
+                    help="auto: right-side projection where m > n (the benchmark configurations fix left)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true")
     ap.add_argument("--refresh-in-loop", type=int, default=0, help="refresh every this many timed steps (0 = never)")
@@ -135,7 +137,8 @@ def main() -> int:
     pool = [stream.next_set() for _ in range(max(1, args.pool))]
     weights = workloads.torch_weights(mats, cfg.seed, cfg.dtype, dev)
     ls = B.LayerSet(mats, cfg.r, s=cfg.s, lam=cfg.lam, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
-                    dtype=cfg.dtype, device=dev, hist_dtype=args.hist_dtype)
+                    dtype=cfg.dtype, device=dev, hist_dtype=args.hist_dtype,
+                    sides=None if args.sides == "left" else args.sides)
     torch.cuda.synchronize()
 
     # projector refresh at step 0 (timed separately, not part of `value`)
@@ -220,7 +223,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype if cfg.dtype != "f32" else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d matrices, rank %d, history s=%d, %s gradients/weights, fp32 moments, %s history"
-                               % (cfg.name, len(mats), cfg.r, cfg.s, cfg.dtype, args.hist_dtype),
+                               % (cfg.name, len(mats), cfg.r, cfg.s, cfg.dtype, args.hist_dtype)
+                               + ("" if args.sides == "left" else ", right-side projection where m > n"),
                    "config_key": args.config, "refreshes_in_timed_region": n_refresh,
                    "gradient_pool": len(pool)},
         "roofline": roofline,

@@ -144,6 +144,15 @@ def test_right_side_projection(dtype):
     assert ls.P(0).shape == (384, 64) and ls.M(0).shape[0] == 64
 
 
+def test_right_side_1b_shapes_sampled():
+    # one block of the 1.1B shapes with the usual side rule (right where m > n: the 5461 x 2048 matrix)
+    cfg = workloads.CONFIGS["c5"]
+    shapes = cfg.matrices()[:7]
+    ls, errs = _run(shapes, cfg.r, cfg.s, "bf16", 3, seed=cfg.seed, k=cfg.k, check=[0, 6], sides="auto")
+    assert ls.side(6) == B.NG_SIDE_RIGHT and ls.side(0) == B.NG_SIDE_LEFT
+    _assert_all(errs, TOL_BF16, "c5 block, auto sides")
+
+
 def test_full_1b_layer_set_sampled():
     """All 168 matrices of the 1.1B configuration in one layer set (the grouped launches, tile
     tables and history size the benchmark times); the oracle follows one matrix of each shape

@@ -79,6 +79,7 @@ enum {
  *                the state is that of the transposed problem: every "m" in the buffer shapes below
  *                reads n and every "n" reads m (P is [n][r]; M, V, H, N are r x ldm). */
 enum { NG_SIDE_LEFT = 0, NG_SIDE_RIGHT = 1 };
+enum { NG_NORM_S = 0, NG_NORM_COUNT = 1 };
 
 typedef struct ng_matrix_desc {
     int32_t m, n, r;       /* weight is m x n (row-major), rank r, 1 <= r <= min(m, n) */
@@ -101,7 +102,9 @@ typedef struct ng_hparams {
                                      (NG_BF16 gradients only).  bf16 slots halve the ring's memory and
                                      the two passes over it that bound the step; M and V are float in
                                      every mode                                                      */
-    int32_t reserved;             /* must be 0                                                       */
+    int32_t fisher_norm;          /* NG_NORM_S (default): F = lambda I + (1/s) sum_j vec(H_j) vec(H_j)^T
+                                     always; NG_NORM_COUNT: 1/(number of valid slots) while the ring
+                                     fills (the two readings of the paper's 1/h, Sec. 2.2 / 2.4)     */
     uint64_t seed;                /* seed of the refresh's random sketch                            */
 } ng_hparams;
 
@@ -118,7 +121,7 @@ typedef struct ng_matrix_layout {
 
 /* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
  * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps,
- * hist_dtype NG_F32, seed 0. */
+ * hist_dtype NG_F32, fisher_norm NG_NORM_S, seed 0. */
 int ng_default_hparams(ng_hparams* hp);
 
 /* Bytes the caller must allocate.  bytes[i*NG_NBUF + b] = size of buffer b of

@@ -62,6 +62,7 @@ class HParams:
     scale: float = 1.0
     weight_decay: float = 0.0
     adam_mode: str = "standard"      # "standard" | "printed"
+    fisher_norm: str = "s"           # "s": 1/s always | "count": 1/(valid slots) while the ring fills
     weight_dtype: str = "f32"        # "f32" | "bf16": storage type of W
 
 
@@ -147,16 +148,17 @@ def fisher_history_matrix(H: np.ndarray) -> np.ndarray:
     return H.reshape(s, -1).T.copy()
 
 
-def natural_gradient_transform(H: np.ndarray, R: np.ndarray, lam: float) -> tuple:
+def natural_gradient_transform(H: np.ndarray, R: np.ndarray, lam: float, h: int = None) -> tuple:
     """Inverse damped empirical Fisher applied to R through Woodbury (Sec. 2.4).
 
-    F = lam*I + U U^T with U = Hmat / sqrt(s).  Following the section's steps:
-    S = I + U^T U / lam,  y = U^T vec(R),  Cholesky solve S z = y,
+    F = lam*I + U U^T with U = Hmat / sqrt(h), h = s unless given (the normaliser of Sec. 2.2's
+    empirical FIM; h = number of valid slots is the other reading while the ring fills).
+    Following the section's steps: S = I + U^T U / lam,  y = U^T vec(R),  Cholesky solve S z = y,
     g~ = vec(R)/lam - U z / lam^2.  Returns (g~ as r x n, dict of K, S, y, z).
     """
     s = H.shape[0]
     Hmat = fisher_history_matrix(H)
-    U = Hmat / np.sqrt(s)
+    U = Hmat / np.sqrt(s if h is None else h)
     g = R.reshape(-1)
     K = Hmat.T @ Hmat                       # s x s Gram of the stored slots
     S = np.eye(s) + (U.T @ U) / lam
@@ -253,7 +255,9 @@ def step(state: OracleState, G: np.ndarray, W: np.ndarray, lr: float, hp: HParam
     tr = {"R": R}
     if hp.s > 0:
         slot = push_history(state, R)
-        g_nat, parts = natural_gradient_transform(state.H, R, hp.lam)
+        h = state.count if hp.fisher_norm == "count" else None
+        g_nat, parts = natural_gradient_transform(state.H, R, hp.lam, h)
+        parts["h"] = hp.s if h is None else h
         tr.update(parts)
         tr["slot"] = slot
     else:

@@ -211,7 +211,8 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
     }
     __syncthreads();
     const double lam = (double)sc.lambda;
-    const double inv_s = 1.0 / (double)s;
+    // normaliser of the empirical Fisher: 1/s, or 1/(valid slots after this push) while the ring fills
+    const double inv_s = 1.0 / (double)(sc.norm_count ? dyn[first + blockIdx.x].count : s);
     if (i < s)
         for (int j = 0; j < s; ++j) A[i][j] = A[i][j] * inv_s + (i == j ? lam : 0.0);
     __syncthreads();

@@ -32,7 +32,7 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
     if (hp->grad_dtype != NG_F32 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->hist_dtype != NG_F32 && hp->hist_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->hist_dtype == NG_BF16 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
-    if (hp->reserved != 0) return NG_ERR_HPARAM;
+    if (hp->fisher_norm != NG_NORM_S && hp->fisher_norm != NG_NORM_COUNT) return NG_ERR_HPARAM;
     if (hp->adam_mode != NG_ADAM_STANDARD && hp->adam_mode != NG_ADAM_PRINTED) return NG_ERR_DTYPE;
     if (hp->s < 0 || hp->s > kMaxS) return NG_ERR_SHAPE;
     if (!(hp->lambda > 0.f) || !isfinite(hp->lambda)) return NG_ERR_HPARAM;
@@ -266,6 +266,7 @@ StepScalars make_scalars(const ng_state* st, float lr) {
     sc.s = st->hp.s > 0 ? st->hp.s : 1;
     sc.use_fisher = st->hp.s > 0 ? 1 : 0;
     sc.hist_bf16 = hist_is_bf16(st->hp) ? 1 : 0;
+    sc.norm_count = st->hp.fisher_norm == NG_NORM_COUNT ? 1 : 0;
     return sc;
 }
 
@@ -343,7 +344,7 @@ int ng_default_hparams(ng_hparams* hp) {
     hp->weight_decay = 0.0f;
     hp->grad_dtype = NG_F32;
     hp->hist_dtype = NG_F32;
-    hp->reserved = 0;
+    hp->fisher_norm = NG_NORM_S;
     hp->adam_mode = NG_ADAM_STANDARD;
     hp->refresh_power_iters = 2;
     hp->refresh_oversample = 8;

@@ -76,6 +76,7 @@ struct StepScalars {
     int s;               // slots read by the kernels (>= 1; the s = 0 case uses one scratch slot)
     int use_fisher;      // 0 when hparams.s == 0
     int hist_bf16;       // history slots are bf16 (else float)
+    int norm_count;      // Fisher normaliser 1/count (valid slots) instead of 1/s
 };
 
 // Grouped-launch work item: which matrix and which tile / part of it a workgroup takes.

@@ -29,6 +29,7 @@ def oracle_hparams(ls: B.LayerSet) -> oracle.HParams:
     return oracle.HParams(s=hp.s, lam=float(hp.lambda_), beta1=float(hp.beta1), beta2=float(hp.beta2),
                           eps=float(hp.eps), scale=float(hp.scale), weight_decay=float(hp.weight_decay),
                           adam_mode="standard" if hp.adam_mode == B.NG_ADAM_STANDARD else "printed",
+                          fisher_norm="count" if hp.fisher_norm == B.NG_NORM_COUNT else "s",
                           weight_dtype=ls.dtype)
 
 
@@ -109,7 +110,7 @@ class Lockstep:
                 e["K"] = rel_err(to_f64(ls.K(i)), tr["K"])
                 # w = (lambda I + K/s)^{-1} e_slot, from the oracle's own K
                 s = ls.hp.s
-                w_ref = np.linalg.solve(self.ohp.lam * np.eye(s) + tr["K"] / s, np.eye(s)[slot[i]])
+                w_ref = np.linalg.solve(self.ohp.lam * np.eye(s) + tr["K"] / tr["h"], np.eye(s)[slot[i]])
                 e["w"] = rel_err(to_f64(ls.w(i)), w_ref)
                 e["pad"] = float(H[:, :, n:].abs().max().item()) if H.shape[2] > n else 0.0
             e["M"] = rel_err(to_f64(ls.M(i)[:, :n]), T(st.M))

@@ -78,7 +78,7 @@ def test_query_sizes_c1_and_bf16_layout():
     (lambda d, hp: setattr(hp, "grad_dtype", 7), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "hist_dtype", 5), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "hist_dtype", B.NG_BF16), B.NG_ERR_DTYPE),   # bf16 history needs bf16 gradients
-    (lambda d, hp: setattr(hp, "reserved", 1), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "fisher_norm", 2), B.NG_ERR_HPARAM),
     (lambda d, hp: setattr(hp, "adam_mode", 2), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "refresh_sweeps", 0), B.NG_ERR_HPARAM),
     (lambda d, hp: setattr(d[0], "r", 0), B.NG_ERR_SHAPE),

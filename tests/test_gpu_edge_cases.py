@@ -144,6 +144,13 @@ def test_right_side_projection(dtype):
     assert ls.P(0).shape == (384, 64) and ls.M(0).shape[0] == 64
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_count_normaliser_while_the_ring_fills(dtype):
+    # 1/count instead of 1/s: differs from the default on the first s - 1 steps
+    ls, errs = _run([(200, 333), (130, 64)], 24, 6, dtype, 9, seed=71, k=24, fisher_norm="count")
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "count normaliser " + dtype)
+
+
 def test_right_side_1b_shapes_sampled():
     # one block of the 1.1B shapes with the usual side rule (right where m > n: the 5461 x 2048 matrix)
     cfg = workloads.CONFIGS["c5"]

@@ -234,6 +234,26 @@ def test_project_is_transpose_product_not_its_transpose():
 
 
 # ------------------------------------------------------------------ integers
+def test_count_normaliser_matches_explicit_fisher_over_valid_slots():
+    # fisher_norm = "count": F = lam I + (1/count) sum over the valid slots while the ring fills
+    rng = np.random.default_rng(31)
+    m, n, r, s = 5, 4, 2, 4
+    hp = HParams(s=s, lam=0.2, fisher_norm="count")
+    st = oracle.init_state(m, n, r, s)
+    st.P, _ = np.linalg.qr(rng.normal(size=(m, r)))
+    W = rng.normal(size=(m, n))
+    slots = collections.deque(maxlen=s)
+    for step in range(6):
+        G = rng.normal(size=(m, n))
+        W = oracle.step(st, G, W, 1e-2, hp)
+        R = st.P.T @ G
+        slots.append(R)
+        F = explicit_fisher(list(slots), hp.lam, len(slots), r * n)     # 1/len(slots), not 1/s
+        expect = np.linalg.solve(F, R.reshape(-1)).reshape(r, n)
+        assert np.allclose(st.trace["g_nat"], expect, rtol=1e-9, atol=1e-12)
+        assert st.trace["h"] == min(step + 1, s)
+
+
 # ------------------------------------------------------------------ right-side form (Q factor of the compact SVD)
 def test_right_projector_orthonormal_lossless_and_eckart_young():
     rng = np.random.default_rng(21)

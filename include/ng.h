@@ -105,6 +105,11 @@ typedef struct ng_hparams {
     int32_t fisher_norm;          /* NG_NORM_S (default): F = lambda I + (1/s) sum_j vec(H_j) vec(H_j)^T
                                      always; NG_NORM_COUNT: 1/(number of valid slots) while the ring
                                      fills (the two readings of the paper's 1/h, Sec. 2.2 / 2.4)     */
+    int32_t carry_history;        /* 0 (default): ng_refresh_projector clears the history (its slots are
+                                     coordinates in the old basis).  1: it re-expresses every slot in
+                                     the new basis, H_j <- (P_new^T P_old) H_j, recomputes the Gram
+                                     matrix and keeps the ring position                              */
+    int32_t reserved;             /* must be 0                                                       */
     uint64_t seed;                /* seed of the refresh's random sketch                            */
 } ng_hparams;
 
@@ -121,7 +126,7 @@ typedef struct ng_matrix_layout {
 
 /* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
  * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps,
- * hist_dtype NG_F32, fisher_norm NG_NORM_S, seed 0. */
+ * hist_dtype NG_F32, fisher_norm NG_NORM_S, carry_history 0, seed 0. */
 int ng_default_hparams(ng_hparams* hp);
 
 /* Bytes the caller must allocate.  bytes[i*NG_NBUF + b] = size of buffer b of

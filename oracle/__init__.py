@@ -11,6 +11,7 @@ from .natural_galore import (  # noqa: F401
     adam_moments,
     back_project_update,
     back_project_update_right,
+    carry_history,
     fisher_history_matrix,
     init_state,
     natural_gradient_transform,

@@ -230,16 +230,36 @@ def back_project_update_right(W, Q, N, lr: float, hp: HParams):
 # --------------------------------------------------------------------------
 # The step and the refresh
 # --------------------------------------------------------------------------
-def refresh_projector(state: OracleState, G: np.ndarray) -> None:
-    """P <- top-r left (right, for side "right") singular vectors of the current gradient; clear history."""
+def carry_history(state: OracleState, P_new: np.ndarray) -> None:
+    """Re-express the stored slots in a new basis: H_j <- (P_new^T P_old) H_j.
+
+    A slot holds the coordinates, in the old basis, of the part of an old gradient inside the old
+    subspace (P_old H_j); its coordinates in the new basis are P_new^T (P_old H_j).  On the right
+    side the slots are m x r and the r x r change of basis multiplies from the right, transposed.
+    """
+    T = P_new.T @ state.P
+    for j in range(state.H.shape[0]):
+        state.H[j] = state.H[j] @ T.T if state.side == "right" else T @ state.H[j]
+
+
+def refresh_projector(state: OracleState, G: np.ndarray, carry: bool = False) -> None:
+    """P <- top-r left (right, for side "right") singular vectors of the current gradient.
+
+    The history is cleared (default: its slots are coordinates in the old basis), or, with
+    ``carry``, re-expressed in the new basis and kept together with head and count.
+    """
     r = state.P.shape[1]
     if state.side == "right":
-        state.P = top_r_right_singular_vectors(G, r)
+        P_new = top_r_right_singular_vectors(G, r)
     else:
-        state.P = top_r_left_singular_vectors(G, r)
-    state.H[...] = 0.0
-    state.head = 0
-    state.count = 0
+        P_new = top_r_left_singular_vectors(G, r)
+    if carry:
+        carry_history(state, P_new)
+    else:
+        state.H[...] = 0.0
+        state.head = 0
+        state.count = 0
+    state.P = P_new
     state.n_refresh += 1
 
 

@@ -77,10 +77,10 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
 template <int SMAX, bool HB>
 __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn,
-                                                  const TileRef* __restrict__ chunks, int s) {
+                                                  const TileRef* __restrict__ chunks, int s, int row_override) {
     const TileRef c = chunks[blockIdx.x];
     const MatDev& md = mats[c.mat];
-    const int head = dyn[c.mat].head;
+    const int head = row_override >= 0 ? row_override : dyn[c.mat].head;
     const long long totalv = md.slot_elems >> (HB ? 3 : 2);   // 16-byte vectors per slot
     const long long span = (long long)md.dot_iters * 256;
     const long long q0 = (long long)c.ti * span;
@@ -147,13 +147,13 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
 }
 
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks, int s,
-                           int hist_bf16, hipStream_t stream) {
+                           int hist_bf16, int row_override, hipStream_t stream) {
     if (n_chunks == 0) return hipSuccess;
     dim3 g(n_chunks), b(256);
 #define NG_GRAM_CASE(S)                                                                          \
     do {                                                                                         \
-        if (hist_bf16) hipLaunchKernelGGL((k_gram_row<S, true>), g, b, 0, stream, mats, dyn, chunks, s);  \
-        else hipLaunchKernelGGL((k_gram_row<S, false>), g, b, 0, stream, mats, dyn, chunks, s);           \
+        if (hist_bf16) hipLaunchKernelGGL((k_gram_row<S, true>), g, b, 0, stream, mats, dyn, chunks, s, row_override);  \
+        else hipLaunchKernelGGL((k_gram_row<S, false>), g, b, 0, stream, mats, dyn, chunks, s, row_override);           \
     } while (0)
     if (s <= 1) NG_GRAM_CASE(1);
     else if (s <= 2) NG_GRAM_CASE(2);
@@ -177,12 +177,12 @@ hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef*
 // LDS) and solves A w = e_head.  A non-positive or non-finite pivot sets bit 0
 // of *status; a non-finite w sets bit 1.
 __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
-                                              int first, StepScalars sc, int* status) {
+                                              int first, StepScalars sc, int row_override, int* status) {
     __shared__ double A[kMaxS][kMaxS + 1];
     __shared__ double bc[kMaxS];
     const MatDev& md = mats[first + blockIdx.x];
     const int s = sc.s;
-    const int head = dyn[first + blockIdx.x].head;
+    const int head = row_override >= 0 ? row_override : dyn[first + blockIdx.x].head;
     const int i = threadIdx.x;
 
     // old Gram matrix into LDS, then overwrite row and column `head` with the new dots
@@ -209,6 +209,7 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
         A[head][i] = v;
         A[i][head] = v;
     }
+    if (row_override >= 0) return;      // only the Gram matrix is rebuilt (history carry-over)
     __syncthreads();
     const double lam = (double)sc.lambda;
     // normaliser of the empirical Fisher: 1/s, or 1/(valid slots after this push) while the ring fills
@@ -263,8 +264,8 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
 }
 
 hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_mats, StepScalars sc,
-                        int* status, hipStream_t stream) {
-    hipLaunchKernelGGL(k_solve, dim3(n_mats), dim3(64), 0, stream, mats, dyn, first, sc, status);
+                        int row_override, int* status, hipStream_t stream) {
+    hipLaunchKernelGGL(k_solve, dim3(n_mats), dim3(64), 0, stream, mats, dyn, first, sc, row_override, status);
     return hipGetLastError();
 }
 
@@ -452,6 +453,37 @@ __global__ __launch_bounds__(256) void k_make_bf16_copies(const MatDev* __restri
         const int rho = r0 + yy, i = i0 + tx;
         if (rho < md.r && i < md.ldk) md.PbT[(long long)rho * md.ldk + i] = f32_to_bf16_rne(tile[tx][yy]);
     }
+}
+
+// ------------------------------------------------------------------ history carry-over helpers
+__global__ __launch_bounds__(256) void k_save_projector(const MatDev* __restrict__ mats) {
+    const MatDev& md = mats[blockIdx.y];
+    const long long total = (long long)md.m * md.r;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256)
+        md.Yc[q] = md.P[q];
+}
+
+hipError_t launch_save_projector(const MatDev* mats, int n_mats, hipStream_t stream) {
+    hipLaunchKernelGGL(k_save_projector, dim3(256, n_mats), dim3(256), 0, stream, mats);
+    return hipGetLastError();
+}
+
+// H[slot] <- carry (float -> the slot's type)
+template <bool HB>
+__global__ __launch_bounds__(256) void k_carry_store(const MatDev* __restrict__ mats, int slot) {
+    const MatDev& md = mats[blockIdx.y];
+    const long long total = md.slot_elems;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256) {
+        const float v = md.carry[q];
+        if (HB) ((bf16_t*)md.H)[(long long)slot * total + q] = f32_to_bf16_rne(v);
+        else md.H[(long long)slot * total + q] = v;
+    }
+}
+
+hipError_t launch_carry_store(const MatDev* mats, int n_mats, int slot, int hist_bf16, hipStream_t stream) {
+    if (hist_bf16) hipLaunchKernelGGL(k_carry_store<true>, dim3(512, n_mats), dim3(256), 0, stream, mats, slot);
+    else hipLaunchKernelGGL(k_carry_store<false>, dim3(512, n_mats), dim3(256), 0, stream, mats, slot);
+    return hipGetLastError();
 }
 
 hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, int max_r, hipStream_t stream) {

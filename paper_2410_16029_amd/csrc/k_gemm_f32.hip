@@ -28,7 +28,8 @@ struct GemmView {
     int epi;
 };
 
-__host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const MatDyn* dy, int grad_dtype) {
+__host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const MatDyn* dy, int grad_dtype,
+                                              int slot = 0, int hist_bf16 = 0) {
     GemmView v;
     v.a_bf16 = 0;
     v.b_bf16 = 0;
@@ -122,6 +123,21 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.M = md.r; v.N = md.r; v.Nvalid = md.r; v.K = md.m;
             v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64;
             break;
+        case OP_T_CARRY:   // change of basis T = P_new^T P_old, P_old saved in Yc
+            v.A = md.P; v.sAi = 1; v.sAk = md.r;
+            v.B = md.Yc; v.sBk = md.r; v.sBj = 1;
+            v.M = md.r; v.N = md.r; v.Nvalid = md.r; v.K = md.m;
+            v.C = md.Linv; v.ldc = md.lp;
+            break;
+        case OP_CARRY_SLOT:   // carry = T H[slot]
+            v.A = md.Linv; v.sAi = md.lp; v.sAk = 1;
+            if (hist_bf16) v.B = reinterpret_cast<const unsigned short*>(md.H) + (long long)slot * md.slot_elems;
+            else v.B = md.H + (long long)slot * md.slot_elems;
+            v.b_bf16 = hist_bf16;
+            v.sBk = md.ldn; v.sBj = 1;
+            v.M = md.r; v.N = md.ldn; v.Nvalid = md.ldn; v.K = md.r;
+            v.C = md.carry; v.ldc = md.ldn;
+            break;
         case OP_APPLY_P2A:
         default:
             v.A = md.P; v.sAi = md.r; v.sAk = 1;
@@ -195,7 +211,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     __shared__ __attribute__((aligned(16))) float As[BK][LDT];
     __shared__ __attribute__((aligned(16))) float Bs[BK][LDT];
     const MatDev& md = mats[blockIdx.z];
-    const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype);
+    const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype, sc.slot, sc.hist_bf16);
     const int i0 = blockIdx.y * TS, j0 = blockIdx.x * TS;
     if (i0 >= v.M || j0 >= v.N) return;
 

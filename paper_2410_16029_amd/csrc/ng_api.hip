@@ -24,7 +24,7 @@ struct Sizes {   // per-matrix derived sizes
     size_t k_gram_off, k_w64_off, k_w32_off;
     size_t aux_pb_off, aux_pbt_off;
     // refresh scratch
-    size_t ws_y, ws_bm, ws_t, ws_linv, ws_ritz, ws_order, ws_flag, ws_parts;
+    size_t ws_y, ws_bm, ws_t, ws_linv, ws_ritz, ws_order, ws_flag, ws_parts, ws_carry;
 };
 
 int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
@@ -33,6 +33,7 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
     if (hp->hist_dtype != NG_F32 && hp->hist_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->hist_dtype == NG_BF16 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->fisher_norm != NG_NORM_S && hp->fisher_norm != NG_NORM_COUNT) return NG_ERR_HPARAM;
+    if ((hp->carry_history != 0 && hp->carry_history != 1) || hp->reserved != 0) return NG_ERR_HPARAM;
     if (hp->adam_mode != NG_ADAM_STANDARD && hp->adam_mode != NG_ADAM_PRINTED) return NG_ERR_DTYPE;
     if (hp->s < 0 || hp->s > kMaxS) return NG_ERR_SHAPE;
     if (!(hp->lambda > 0.f) || !isfinite(hp->lambda)) return NG_ERR_HPARAM;
@@ -115,6 +116,7 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
     z->ws_ritz = align_up((size_t)z->lp * 8, 256);
     z->ws_order = align_up((size_t)z->lp * 4, 256);
     z->ws_flag = 256;
+    z->ws_carry = hp.carry_history ? align_up(rn * 4, 256) : 0;
     z->ws_parts = align_up((size_t)kDotPartsMax * (s > 0 ? s : 1) * 8, 256);
 }
 
@@ -176,7 +178,8 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     p->off_scratch = off;
     for (int i = 0; i < n_mats; ++i) {
         const Sizes& z = p->sz[i];
-        off += z.ws_parts + 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag;
+        off += z.ws_parts + 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag +
+               z.ws_carry;
     }
     p->total = off;
 }
@@ -345,6 +348,8 @@ int ng_default_hparams(ng_hparams* hp) {
     hp->grad_dtype = NG_F32;
     hp->hist_dtype = NG_F32;
     hp->fisher_norm = NG_NORM_S;
+    hp->carry_history = 0;
+    hp->reserved = 0;
     hp->adam_mode = NG_ADAM_STANDARD;
     hp->refresh_power_iters = 2;
     hp->refresh_oversample = 8;
@@ -465,6 +470,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.ritz = (double*)(ws + off); off += z.ws_ritz;
             md.order = (int*)(ws + off); off += z.ws_order;
             md.jflag = (int*)(ws + off); off += z.ws_flag;
+            md.carry = z.ws_carry ? (float*)(ws + off) : nullptr; off += z.ws_carry;
             md.lp = z.lp; md.jb = z.jb;
             // units of the Gram-row reduction: 16-byte vectors of a slot
             const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
@@ -596,6 +602,9 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
         NG_HIP(launch_jacobi_sweep_end(st->d_mats, st->n_mats, stream));
     }
     NG_HIP(launch_jacobi_finish(st->d_mats, st->n_mats, st->d_status, stream));
+    // history carry-over needs the outgoing projector: keep it in Yc (free from here on)
+    const bool carry = st->hp.carry_history && st->hp.s > 0 && st->projector_valid;
+    if (carry) NG_HIP(launch_save_projector(st->d_mats, st->n_mats, stream));
     if ((rc = gemm(st, OP_ROTATE, stream, sc)) != NG_OK) return rc;
     // one CholeskyQR pass on P (m x r) restores orthonormality to rounding level, then fix signs
     if ((rc = gemm(st, OP_GRAM_P, stream, sc)) != NG_OK) return rc;
@@ -604,11 +613,27 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     if ((rc = gemm(st, OP_APPLY_P2A, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_sign_fix(st->d_mats, st->n_mats, st->max_r, stream));
 
-    if ((rc = finish_projector(st, true, stream)) != NG_OK) return rc;
+    if (carry) {
+        // H_j <- (P_new^T P_old) H_j for every slot, then the whole Gram matrix again
+        if ((rc = gemm(st, OP_T_CARRY, stream, sc)) != NG_OK) return rc;
+        StepScalars scs = sc;
+        for (int slot = 0; slot < st->hp.s; ++slot) {
+            scs.slot = slot;
+            if ((rc = gemm(st, OP_CARRY_SLOT, stream, scs)) != NG_OK) return rc;
+            NG_HIP(launch_carry_store(st->d_mats, st->n_mats, slot, sc.hist_bf16, stream));
+        }
+        for (int row = 0; row < st->hp.s; ++row) {
+            NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, row, stream));
+            NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, row, st->d_status, stream));
+        }
+    }
+    if ((rc = finish_projector(st, !carry, stream)) != NG_OK) return rc;
     st->projector_valid = true;
     for (int i = 0; i < st->n_mats; ++i) {
-        st->head[i] = 0;
-        st->count[i] = 0;
+        if (!carry) {
+            st->head[i] = 0;
+            st->count[i] = 0;
+        }
         st->n_refresh[i] += 1;
     }
     return NG_OK;
@@ -637,10 +662,10 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
-    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, stream));
+    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, -1, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
-    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, st->d_status, stream));
+    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, -1, st->d_status, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_ADAM], stream));
     NG_HIP(launch_transform_adam(st->d_mats, st->d_dyn, st->d_patches, (int)st->plan.patches.size(), sc,

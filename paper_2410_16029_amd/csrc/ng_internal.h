@@ -52,6 +52,7 @@ struct MatDev {
     double* ritz;     // [lp]
     int* order;       // [lp]
     int* jflag;       // [0] rotations this sweep, [1] converged
+    float* carry;     // [r][ldn] scratch of the history carry-over (null unless enabled)
     int lp, jb;       // padded size and row-block size of the blocked Jacobi
 };
 
@@ -77,6 +78,7 @@ struct StepScalars {
     int use_fisher;      // 0 when hparams.s == 0
     int hist_bf16;       // history slots are bf16 (else float)
     int norm_count;      // Fisher normaliser 1/count (valid slots) instead of 1/s
+    int slot;            // history slot an OP_CARRY_SLOT product works on
 };
 
 // Grouped-launch work item: which matrix and which tile / part of it a workgroup takes.
@@ -114,6 +116,8 @@ enum GemmOp {
     OP_ROTATE,            // P = Ya * Urot (m x r), Urot (l x r floats) staged in Bm
     OP_GRAM_P,            // T = P^T P (r x r) -> double
     OP_APPLY_P2A,         // Ya[m][r] = P Linv^T
+    OP_T_CARRY,           // Linv (r x r, float) = P^T Yc, Yc holding the previous projector
+    OP_CARRY_SLOT,        // carry (r x ldn) = Linv * H[slot]
     OP_COUNT
 };
 void gemm_f32_dims(int op, const MatDev& md, int* M, int* N, int* K);
@@ -132,10 +136,14 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
                               StepScalars sc, const void* zero16, int sides, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
+// row_override >= 0: the Gram row of that slot instead of the step's head (history carry-over);
+// launch_solve then only stores the row and column of K and skips the solve
 hipError_t launch_gram_row(const MatDev* mats, const MatDyn* dyn, const TileRef* chunks, int n_chunks,
-                           int s, int hist_bf16, hipStream_t stream);
+                           int s, int hist_bf16, int row_override, hipStream_t stream);
 hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_mats, StepScalars sc,
-                        int* status, hipStream_t stream);
+                        int row_override, int* status, hipStream_t stream);
+hipError_t launch_save_projector(const MatDev* mats, int n_mats, hipStream_t stream);   // Yc <- P
+hipError_t launch_carry_store(const MatDev* mats, int n_mats, int slot, int hist_bf16, hipStream_t stream);
 hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const TileRef* patches, int n_patches,
                                  StepScalars sc, int grad_dtype, int* status, hipStream_t stream);
 hipError_t launch_make_bf16_copies(const MatDev* mats, int n_mats, int max_m, int max_r, hipStream_t stream);

@@ -47,6 +47,7 @@ class Lockstep:
             side = "right" if ls.side(i) == B.NG_SIDE_RIGHT else "left"
             self.states[i] = oracle.init_state(m, n, ls.descs[i].r, ls.hp.s, side)
         self.Wo = {}
+        self._refreshed = False
 
     def adopt_gpu_projector(self):
         """The oracle steps with the very projector the GPU holds (its basis is not unique)."""
@@ -59,13 +60,21 @@ class Lockstep:
             self.Wo[i] = to_f64(weights[i])
 
     def refresh(self, grads):
+        """GPU refresh; the oracle takes over the GPU's new basis (a refresh result is not unique)
+        and clears its history or, with carry_history, re-expresses it in that basis."""
+        carry = bool(self.ls.hp.carry_history) and self.ls.hp.s > 0 and self._refreshed
         self.ls.refresh(grads)
+        torch.cuda.synchronize()
         for i in self.check:
             st = self.states[i]
-            st.H[...] = 0.0
-            st.head = 0
-            st.count = 0
+            if carry:
+                oracle.carry_history(st, to_f64(self.ls.P(i)))
+            else:
+                st.H[...] = 0.0
+                st.head = 0
+                st.count = 0
             st.n_refresh += 1
+        self._refreshed = True
         self.adopt_gpu_projector()
 
     def step(self, grads, weights, lr):

@@ -151,6 +151,36 @@ def test_count_normaliser_while_the_ring_fills(dtype):
     _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "count normaliser " + dtype)
 
 
+@pytest.mark.parametrize("dtype,hist", [("f32", "f32"), ("bf16", "f32"), ("bf16", "bf16")])
+def test_history_carry_over_across_refresh(dtype, hist):
+    # carry_history: a refresh in the middle of a run re-expresses the slots in the new basis, rebuilds
+    # the Gram matrix and keeps the ring position; left- and right-side matrices
+    shapes = [(200, 333), (333, 200), (130, 64)]
+    sides = [B.NG_SIDE_LEFT, B.NG_SIDE_RIGHT, B.NG_SIDE_LEFT]
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    stream = workloads.TorchGradientStream(shapes, 24, 0.01, 73, dtype, DEV)
+    W = workloads.torch_weights(shapes, 73, dtype, DEV)
+    ls = B.LayerSet(shapes, 24, s=4, dtype=dtype, device=DEV, sides=sides, carry_history=True,
+                    hist_dtype=hist if dtype == "bf16" else None)
+    lk = Lockstep(ls, tol=tol)
+    lk.set_weights(W)
+    errs = []
+    for step in range(9):
+        G = stream.next_set()
+        if step in (0, 3, 6):
+            lk.refresh(G)
+            assert ls.status() == B.NG_OK
+            if step > 0:    # the whole Gram matrix was rebuilt from the carried slots
+                for i in range(len(shapes)):
+                    Hm = lk.states[i].H.reshape(4, -1)
+                    err = np.abs(ls.K(i).cpu().numpy() - Hm @ Hm.T).max() / np.abs(Hm @ Hm.T).max()
+                    assert err <= tol, ("K after carry", i, err)
+        errs.append(lk.step(G, W, 1e-3))
+    assert ls.status() == B.NG_OK
+    _assert_all(errs, tol, "carry-over %s/%s" % (dtype, hist))
+    assert ls.counters(0) == (9, 9 % 4, 4, 3)
+
+
 def test_right_side_1b_shapes_sampled():
     # one block of the 1.1B shapes with the usual side rule (right where m > n: the 5461 x 2048 matrix)
     cfg = workloads.CONFIGS["c5"]

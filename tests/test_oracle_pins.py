@@ -254,6 +254,45 @@ def test_count_normaliser_matches_explicit_fisher_over_valid_slots():
         assert st.trace["h"] == min(step + 1, s)
 
 
+@pytest.mark.parametrize("side", ["left", "right"])
+def test_history_carry_over_is_the_old_subspace_part_in_the_new_basis(side):
+    # Kept next to the oracle: the full old gradients.  After a refresh with carry, slot j must hold
+    # the new-basis coordinates of the old-subspace part of G_j, and the ring positions survive.
+    rng = np.random.default_rng(41)
+    m, n, r, s = 7, 6, 3, 3
+    hp = HParams(s=s, lam=0.1)
+    st = oracle.init_state(m, n, r, s, side)
+    G0 = rng.normal(size=(m, n))
+    oracle.refresh_projector(st, G0)
+    W = rng.normal(size=(m, n))
+    kept = {}
+    for _ in range(4):
+        G = rng.normal(size=(m, n))
+        kept[st.head] = G
+        W = oracle.step(st, G, W, 1e-2, hp)
+    P_old = st.P.copy()
+    head, count = st.head, st.count
+    Gn = rng.normal(size=(m, n))
+    oracle.refresh_projector(st, Gn, carry=True)
+    assert (st.head, st.count, st.n_refresh) == (head, count, 2)
+    P_new = st.P
+    assert not np.allclose(P_new, P_old)
+    for j, G in kept.items():
+        if side == "left":
+            expect = P_new.T @ (P_old @ (P_old.T @ G))
+        else:
+            expect = ((G @ P_old) @ P_old.T) @ P_new
+        assert np.allclose(st.H[j], expect, atol=1e-12)
+    # same subspace, rotated basis: the carried slots equal a fresh projection with the new basis
+    st2 = oracle.init_state(m, n, r, s, side)
+    st2.P = P_old.copy()
+    st2.H[0] = (P_old.T @ G0) if side == "left" else (G0 @ P_old)
+    Theta, _ = np.linalg.qr(rng.normal(size=(r, r)))
+    oracle.carry_history(st2, P_old @ Theta)
+    fresh = ((P_old @ Theta).T @ G0) if side == "left" else (G0 @ (P_old @ Theta))
+    assert np.allclose(st2.H[0], fresh, atol=1e-12)
+
+
 # ------------------------------------------------------------------ right-side form (Q factor of the compact SVD)
 def test_right_projector_orthonormal_lossless_and_eckart_young():
     rng = np.random.default_rng(21)

@@ -3,8 +3,10 @@
 //   k_project_bf16   R = P^T G        (paper Sec. 1, projection equation)
 //                    A = PbT [r][ldk] (bf16 copy of P^T, contraction index contiguous)
 //                    B = G   [m][ld_g] (caller's gradient: contraction index is the ROW, so the tile
-//                                       is transposed in registers on its way into LDS)
-//                    C -> ring slot `head` of H, float [r][ldn]
+//                                       is transposed in registers on its way into LDS; on the right
+//                                       side the problem is transposed and the gradient's rows are
+//                                       contraction-contiguous columns: no transpose)
+//                    C -> ring slot `head` of H, float or bf16 [r][ldn]
 //   k_update_bf16_dl W <- W - lr (scale P N + wd W)   (paper Sec. 2.2, update equation)
 //                    A = Pb [m][ldr], B = N in the octet layout [r/8][ldn][8] written by the
 //                    transform+Adam kernel (both k-packed: 16-byte chunks go from memory straight

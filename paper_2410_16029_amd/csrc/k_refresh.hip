@@ -229,9 +229,11 @@ __global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ 
     const double* __restrict__ L = md.T;
     float* __restrict__ Xg = md.Linv;
     const int rows = nn - c0;                       // rows c0 .. nn-1 are non-trivial
-    double* lrow = reinterpret_cast<double*>(tri_smem);            // [rows]
-    double* red = lrow + ((rows + 1) & ~1);                          // [S][CB]
-    float* Xs = reinterpret_cast<float*>(red + S * CB);             // [rows][CB]
+    constexpr int RB = 4;                           // rows resolved per step
+    const int lrs = (rows + RB + 1) & ~1;           // doubles per staged L row
+    double* lrow = reinterpret_cast<double*>(tri_smem);            // [RB][lrs]
+    double* red = lrow + RB * lrs;                                   // [RB][S][CB]
+    float* Xs = reinterpret_cast<float*>(red + RB * S * CB);        // [rows][CB]
     const int tid = threadIdx.x, c = tid % CB, sub = tid / CB;
     const bool col_ok = c0 + c < nn;
 
@@ -240,21 +242,47 @@ __global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ 
         const int i = q / CB, cc = q % CB;
         if (c0 + cc < nn) Xg[(long long)i * ld + c0 + cc] = 0.f;
     }
-    for (int i = c0; i < nn; ++i) {
-        const int len = i - c0;                    // entries L[i][c0 .. i-1] take part in the dot product
-        for (int p = tid; p <= len; p += 256) lrow[p] = L[(long long)i * ld + c0 + p];
+    // RB rows per step: their dot products with the rows already solved run together (one pass
+    // over the block, one reduction), the RB x RB triangle that couples them is resolved in order
+    for (int i0 = c0; i0 < nn; i0 += RB) {
+        const int len = i0 - c0;                   // entries L[i][c0 .. i0-1] meet solved rows
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const int i = i0 + q;
+            if (i < nn)
+                for (int p = tid; p <= len + q; p += 256) lrow[q * lrs + p] = L[(long long)i * ld + c0 + p];
+        }
         __syncthreads();
-        double acc = 0.0;
-        for (int p = sub; p < len; p += S) acc += lrow[p] * (double)Xs[p * CB + c];
-        red[sub * CB + c] = acc;
+        double acc[RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) acc[q] = 0.0;
+        for (int p = sub; p < len; p += S) {
+            const double xv = (double)Xs[p * CB + c];
+#pragma unroll
+            for (int q = 0; q < RB; ++q) acc[q] += lrow[q * lrs + p] * xv;
+        }
+#pragma unroll
+        for (int q = 0; q < RB; ++q) red[(q * S + sub) * CB + c] = acc[q];
         __syncthreads();
         if (sub == 0) {
-            double tot = 0.0;
+            double x[RB];
 #pragma unroll
-            for (int q = 0; q < S; ++q) tot += red[q * CB + c];
-            const float x = (float)(((i == c0 + c ? 1.0 : 0.0) - tot) / lrow[len]);
-            Xs[len * CB + c] = x;
-            if (col_ok) Xg[(long long)i * ld + c0 + c] = x;
+            for (int q = 0; q < RB; ++q) {
+                const int i = i0 + q;
+                if (i < nn) {
+                    double tot = 0.0;
+#pragma unroll
+                    for (int w = 0; w < S; ++w) tot += red[(q * S + w) * CB + c];
+#pragma unroll
+                    for (int u = 0; u < q; ++u) tot += lrow[q * lrs + len + u] * x[u];
+                    x[q] = ((i == c0 + c ? 1.0 : 0.0) - tot) / lrow[q * lrs + len + q];
+                    // the solved entry goes through float, as every later row reads it back from Xs
+                    const float xf = (float)x[q];
+                    x[q] = (double)xf;
+                    Xs[(len + q) * CB + c] = xf;
+                    if (col_ok) Xg[(long long)i * ld + c0 + c] = xf;
+                }
+            }
         }
         __syncthreads();
     }
@@ -263,7 +291,7 @@ __global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ 
 hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream) {
     // column-block width: the widest whose LDS block fits
     auto lds_for = [&](int cb) {
-        return (size_t)((max_order + 1) & ~1) * 8 + (size_t)256 * 8 + (size_t)max_order * cb * 4;
+        return (size_t)4 * ((max_order + 5) & ~1) * 8 + (size_t)4 * 256 * 8 + (size_t)max_order * cb * 4;
     };
     static bool attr_done = false;
     if (!attr_done) {

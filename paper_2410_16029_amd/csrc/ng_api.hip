@@ -204,7 +204,6 @@ struct ng_state {
     int* d_status;
     TileRef *d_proj, *d_upd, *d_dots, *d_patches;
     int n_dots;
-    std::vector<int> dots_begin, patch_begin;   // per matrix: first entry in the tables (+ end sentinel)
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
     int max_ti[OP_COUNT], max_tj[OP_COUNT], max_tk[OP_COUNT];   // largest M, N, K of each fp32 product
     int max_jpairs, jb_mask;
@@ -428,7 +427,6 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         st->mats.resize(n_mats);
         std::vector<TileRef> dots;
         size_t off = pl.off_scratch;
-        const int s_eff = hp->s > 0 ? hp->s : 1;
         st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
         st->max_jpairs = 0;
         st->jb_mask = 0;
@@ -478,7 +476,6 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             if (iters < 1) iters = 1;
             md.dot_iters = (int)iters;
             md.dot_nparts = (int)((total4 + iters * 256 - 1) / (iters * 256));
-            st->dots_begin.push_back((int)dots.size());
             if (hp->s > 0)
                 for (int p = 0; p < md.dot_nparts; ++p) dots.push_back(TileRef{i, p, 0, 0});
             if (md.m > st->max_m) st->max_m = md.m;
@@ -500,16 +497,8 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
                 if (N > st->max_tj[op]) st->max_tj[op] = N;
                 if (K > st->max_tk[op]) st->max_tk[op] = K;
             }
-            (void)s_eff;
         }
         st->n_dots = (int)dots.size();
-        st->dots_begin.push_back((int)dots.size());
-        {
-            // patches were appended matrix by matrix in make_plan
-            st->patch_begin.assign(n_mats + 1, 0);
-            for (size_t q = 0; q < pl.patches.size(); ++q) st->patch_begin[pl.patches[q].mat + 1] += 1;
-            for (int i = 0; i < n_mats; ++i) st->patch_begin[i + 1] += st->patch_begin[i];
-        }
 
         // upload the tables (synchronous copies; init is not a hot path)
         hipError_t e = hipSuccess;

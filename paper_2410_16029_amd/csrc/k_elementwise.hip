@@ -270,8 +270,6 @@ hipError_t launch_solve(const MatDev* mats, const MatDyn* dyn, int first, int n_
 }
 
 // ------------------------------------------------------------------ transform + Adam
-// One thread owns an 8 (rows) x 4 (columns) patch of the r x ldn space, a
-// wavefront 8 rows x 256 columns, a workgroup 32 rows x 256 columns.
 //   g~ = sum_j w_j H_j          (second pass over the ring; w from k_solve)
 //   M <- b1 M + (1-b1) g~ ; V <- b2 V + (1-b2) g~^2
 //   N  = (M * bc1) / (sqrt(V) * bc2 + eps)         standard
@@ -297,44 +295,56 @@ __device__ __forceinline__ f32x4_t load_hist4(const NG_AS1 unsigned char* slot, 
     return __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(slot + off));
 }
 
+// A lane owns a 4 (rows) x 4 (columns) patch; the two lanes of a pair (even: rows 0..3, odd: rows
+// 4..7 of an 8-row band) share the columns, so together they produce the 16-byte octets of N.  The
+// small patch keeps the register count low and the occupancy high, which is what feeds HBM here.
+// Wavefront = 8 rows x 128 columns, workgroup = 32 rows x 128 columns.
 template <bool BF16_N, bool HB>
 __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict__ mats,
                                                         const MatDyn* __restrict__ dyn,
                                                         const TileRef* __restrict__ patches, StepScalars sc,
                                                         int* status) {
+    constexpr int RT = 4;
     const TileRef pr = patches[blockIdx.x];
     const MatDev& md = mats[pr.mat];
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
-    const int row0 = pr.ti * 32 + wv * 8;
-    const int col0 = pr.tj * 256 + lane * 4;
+    const int band0 = pr.ti * 32 + wv * 8;                             // first row of the 8-row band
+    const int half = lane & 1;
+    const int row0 = band0 + RT * half;
+    const int col0 = pr.tj * kAdamPatchCols + (lane >> 1) * 4;
     const int ldn = md.ldn, r = md.r;
-    if (row0 >= r || col0 >= ldn) return;
-    const int nrow = (r - row0 < 8) ? (r - row0) : 8;
-    // Branch-free loads: a row beyond nrow re-reads row nrow-1 and its result is dropped.
-    // Element offsets of this thread's 8 row segments inside a slot / inside M, V (32-bit).
-    unsigned eoff[8];
+    if (band0 >= r || col0 >= ldn) return;
+    // rows of this lane inside the matrix (0 for the odd lane of a band that ends early)
+    const int nrow = r - row0 < 0 ? 0 : (r - row0 < RT ? r - row0 : RT);
+    // Branch-free loads: a row beyond nrow re-reads the band's last valid row and its result is dropped.
+    // Element offsets of this thread's row segments inside a slot / inside M, V (32-bit).
+    unsigned eoff[RT];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) eoff[e] = (unsigned)(row0 + (e < nrow ? e : nrow - 1)) * (unsigned)ldn + (unsigned)col0;
+    for (int e = 0; e < RT; ++e) {
+        const int row = row0 + e < r ? row0 + e : r - 1;
+        eoff[e] = (unsigned)row * (unsigned)ldn + (unsigned)col0;
+    }
     constexpr unsigned HS = HB ? 2u : 4u;   // bytes per history element
 
-    f32x4_t g[8];
+    f32x4_t g[RT];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) g[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < RT; ++e) g[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     const int s = sc.s;
     const NG_AS1 unsigned char* __restrict__ Hbase = (const NG_AS1 unsigned char*)md.H;
     const long long slot_bytes = md.slot_elems * (long long)HS;
     if (sc.use_fisher) {
         const NG_AS1 float* __restrict__ w = (const NG_AS1 float*)md.w32;
+#pragma unroll 2
         for (int j = 0; j < s; ++j) {
             const float wj = w[j];
             const NG_AS1 unsigned char* slot = Hbase + (long long)j * slot_bytes;
-            f32x4_t h[8];
+            f32x4_t h[RT];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = load_hist4<HB>(slot, eoff[e] * HS);
+            for (int e = 0; e < RT; ++e) h[e] = load_hist4<HB>(slot, eoff[e] * HS);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < RT; ++e) {
                 g[e].x = fmaf(wj, h[e].x, g[e].x);
                 g[e].y = fmaf(wj, h[e].y, g[e].y);
                 g[e].z = fmaf(wj, h[e].z, g[e].z);
@@ -344,23 +354,23 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     } else {
         // the single scratch slot holds R
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = load_hist4<HB>(Hbase, eoff[e] * HS);
+        for (int e = 0; e < RT; ++e) g[e] = load_hist4<HB>(Hbase, eoff[e] * HS);
     }
 
     const float b1 = sc.beta1, b2 = sc.beta2, ob1 = 1.0f - sc.beta1, ob2 = 1.0f - sc.beta2;
     const float bc1 = dyn[pr.mat].bc1, bc2 = dyn[pr.mat].bc2;
     NG_AS1 unsigned char* Mb = (NG_AS1 unsigned char*)md.M;
     NG_AS1 unsigned char* Vb = (NG_AS1 unsigned char*)md.V;
-    f32x4_t mv[8], vv[8];
+    f32x4_t mv[RT], vv[RT];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < RT; ++e) {
         mv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
         vv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
     }
-    f32x4_t nv[8];
+    f32x4_t nv[RT];
     bool bad = false;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < RT; ++e) {
         f32x4_t m = mv[e], v = vv[e];
         const f32x4_t ge = g[e];
         m.x = fmaf(b1, m.x, ob1 * ge.x);
@@ -397,21 +407,40 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     }
 
     if (BF16_N) {
-        // [octet][col][8]: this thread's 4 columns are 4 consecutive 16-byte units
-        NG_AS1 u32x4_t* Np = (NG_AS1 u32x4_t*)((NG_AS1 bf16_t*)md.N + ((long long)(row0 >> 3) * ldn + col0) * 8);
+        // [octet][col][8]: this lane holds rows 4 half .. 4 half + 3 of the band's octet for its 4
+        // columns, i.e. 8 of each octet's 16 bytes.  The pair swaps two columns so that each lane
+        // stores two whole octets (32 contiguous bytes): the even lane columns 0 and 1, the odd
+        // lane columns 2 and 3.
+        unsigned int lo[4], hi[4];     // per column: rows (0,1) and (2,3) of this lane's four rows
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            u32x4_t o;
-            o.x = pack_bf16x2(nv[0][c], nv[1][c]);
-            o.y = pack_bf16x2(nv[2][c], nv[3][c]);
-            o.z = pack_bf16x2(nv[4][c], nv[5][c]);
-            o.w = pack_bf16x2(nv[6][c], nv[7][c]);
-            Np[c] = o;   // (a nontemporal store is slower here: measured)
+            lo[c] = pack_bf16x2(nv[0][c], nv[1][c]);
+            hi[c] = pack_bf16x2(nv[2][c], nv[3][c]);
         }
+        // what the partner needs from this lane: even lane gives columns 2, 3; odd lane gives 0, 1
+        const unsigned int s0 = half ? lo[0] : lo[2], s1 = half ? hi[0] : hi[2];
+        const unsigned int s2 = half ? lo[1] : lo[3], s3 = half ? hi[1] : hi[3];
+        const unsigned int p0 = (unsigned int)__builtin_amdgcn_mov_dpp((int)s0, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+        const unsigned int p1 = (unsigned int)__builtin_amdgcn_mov_dpp((int)s1, 0xB1, 0xf, 0xf, false);
+        const unsigned int p2 = (unsigned int)__builtin_amdgcn_mov_dpp((int)s2, 0xB1, 0xf, 0xf, false);
+        const unsigned int p3 = (unsigned int)__builtin_amdgcn_mov_dpp((int)s3, 0xB1, 0xf, 0xf, false);
+        // columns kept by this lane: even 0, 1; odd 2, 3.  Octet = rows 0..3 (even lane's) then 4..7 (odd's).
+        u32x4_t oa, ob;
+        if (!half) {
+            oa = (u32x4_t){lo[0], hi[0], p0, p1};
+            ob = (u32x4_t){lo[1], hi[1], p2, p3};
+        } else {
+            oa = (u32x4_t){p0, p1, lo[2], hi[2]};
+            ob = (u32x4_t){p2, p3, lo[3], hi[3]};
+        }
+        NG_AS1 u32x4_t* Np =
+            (NG_AS1 u32x4_t*)((NG_AS1 bf16_t*)md.N + ((long long)(band0 >> 3) * ldn + col0 + 2 * half) * 8);
+        Np[0] = oa;   // (a nontemporal store is slower here: measured)
+        Np[1] = ob;
     } else {
         NG_AS1 unsigned char* Nf = (NG_AS1 unsigned char*)md.N;
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < RT; ++e)
             if (e < nrow) *(NG_AS1 f32x4_t*)(Nf + eoff[e] * 4u) = nv[e];
     }
     if (bad) atomicOr(status, 2);

@@ -162,7 +162,7 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
                 for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
         }
         for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
-            for (int tj = 0; tj < ceil_div(z.ldn, 256); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
+            for (int tj = 0; tj < ceil_div(z.ldn, kAdamPatchCols); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
     }
     xcd_order(proj, &p->proj);
     xcd_order(upd, &p->upd);

@@ -13,6 +13,7 @@ typedef unsigned short bf16_t;   // raw bfloat16 bits
 
 constexpr int kMaxS = 64;        // history slots
 constexpr int kDotPartsMax = 256; // per-matrix partial sums of the Gram-row reduction
+constexpr int kAdamPatchCols = 128; // columns of one transform+Adam workgroup patch (32 rows)
 constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (by kernel argument)
 constexpr int kJacobiLdsBudget = 139264;   // bytes of LDS the blocked Jacobi may use for its two row blocks
                                            // (16-row blocks up to lp = 544; the Gram variant adds 24 KiB)

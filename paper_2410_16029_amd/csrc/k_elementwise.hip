@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     const long long slot_bytes = md.slot_elems * (long long)HS;
     if (sc.use_fisher) {
         const NG_AS1 float* __restrict__ w = (const NG_AS1 float*)md.w32;
-#pragma unroll 2
+#pragma unroll 1
         for (int j = 0; j < s; ++j) {
             const float wj = w[j];
             const NG_AS1 unsigned char* slot = Hbase + (long long)j * slot_bytes;
@@ -361,49 +361,63 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     const float bc1 = dyn[pr.mat].bc1, bc2 = dyn[pr.mat].bc2;
     NG_AS1 unsigned char* Mb = (NG_AS1 unsigned char*)md.M;
     NG_AS1 unsigned char* Vb = (NG_AS1 unsigned char*)md.V;
-    f32x4_t mv[RT], vv[RT];
-#pragma unroll
-    for (int e = 0; e < RT; ++e) {
-        mv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
-        vv[e] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
-    }
-    f32x4_t nv[RT];
+    // two rows at a time (the moments of all four rows at once would cost occupancy)
+    unsigned int lo[4], hi[4];     // bf16 N, per column: rows (0,1) and (2,3) of this lane's four rows
     bool bad = false;
 #pragma unroll
-    for (int e = 0; e < RT; ++e) {
-        f32x4_t m = mv[e], v = vv[e];
-        const f32x4_t ge = g[e];
-        m.x = fmaf(b1, m.x, ob1 * ge.x);
-        m.y = fmaf(b1, m.y, ob1 * ge.y);
-        m.z = fmaf(b1, m.z, ob1 * ge.z);
-        m.w = fmaf(b1, m.w, ob1 * ge.w);
-        v.x = fmaf(b2, v.x, ob2 * ge.x * ge.x);
-        v.y = fmaf(b2, v.y, ob2 * ge.y * ge.y);
-        v.z = fmaf(b2, v.z, ob2 * ge.z * ge.z);
-        v.w = fmaf(b2, v.w, ob2 * ge.w * ge.w);
-        f32x4_t o;
-        if (sc.adam_mode == NG_ADAM_STANDARD) {
-            o.x = (m.x * bc1) / (sqrtf(v.x) * bc2 + sc.eps);
-            o.y = (m.y * bc1) / (sqrtf(v.y) * bc2 + sc.eps);
-            o.z = (m.z * bc1) / (sqrtf(v.z) * bc2 + sc.eps);
-            o.w = (m.w * bc1) / (sqrtf(v.w) * bc2 + sc.eps);
-        } else {
-            o.x = m.x / sqrtf(v.x + sc.eps);
-            o.y = m.y / sqrtf(v.y + sc.eps);
-            o.z = m.z / sqrtf(v.z + sc.eps);
-            o.w = m.w / sqrtf(v.w + sc.eps);
+    for (int pr2 = 0; pr2 < 2; ++pr2) {
+        f32x4_t mv[2], vv[2], nv[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            mv[u] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Mb + eoff[2 * pr2 + u] * 4u));
+            vv[u] = __builtin_nontemporal_load((const NG_AS1 f32x4_t*)(Vb + eoff[2 * pr2 + u] * 4u));
         }
-        const bool live = e < nrow;
-        if (live) {
-            __builtin_nontemporal_store(m, (NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
-            __builtin_nontemporal_store(v, (NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = 2 * pr2 + u;
+            f32x4_t m = mv[u], v = vv[u];
+            const f32x4_t ge = g[e];
+            m.x = fmaf(b1, m.x, ob1 * ge.x);
+            m.y = fmaf(b1, m.y, ob1 * ge.y);
+            m.z = fmaf(b1, m.z, ob1 * ge.z);
+            m.w = fmaf(b1, m.w, ob1 * ge.w);
+            v.x = fmaf(b2, v.x, ob2 * ge.x * ge.x);
+            v.y = fmaf(b2, v.y, ob2 * ge.y * ge.y);
+            v.z = fmaf(b2, v.z, ob2 * ge.z * ge.z);
+            v.w = fmaf(b2, v.w, ob2 * ge.w * ge.w);
+            f32x4_t o;
+            if (sc.adam_mode == NG_ADAM_STANDARD) {
+                o.x = (m.x * bc1) / (sqrtf(v.x) * bc2 + sc.eps);
+                o.y = (m.y * bc1) / (sqrtf(v.y) * bc2 + sc.eps);
+                o.z = (m.z * bc1) / (sqrtf(v.z) * bc2 + sc.eps);
+                o.w = (m.w * bc1) / (sqrtf(v.w) * bc2 + sc.eps);
+            } else {
+                o.x = m.x / sqrtf(v.x + sc.eps);
+                o.y = m.y / sqrtf(v.y + sc.eps);
+                o.z = m.z / sqrtf(v.z + sc.eps);
+                o.w = m.w / sqrtf(v.w + sc.eps);
+            }
+            const bool live = e < nrow;
+            if (live) {
+                __builtin_nontemporal_store(m, (NG_AS1 f32x4_t*)(Mb + eoff[e] * 4u));
+                __builtin_nontemporal_store(v, (NG_AS1 f32x4_t*)(Vb + eoff[e] * 4u));
+            }
+            bad |= live && (!(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
+                            !(fabsf(o.w) <= 3.0e38f));
+            nv[u].x = live ? o.x : 0.f;
+            nv[u].y = live ? o.y : 0.f;
+            nv[u].z = live ? o.z : 0.f;
+            nv[u].w = live ? o.w : 0.f;
+            if (!BF16_N && live) *(NG_AS1 f32x4_t*)((NG_AS1 unsigned char*)md.N + eoff[e] * 4u) = nv[u];
         }
-        bad |= live && (!(fabsf(o.x) <= 3.0e38f) | !(fabsf(o.y) <= 3.0e38f) | !(fabsf(o.z) <= 3.0e38f) |
-                        !(fabsf(o.w) <= 3.0e38f));
-        nv[e].x = live ? o.x : 0.f;
-        nv[e].y = live ? o.y : 0.f;
-        nv[e].z = live ? o.z : 0.f;
-        nv[e].w = live ? o.w : 0.f;
+        if (BF16_N) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned int pk = pack_bf16x2(nv[0][c], nv[1][c]);
+                if (pr2 == 0) lo[c] = pk;
+                else hi[c] = pk;
+            }
+        }
     }
 
     if (BF16_N) {
@@ -411,12 +425,6 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
         // columns, i.e. 8 of each octet's 16 bytes.  The pair swaps two columns so that each lane
         // stores two whole octets (32 contiguous bytes): the even lane columns 0 and 1, the odd
         // lane columns 2 and 3.
-        unsigned int lo[4], hi[4];     // per column: rows (0,1) and (2,3) of this lane's four rows
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            lo[c] = pack_bf16x2(nv[0][c], nv[1][c]);
-            hi[c] = pack_bf16x2(nv[2][c], nv[3][c]);
-        }
         // what the partner needs from this lane: even lane gives columns 2, 3; odd lane gives 0, 1
         const unsigned int s0 = half ? lo[0] : lo[2], s1 = half ? hi[0] : hi[2];
         const unsigned int s2 = half ? lo[1] : lo[3], s3 = half ? hi[1] : hi[3];
@@ -437,11 +445,6 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
             (NG_AS1 u32x4_t*)((NG_AS1 bf16_t*)md.N + ((long long)(band0 >> 3) * ldn + col0 + 2 * half) * 8);
         Np[0] = oa;   // (a nontemporal store is slower here: measured)
         Np[1] = ob;
-    } else {
-        NG_AS1 unsigned char* Nf = (NG_AS1 unsigned char*)md.N;
-#pragma unroll
-        for (int e = 0; e < RT; ++e)
-            if (e < nrow) *(NG_AS1 f32x4_t*)(Nf + eoff[e] * 4u) = nv[e];
     }
     if (bad) atomicOr(status, 2);
 }

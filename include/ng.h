@@ -197,6 +197,12 @@ int ng_set_profiling(ng_state* st, int enabled);
 int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset);
 
 const char* ng_strerror(int code);
+
+/* sizeof of a structure of this header as the library was compiled: which = 0 ng_matrix_desc,
+ * 1 ng_hparams, 2 ng_matrix_buffers, 3 ng_matrix_layout; 0 for any other value.  Lets a binding
+ * written in another language check its own declarations.  Host only. */
+size_t ng_struct_size(int which);
+
 void ng_destroy(ng_state* st);
 
 #ifdef __cplusplus

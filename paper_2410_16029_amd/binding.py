@@ -71,6 +71,11 @@ _lib.ng_get_layout.argtypes = [C.c_void_p, C.c_int, _P(ng_matrix_layout)]
 _lib.ng_get_status.argtypes = [C.c_void_p, C.c_void_p]
 _lib.ng_set_profiling.argtypes = [C.c_void_p, C.c_int]
 _lib.ng_get_phase_ms.argtypes = [C.c_void_p, _P(C.c_double), _P(C.c_int64), C.c_int]
+_lib.ng_struct_size.argtypes = [C.c_int]
+_lib.ng_struct_size.restype = C.c_size_t
+for _which, _cls in enumerate((ng_matrix_desc, ng_hparams, ng_matrix_buffers, ng_matrix_layout)):
+    if _lib.ng_struct_size(_which) != C.sizeof(_cls):
+        raise ImportError("binding.py and libng.so disagree on sizeof(%s): rebuild the library" % _cls.__name__)
 _lib.ng_strerror.argtypes = [C.c_int]
 _lib.ng_strerror.restype = C.c_char_p
 _lib.ng_destroy.argtypes = [C.c_void_p]

@@ -770,6 +770,16 @@ const char* ng_strerror(int code) {
     }
 }
 
+size_t ng_struct_size(int which) {
+    switch (which) {
+        case 0: return sizeof(ng_matrix_desc);
+        case 1: return sizeof(ng_hparams);
+        case 2: return sizeof(ng_matrix_buffers);
+        case 3: return sizeof(ng_matrix_layout);
+        default: return 0;
+    }
+}
+
 void ng_destroy(ng_state* st) {
     if (!st) return;
     if (st->ev_created) {

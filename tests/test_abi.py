@@ -24,6 +24,16 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_binding_structs_match_the_compiled_header():
+    for which, cls in enumerate((B.ng_matrix_desc, B.ng_hparams, B.ng_matrix_buffers, B.ng_matrix_layout)):
+        assert B._lib.ng_struct_size(which) == C.sizeof(cls), cls.__name__
+    assert B._lib.ng_struct_size(9) == 0
+    # the defaults land in the fields the binding names (a shifted layout would scramble them)
+    hp = B.ng_default_hparams()
+    assert (hp.refresh_power_iters, hp.refresh_oversample, hp.refresh_sweeps) == (2, 8, 30)
+    assert (hp.hist_dtype, hp.fisher_norm, hp.carry_history, hp.reserved, hp.seed) == (B.NG_F32, B.NG_NORM_S, 0, 0, 0)
+
+
 def test_query_sizes_c1_and_bf16_layout():
     hp = B.ng_default_hparams()
     assert (hp.s, hp.grad_dtype, hp.adam_mode) == (4, B.NG_F32, B.NG_ADAM_STANDARD)

@@ -13,7 +13,7 @@ from test_gpu_parity import DEV, TOL_BF16, TOL_F32, _assert_all
 pytestmark = pytest.mark.gpu
 
 
-def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pad_g=0, **kw):
+def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pad_g=0, gscale=1.0, **kw):
     """Free-running lockstep; with pad_w / pad_g the weights / gradients are column slices of
     wider tensors (leading dimension larger than n) whose remaining columns must stay untouched."""
     tol = TOL_F32 if dtype == "f32" else TOL_BF16
@@ -37,6 +37,8 @@ def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pa
     errs = []
     for step in range(steps):
         G = stream.next_set()
+        if gscale != 1.0:
+            G = [(g.float() * gscale).to(g.dtype) for g in G]
         if pad_g:
             Gfull = [torch.full((m, n + pad_g), float("nan"), dtype=g.dtype, device=DEV)
                      for (m, n), g in zip(shapes, G)]
@@ -179,6 +181,18 @@ def test_history_carry_over_across_refresh(dtype, hist):
     assert ls.status() == B.NG_OK
     _assert_all(errs, tol, "carry-over %s/%s" % (dtype, hist))
     assert ls.counters(0) == (9, 9 % 4, 4, 3)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("gscale", [1e-4, 1e2])
+def test_gradient_scale_extremes(dtype, gscale):
+    # ||R||^2 far below and far above s * lambda: the damping-dominated and the history-dominated
+    # regimes of the s x s system (lambda = 1e-3).  The upper scale is bounded by the oracle, not by
+    # the library: the printed form g/lambda - U z/lambda^2, which the oracle evaluates literally in
+    # float64, cancels about log10(||R||^2 / (s lambda)) digits (9.4 here; at a scale of 1e3 it is
+    # left with fewer digits than the 1e-4 tolerance).
+    ls, errs = _run([(200, 333), (130, 64)], 24, 4, dtype, 6, seed=79, k=24, gscale=gscale)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "gradient scale %g %s" % (gscale, dtype))
 
 
 def test_right_side_1b_shapes_sampled():

@@ -39,13 +39,22 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 // ------------------------------------------------------------------ per-step table upload
-__global__ void k_upload_dyn(MatDyn* table, DynChunk chunk, int first, int n) {
+__global__ void k_upload_dyn(MatDyn* table, DynChunk chunk, int first, int n, const MatDev* mats) {
     int i = threadIdx.x;
-    if (i < n) table[first + i] = chunk.e[i];
+    if (i >= n) return;
+    table[first + i] = chunk.e[i];
+    if (mats == nullptr) return;
+    // the zero-padded copy of the last gradient row's final partial 8-column chunk (bf16 projection)
+    const MatDev& md = mats[first + i];
+    const int nf = md.n & 7;
+    if (md.side == NG_SIDE_RIGHT || nf == 0 || md.tail8 == nullptr || chunk.e[i].g == nullptr) return;
+    const bf16_t* last = (const bf16_t*)chunk.e[i].g + (long long)(md.m - 1) * md.ld_g + (md.n - nf);
+    for (int x = 0; x < 8; ++x) md.tail8[x] = x < nf ? last[x] : (bf16_t)0;
 }
 
-hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, hipStream_t stream) {
-    hipLaunchKernelGGL(k_upload_dyn, dim3(1), dim3(128), 0, stream, table, chunk, first, n);
+hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, const MatDev* mats,
+                             hipStream_t stream) {
+    hipLaunchKernelGGL(k_upload_dyn, dim3(1), dim3(128), 0, stream, table, chunk, first, n, mats);
     return hipGetLastError();
 }
 

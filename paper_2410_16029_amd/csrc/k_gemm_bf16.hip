@@ -360,6 +360,82 @@ __device__ __forceinline__ void gemm_mainloop(floatx16 (&acc)[C::MI][C::NJ], LA&
     }
 }
 
+// Accumulators of one projection tile -> ring slot `head`.  Called after a barrier that ends the
+// main loop (the bf16 form stages the tile through the operand LDS).
+template <class C, bool HB>
+__device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], const MatDev& md, const MatDyn& dy,
+                                                 unsigned char* smem, int i0, int j0, int t, int wm, int wn, int li,
+                                                 int h) {
+    const int r = md.r, ldn = md.ldn, n = md.n;   // columns n..ldn-1 of the slot are zero
+    if (!HB) {
+        NG_AS1 float* R = (NG_AS1 float*)md.H + (long long)dy.head * md.slot_elems;
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj) {
+                const int col = j0 + wn * C::WN + nj * 32 + li;
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int row = i0 + wm * C::WM + mi * 32 + 8 * g + 4 * h + e;
+                        // (two stores under lane masks: a select on the value would pull every
+                        // accumulator into an ordinary register at once)
+                        if (row < r) {
+                            if (col < n) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = acc[mi][nj][4 * g + e];
+                            else if (col < ldn) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = 0.f;
+                        }
+                    }
+            }
+    } else {
+        // bf16 slot: the tile goes through LDS (float), one 32-row block of every wave-row at a
+        // time, so that each thread converts and stores 8 consecutive columns (16 bytes) of a row
+        // (the main loop ended on a barrier; ldn % 32 == 0, so a chunk that starts inside a row
+        // ends inside it)
+        constexpr int ROWS = C::NWM * 32, CH = C::BN / 8, PER_T = ROWS * CH / C::NT;
+        static_assert(ROWS * CH % C::NT == 0, "epilogue mapping");
+        float* Cs = reinterpret_cast<float*>(smem);
+        NG_AS1 bf16_t* Rb = (NG_AS1 bf16_t*)md.H + (long long)dy.head * md.slot_elems;
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        Cs[(wm * 32 + 8 * g + 4 * h + e) * C::LDC + wn * C::WN + nj * 32 + li] = acc[mi][nj][4 * g + e];
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PER_T; ++p) {
+                const int q = t + C::NT * p;
+                const int lr = q / CH, cc = q % CH;
+                const int row = i0 + (lr / 32) * C::WM + mi * 32 + (lr % 32);
+                const int col = j0 + cc * 8;
+                if (row < r && col < ldn) {
+                    const float* cp = Cs + lr * C::LDC + cc * 8;
+                    f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(cp);
+                    f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(cp + 4);
+                    if (col + 8 > n) {   // columns n..ldn-1 of the slot are zero
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            if (col + x >= n) c0[x] = 0.f;
+                            if (col + 4 + x >= n) c1[x] = 0.f;
+                        }
+                    }
+                    u32x4_t ov;
+                    ov.x = pack_bf16x2(c0.x, c0.y);
+                    ov.y = pack_bf16x2(c0.z, c0.w);
+                    ov.z = pack_bf16x2(c1.x, c1.y);
+                    ov.w = pack_bf16x2(c1.z, c1.w);
+                    *(NG_AS1 u32x4_t*)(Rb + ((unsigned)row * (unsigned)ldn + (unsigned)col)) = ov;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
 // HB: the ring slot receives bf16 instead of float.  RIGHT: the right-side form (the kernel's m x n
 // problem is the transpose of the caller's gradient: its columns are the gradient's rows).
 template <class C, bool HB, bool RIGHT>
@@ -408,61 +484,7 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
         }
     }
 
-    if (!HB) {
-        NG_AS1 float* R = (NG_AS1 float*)md.H + (long long)dy.head * md.slot_elems;
-#pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-            for (int nj = 0; nj < C::NJ; ++nj) {
-                const int col = j0 + wn * C::WN + nj * 32 + li;
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int row = i0 + wm * C::WM + mi * 32 + 8 * g + 4 * h + e;
-                        if (row < r && col < ldn) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = acc[mi][nj][4 * g + e];
-                    }
-            }
-    } else {
-        // bf16 slot: the tile goes through LDS (float), one 32-row block of every wave-row at a
-        // time, so that each thread converts and stores 8 consecutive columns (16 bytes) of a row
-        // (the main loop ended on a barrier; ldn % 32 == 0, so a chunk that starts inside a row
-        // ends inside it)
-        constexpr int ROWS = C::NWM * 32, CH = C::BN / 8, PER_T = ROWS * CH / C::NT;
-        static_assert(ROWS * CH % C::NT == 0, "epilogue mapping");
-        float* Cs = reinterpret_cast<float*>(smem);
-        NG_AS1 bf16_t* Rb = (NG_AS1 bf16_t*)md.H + (long long)dy.head * md.slot_elems;
-#pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi) {
-#pragma unroll
-            for (int nj = 0; nj < C::NJ; ++nj)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        Cs[(wm * 32 + 8 * g + 4 * h + e) * C::LDC + wn * C::WN + nj * 32 + li] = acc[mi][nj][4 * g + e];
-            __syncthreads();
-#pragma unroll
-            for (int p = 0; p < PER_T; ++p) {
-                const int q = t + C::NT * p;
-                const int lr = q / CH, cc = q % CH;
-                const int row = i0 + (lr / 32) * C::WM + mi * 32 + (lr % 32);
-                const int col = j0 + cc * 8;
-                if (row < r && col < ldn) {
-                    const float* cp = Cs + lr * C::LDC + cc * 8;
-                    const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(cp);
-                    const f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(cp + 4);
-                    u32x4_t ov;
-                    ov.x = pack_bf16x2(c0.x, c0.y);
-                    ov.y = pack_bf16x2(c0.z, c0.w);
-                    ov.z = pack_bf16x2(c1.x, c1.y);
-                    ov.w = pack_bf16x2(c1.z, c1.w);
-                    *(NG_AS1 u32x4_t*)(Rb + ((unsigned)row * (unsigned)ldn + (unsigned)col)) = ov;
-                }
-            }
-            __syncthreads();
-        }
-    }
+    project_epilogue<C, HB>(acc, md, dy, smem, i0, j0, t, wm, wn, li, h);
 }
 
 // =================================================================== update
@@ -780,42 +802,209 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restri
                        sc);
 }
 
+// =================================================================== projection, operands loaded straight into LDS
+// Left side, gradients of at least 8 columns.  A = PbT rows (RowMajorSrc, as in the update).  B = the caller's gradient G [k][ld_g]: its 16-byte chunks (8 consecutive columns of one
+// contraction row, at any 2-byte alignment) go into LDS as they are,
+//   slot(k, jc) = k * JC + (jc ^ ((k & 3) << 2))          (JC = BN / 8 chunks per contraction row)
+// and the MFMA fragment (8 consecutive k of one column) is assembled by two transposing reads:
+// ds_read_b64_tr_b16 hands lane i of a group of 16 lanes the values M[4e + i/4][i % 4], e = 0..3, where
+// M[q] are the 4 bf16 lane q of the group points at.  With lane q pointing at contraction row q / 4,
+// columns 4 (q % 4)..+3 of a 16-column block, lane i receives 4 consecutive k of column i.  The XOR
+// on the chunk index puts the four contraction rows of one read into different bank quarters.
+// The read is issued from inline assembly: as a builtin it makes the compiler wait for every
+// direct-to-LDS load in flight (it cannot tell that the ring stage being read is not the one being
+// filled), which serialises the ring.  The compiler does not count these reads, so
+// lds_read_tr16_done() waits for them and ties the result registers to that wait: nothing may
+// touch a result before it has passed through that call.
+#define lds_read_tr16(dst, addr, off) \
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
+__device__ __forceinline__ void lds_read_tr16_done(u32x2_t& x, u32x2_t& y) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x), "+v"(y)::"memory");
+}
+
+template <class C, int DBK>
+struct GradSrc {
+    static constexpr int JC = C::BN / 8, RPI = 64 / JC, INSTR = DBK / (RPI * C::NW);
+    static_assert((JC == 16 || JC == 32) && DBK % (RPI * C::NW) == 0 && (RPI * C::NW) % 4 == 0, "chunk mapping");
+    const NG_AS1 unsigned char* ptr;   // this lane's chunk in contraction row 0 of the matrix
+    long long pitch;                   // bytes per contraction row
+    int krow, m;                       // krow: this lane's row within the rows of instruction 0; m: rows to fetch
+    const NG_AS1 unsigned char* lastp; // source of this lane's chunk in row m, if it has one there
+    bool colok;
+    __device__ __forceinline__ void init(const void* G, long long ld_g, int m_, int n, int j0, int lane, int wv,
+                                         const void* tail8, const NG_AS1 unsigned char* zp) {
+        krow = wv * RPI + lane / JC;
+        const int jc = (lane % JC) ^ ((krow & 3) << 2);
+        const int col = j0 + 8 * jc;
+        colok = col < n;
+        // the chunk that straddles the last column is not fetched from the last row (it would end
+        // past the matrix) but from its zero-padded copy
+        const bool straddle = colok && col + 8 > n;
+        m = straddle ? m_ - 1 : m_;
+        lastp = straddle ? (const NG_AS1 unsigned char*)tail8 : zp;
+        pitch = ld_g * 2;
+        ptr = (const NG_AS1 unsigned char*)G + (long long)(colok ? col : 0) * 2;
+    }
+    __device__ __forceinline__ void issue(int kt, unsigned char* stage, const NG_AS1 unsigned char* zp, int wv) const {
+#pragma unroll
+        for (int p = 0; p < INSTR; ++p) {
+            const int k = kt * DBK + p * C::NW * RPI + krow;   // (p NW RPI) % 4 == 0: the XOR of init holds for every p
+            const NG_AS1 unsigned char* g = (colok && k < m) ? ptr + k * pitch : (k == m ? lastp : zp);
+            __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g, (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16,
+                                             0, 0);
+        }
+    }
+    // byte offset inside the stage that lane (li = lane % 32, h = lane / 32) passes to the first
+    // transposing read of column block cb (first column, a multiple of 32) and k-slots 8h..8h+3;
+    // the second read (k-slots +4) is 4 rows further, the next 16-deep step 16 rows.
+    static constexpr int ROW_BYTES = JC * 16;
+    static __device__ __forceinline__ int frag(int cb, int li, int h) {
+        const int q = li & 15;
+        const int k = 8 * h + (q >> 2);
+        const int jc = (cb >> 3) + 2 * (li >> 4) + ((q & 3) >> 1);
+        return (k * JC + (jc ^ ((q >> 2) << 2))) * 16 + (q & 1) * 8;
+    }
+};
+
+template <class C, int DBK, int NST, bool HB>
+__global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restrict__ mats,
+                                                           const MatDyn* __restrict__ dyn,
+                                                           const TileRef* __restrict__ tiles, const void* zero16) {
+    typedef DlCfg<C, DBK, NST> D;
+    constexpr int KK = DBK / 16;
+    typedef RowMajorSrc<C, DBK, C::BM> ARows;
+    typedef GradSrc<C, DBK> BGrad;
+    static_assert(BGrad::INSTR == D::B_INSTR, "stage accounting");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const TileRef tr = tiles[blockIdx.x];
+    if (tr.mat < 0) return;   // padding entry of the XCD-ordered table
+    const MatDev& md = mats[tr.mat];
+    if (md.side == NG_SIDE_RIGHT) return;
+    const int i0 = tr.ti * C::BM, j0 = tr.tj * C::BN;
+    if (!projection_tile_direct(md.n)) return;   // k_project_bf16 takes those
+    const MatDyn dy = dyn[tr.mat];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wv / C::NWN, wn = wv % C::NWN, li = lane & 31, h = lane >> 5;
+    const int nk = (md.m + DBK - 1) / DBK;
+
+    floatx16 acc[C::MI][C::NJ];
+    zero_acc<C>(acc);
+
+    const NG_AS1 unsigned char* zp = (const NG_AS1 unsigned char*)zero16;
+    ARows a_rm;
+    BGrad b_g;
+    a_rm.init(md.PbT, md.ldk, i0, md.r, lane, wv);
+    b_g.init(dy.g, md.ld_g, md.m, md.n, j0, lane, wv, md.tail8, zp);
+    auto issue = [&](int kt) {
+        unsigned char* stage = smem + (kt % NST) * D::STAGE;
+        a_rm.issue(kt, stage, zp, wv);
+        b_g.issue(kt, stage + D::A_BYTES, zp, wv);
+    };
+    const int a_row = wm * C::WM + li;
+    const int a_sw = ARows::swz(li);
+    int b_off[C::NJ];
+#pragma unroll
+    for (int nj = 0; nj < C::NJ; ++nj) b_off[nj] = D::A_BYTES + BGrad::frag(wn * C::WN + 32 * nj, li, h);
+
+    // the ring protocol of k_update_bf16_dl
+    constexpr int PER_STAGE = D::A_INSTR + D::B_INSTR;
+    static_assert(NST == 3, "ring depth");
+    for (int q = 0; q < NST - 1; ++q)
+        if (q < nk) issue(q);
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) wait_vmcnt<PER_STAGE>();
+        else wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");
+        if (kt + NST - 1 < nk) issue(kt + NST - 1);
+        const unsigned char* cur = smem + (kt % NST) * D::STAGE;
+        const unsigned cur_lds = (unsigned)(unsigned long long)(NG_AS3 unsigned char*)cur;   // LDS byte address
+        u32x4_t a[KK][C::MI], b[KK][C::NJ];
+        u32x2_t blo[KK][C::NJ], bhi[KK][C::NJ];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+                a[kk][mi] = *reinterpret_cast<const u32x4_t*>(cur + ARows::frag(a_row + 32 * mi, a_sw, 2 * kk + h));
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj) {
+                const unsigned bp = cur_lds + b_off[nj];
+                lds_read_tr16(blo[kk][nj], bp, kk * 16 * BGrad::ROW_BYTES);
+                lds_read_tr16(bhi[kk][nj], bp, kk * 16 * BGrad::ROW_BYTES + 4 * BGrad::ROW_BYTES);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj) {
+                lds_read_tr16_done(blo[kk][nj], bhi[kk][nj]);
+                b[kk][nj] = (u32x4_t){blo[kk][nj].x, blo[kk][nj].y, bhi[kk][nj].x, bhi[kk][nj].y};
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+                for (int nj = 0; nj < C::NJ; ++nj)
+                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8_t*>(&a[kk][mi]), *reinterpret_cast<const bf16x8_t*>(&b[kk][nj]),
+                        acc[mi][nj], 0, 0, 0);
+    }
+    __syncthreads();   // every wave is done with the ring: the bf16 epilogue stages C through the same LDS
+
+    // what the chunk that straddles the last column brought in beyond column n - 1 sits in accumulator
+    // columns >= n, which the epilogue zeroes
+    project_epilogue<C, HB>(acc, md, dy, smem, i0, j0, t, wm, wn, li, h);
+}
+
 // =================================================================== launchers
 // Tile configurations: 256 x 128 workgroup tiles (128 x 64 per wavefront); the projection falls
 // back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half empty).
 typedef Cfg<128, 128, 64, 64, 64> Cfg0;
 typedef Cfg<256, 128, 128, 64, 64> Cfg2;
+typedef Cfg<128, 256, 64, 128, 64> Cfg3;   // projection: twice the gradient bytes per stage
 
 static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
 
+// The tile table has three runs: left-side tiles for the direct-to-LDS kernel, the other left-side
+// tiles (gradients of fewer than 8 columns) and right-side tiles (register-staged kernel, one
+// instance per side).
 template <class C, bool HB>
-static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles, int sides,
-                              hipStream_t stream) {
+static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_direct, int n_staged,
+                              int n_right, const void* zero16, hipStream_t stream) {
+    constexpr int DBK = 32, NST = 3;   // as in the update: two workgroups per CU
+    constexpr int lds_dl = DlCfg<C, DBK, NST>::LDS_BYTES;
     static bool attr = false;
     if (!attr) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16_dl<C, DBK, NST, HB>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_dl);
         attr = true;
     }
-    if (sides & 1)
-        hipLaunchKernelGGL((k_project_bf16<C, HB, false>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
-                           tiles);
-    if (sides & 2)
-        hipLaunchKernelGGL((k_project_bf16<C, HB, true>), dim3(n_tiles), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
-                           tiles);
+    if (n_direct > 0)
+        hipLaunchKernelGGL((k_project_bf16_dl<C, DBK, NST, HB>), dim3(n_direct), dim3(C::NT), lds_dl, stream, mats, dyn,
+                           tiles, zero16);
+    if (n_staged > 0)
+        hipLaunchKernelGGL((k_project_bf16<C, HB, false>), dim3(n_staged), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
+                           tiles + n_direct);
+    if (n_right > 0)
+        hipLaunchKernelGGL((k_project_bf16<C, HB, true>), dim3(n_right), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
+                           tiles + n_direct + n_staged);
     return hipGetLastError();
 }
 
-hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, int hist_bf16, int sides, hipStream_t stream) {
-    if (n_tiles == 0) return hipSuccess;
+hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_direct, int n_staged,
+                               int n_right, int max_r, int hist_bf16, const void* zero16, hipStream_t stream) {
     if (project_cfg(max_r) == 0)
-        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_tiles, sides, stream)
-                         : run_project<Cfg0, false>(mats, dyn, tiles, n_tiles, sides, stream);
-    return hist_bf16 ? run_project<Cfg2, true>(mats, dyn, tiles, n_tiles, sides, stream)
-                     : run_project<Cfg2, false>(mats, dyn, tiles, n_tiles, sides, stream);
+        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
+                         : run_project<Cfg0, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
+    return hist_bf16 ? run_project<Cfg3, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
+                     : run_project<Cfg3, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
 }
 
 // sides: bit 0 = the layer set has left-side matrices, bit 1 = right-side ones.  Each side has its own
@@ -847,8 +1036,8 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
 // which: 0 = projection (needs the largest rank of the layer set), 1 = update
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
     const bool small = which == 0 && project_cfg(max_r) == 0;
-    *bm = small ? Cfg0::BM : Cfg2::BM;
-    *bn = small ? Cfg0::BN : Cfg2::BN;
+    *bm = small ? Cfg0::BM : (which == 0 ? Cfg3::BM : Cfg2::BM);
+    *bn = small ? Cfg0::BN : (which == 0 ? Cfg3::BN : Cfg2::BN);
 }
 
 }  // namespace ng

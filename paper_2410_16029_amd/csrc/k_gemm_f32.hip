@@ -198,15 +198,15 @@ __device__ __forceinline__ f32x4_t load_vec4(const NG_AS1 void* p, long long bas
 // block per wavefront, for products with a short side or a short contraction), BK = 16.  Each
 // thread moves 4-element vectors per operand and k-step, taken along the operand's contiguous
 // dimension (tile index or contraction index, whichever has stride 1).
-constexpr int BK = 16;
-
-template <int TS>
+template <int TS, int BK>
 __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn, int grad_dtype,
                                                   StepScalars sc) {
     constexpr int LDT = TS + 4;
     constexpr int NB = TS / 64;          // 32 x 32 blocks per wavefront and dimension
-    constexpr int NV = TS / 64;          // vectors per thread, operand and k-step
+    constexpr int NV = TS * BK / 1024;   // vectors per thread, operand and k-step
+    constexpr int KT = BK / 4;           // threads along the contraction index (k-fast mapping)
+    constexpr int RPP = 256 / KT;        // tile rows per pass of the k-fast mapping
     constexpr int TPR = TS / 4;          // threads along the tile index (tile-fast mapping)
     __shared__ __attribute__((aligned(16))) float As[BK][LDT];
     __shared__ __attribute__((aligned(16))) float Bs[BK][LDT];
@@ -224,12 +224,12 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
 
     // loader mappings: vector q of this thread covers 4 consecutive positions of the stride-1
     // dimension.  tile-fast: positions 4 (t % TPR) of the tile index at k = t / TPR + (256 / TPR) q;
-    // k-fast: k = 4 (t % 4) at tile index t / 4 + 64 q.
+    // k-fast: k = 4 (t % KT) at tile index t / KT + RPP q.
     const bool a_i_fast = (v.sAi == 1);
     const bool b_j_fast = (v.sBj == 1);
     constexpr int KSTEP = 256 / TPR;
     const int tf = 4 * (t % TPR), tk = t / TPR;    // tile-fast mapping
-    const int kf = 4 * (t & 3), kt_ = t >> 2;      // k-fast mapping
+    const int kf = 4 * (t % KT), kt_ = t / KT;     // k-fast mapping
 
     floatx16 acc[NB][NB];
 #pragma unroll
@@ -247,14 +247,14 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
                 const int i = i0 + tf, k = k0 + tk + KSTEP * q;
                 ra[q] = load_vec4(Ap, (long long)i + (long long)k * v.sAk, i, v.M, k < v.K, v.a_bf16);
             } else {
-                const int i = i0 + kt_ + 64 * q, k = k0 + kf;
+                const int i = i0 + kt_ + RPP * q, k = k0 + kf;
                 ra[q] = load_vec4(Ap, (long long)i * v.sAi + (long long)k, k, v.K, i < v.M, v.a_bf16);
             }
             if (b_j_fast) {
                 const int j = j0 + tf, k = k0 + tk + KSTEP * q;
                 rb[q] = load_vec4(Bp, (long long)k * v.sBk + (long long)j, j, v.Nvalid, k < v.K, v.b_bf16);
             } else {
-                const int j = j0 + kt_ + 64 * q, k = k0 + kf;
+                const int j = j0 + kt_ + RPP * q, k = k0 + kf;
                 rb[q] = load_vec4(Bp, (long long)k + (long long)j * v.sBj, k, v.K, j < v.Nvalid, v.b_bf16);
             }
         }
@@ -265,21 +265,30 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
             if (a_i_fast) {
                 *reinterpret_cast<f32x4_t*>(&As[tk + KSTEP * q][tf]) = ra[q];
             } else {
-                As[kf][kt_ + 64 * q] = ra[q].x;
-                As[kf + 1][kt_ + 64 * q] = ra[q].y;
-                As[kf + 2][kt_ + 64 * q] = ra[q].z;
-                As[kf + 3][kt_ + 64 * q] = ra[q].w;
+                As[kf][kt_ + RPP * q] = ra[q].x;
+                As[kf + 1][kt_ + RPP * q] = ra[q].y;
+                As[kf + 2][kt_ + RPP * q] = ra[q].z;
+                As[kf + 3][kt_ + RPP * q] = ra[q].w;
             }
             if (b_j_fast) {
                 *reinterpret_cast<f32x4_t*>(&Bs[tk + KSTEP * q][tf]) = rb[q];
             } else {
-                Bs[kf][kt_ + 64 * q] = rb[q].x;
-                Bs[kf + 1][kt_ + 64 * q] = rb[q].y;
-                Bs[kf + 2][kt_ + 64 * q] = rb[q].z;
-                Bs[kf + 3][kt_ + 64 * q] = rb[q].w;
+                Bs[kf][kt_ + RPP * q] = rb[q].x;
+                Bs[kf + 1][kt_ + RPP * q] = rb[q].y;
+                Bs[kf + 2][kt_ + RPP * q] = rb[q].z;
+                Bs[kf + 3][kt_ + RPP * q] = rb[q].w;
             }
         }
     };
+
+    // 32 x 32 blocks that lie wholly outside the product (the tail tile of a dimension such as
+    // l = r + 8) are skipped: their operands are zero fill and their results are never stored.
+    bool vx[NB], vy[NB];
+#pragma unroll
+    for (int x = 0; x < NB; ++x) {
+        vx[x] = i0 + wm * (TS / 2) + 32 * x < v.M;
+        vy[x] = j0 + wn * (TS / 2) + 32 * x < v.N;
+    }
 
     const int nk = (v.K + BK - 1) / BK;
     fetch(0);
@@ -299,7 +308,8 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
             for (int x = 0; x < NB; ++x)
 #pragma unroll
                 for (int y = 0; y < NB; ++y)
-                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+                    if (vx[x] && vy[y])
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
         }
         __syncthreads();
         if (kt + 1 < nk) stage();
@@ -343,8 +353,8 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
     const bool big = max_m >= 128 && max_n >= 128 && max_k >= 64;
     const int ts = big ? 128 : 64;
     dim3 g((max_n + ts - 1) / ts, (max_m + ts - 1) / ts, n_mats);
-    if (big) hipLaunchKernelGGL(k_gemm_f32<128>, g, dim3(256), 0, stream, (int)op, mats, dyn, grad_dtype, sc);
-    else hipLaunchKernelGGL(k_gemm_f32<64>, g, dim3(256), 0, stream, (int)op, mats, dyn, grad_dtype, sc);
+    if (big) k_gemm_f32<128, 32><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
+    else k_gemm_f32<64, 16><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
     return hipGetLastError();
 }
 

@@ -124,7 +124,8 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
 struct Plan {
     std::vector<Sizes> sz;
     std::vector<TileRef> proj, upd, dots, patches;
-    size_t off_status, off_mats, off_dyn, off_proj, off_upd, off_dots, off_patches, off_scratch;
+    int proj_direct, proj_staged, proj_right;   // lengths of the three runs of proj
+    size_t off_status, off_mats, off_dyn, off_tail8, off_proj, off_upd, off_dots, off_patches, off_scratch;
     size_t total;
 };
 
@@ -148,15 +149,20 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     int pbm = 128, pbn = 128, ubm = 128, ubn = 128;
     bf16_tile_shape(0, max_r, &pbm, &pbn);
     bf16_tile_shape(1, max_r, &ubm, &ubn);
-    std::vector<TileRef> proj, upd;
+    std::vector<TileRef> proj_direct, proj_staged, proj_right, upd;
     p->dots.clear();
     p->patches.clear();
     for (int i = 0; i < n_mats; ++i) {
         derive(d[i], hp, &p->sz[i]);
         const Sizes& z = p->sz[i];
         if (hp.grad_dtype == NG_BF16) {
-            for (int tj = 0; tj < ceil_div(z.ldn, pbn); ++tj)
-                for (int ti = 0; ti < ceil_div(d[i].r, pbm); ++ti) proj.push_back(TileRef{i, ti, tj, 0});
+            const int n_eff = effective(d[i]).n;
+            for (int tj = 0; tj < ceil_div(z.ldn, pbn); ++tj) {
+                std::vector<TileRef>& run = d[i].side == NG_SIDE_RIGHT      ? proj_right
+                                            : projection_tile_direct(n_eff) ? proj_direct
+                                                                            : proj_staged;
+                for (int ti = 0; ti < ceil_div(d[i].r, pbm); ++ti) run.push_back(TileRef{i, ti, tj, 0});
+            }
             // update tiles cover the weight in the caller's orientation on either side
             for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
                 for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
@@ -164,13 +170,25 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
             for (int tj = 0; tj < ceil_div(z.ldn, kAdamPatchCols); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
     }
-    xcd_order(proj, &p->proj);
+    {
+        std::vector<TileRef> a, b, c;
+        xcd_order(proj_direct, &a);
+        xcd_order(proj_staged, &b);
+        xcd_order(proj_right, &c);
+        p->proj_direct = (int)a.size();
+        p->proj_staged = (int)b.size();
+        p->proj_right = (int)c.size();
+        p->proj = a;
+        p->proj.insert(p->proj.end(), b.begin(), b.end());
+        p->proj.insert(p->proj.end(), c.begin(), c.end());
+    }
     xcd_order(upd, &p->upd);
     // Gram-row parts are appended in make_mats (they need dot_nparts)
     size_t off = 0;
     p->off_status = off; off += 256;
     p->off_mats = off;   off += align_up(sizeof(MatDev) * (size_t)n_mats, 256);
     p->off_dyn = off;    off += align_up(sizeof(MatDyn) * (size_t)n_mats, 256);
+    p->off_tail8 = off;  off += align_up((size_t)16 * (size_t)n_mats, 256);
     p->off_proj = off;   off += align_up(sizeof(TileRef) * p->proj.size(), 256);
     p->off_upd = off;    off += align_up(sizeof(TileRef) * p->upd.size(), 256);
     p->off_dots = off;   off += align_up(sizeof(TileRef) * (size_t)n_mats * kDotPartsMax, 256);
@@ -250,7 +268,8 @@ int upload_dyn(ng_state* st, const void* const* grads, void* const* weights, boo
                 e.bc2 = 1.f;
             }
         }
-        NG_HIP(launch_upload_dyn(st->d_dyn, chunk, first, n, stream));
+        NG_HIP(launch_upload_dyn(st->d_dyn, chunk, first, n,
+                                 (stepping && st->hp.grad_dtype == NG_BF16) ? st->d_mats : nullptr, stream));
     }
     return NG_OK;
 }
@@ -457,6 +476,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
                 char* ab = (char*)bufs[i].buf[NG_BUF_AUX];
                 md.Pb = (bf16_t*)(ab + z.aux_pb_off);
                 md.PbT = (bf16_t*)(ab + z.aux_pbt_off);
+                md.tail8 = (bf16_t*)(ws + pl.off_tail8 + (size_t)16 * i);
             }
             md.dot_parts = (double*)(ws + off); off += z.ws_parts;
             md.Ya = (float*)(ws + off); off += z.ws_y;
@@ -647,7 +667,9 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, (int)st->plan.proj.size(), st->max_r, sc.hist_bf16, st->sides, stream));
+    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, st->plan.proj_direct, st->plan.proj_staged,
+                                       st->plan.proj_right, st->max_r, sc.hist_bf16, (const char*)st->d_status + 64,
+                                       stream));
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));

@@ -54,6 +54,8 @@ struct MatDev {
     int* order;       // [lp]
     int* jflag;       // [0] rotations this sweep, [1] converged
     float* carry;     // [r][ldn] scratch of the history carry-over (null unless enabled)
+    bf16_t* tail8;    // 8 bf16 in the workspace: the last gradient row's columns from the last multiple of
+                      // 8 on, zero-padded (rewritten every step, see launch_upload_dyn)
     int lp, jb;       // padded size and row-block size of the blocked Jacobi
 };
 
@@ -90,10 +92,18 @@ struct TileRef {
     int pad;
 };
 
+// Left-side projection tiles of a gradient with at least 8 columns take the direct-to-LDS kernel.  It
+// reads whole 16-byte chunks; the one chunk per row that straddles the last column (n % 8 != 0) reads up
+// to 7 elements past the row's end, which is the start of the next row or its padding: inside the
+// caller's buffer for every row but the last, whose chunk comes from MatDev::tail8 instead.
+__host__ __device__ inline bool projection_tile_direct(int n) { return n >= 8; }
+
 // ---------------------------------------------------------------- launchers
 // Every launcher enqueues on `stream` and returns hipGetLastError().
 
-hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, hipStream_t stream);
+// mats != null: also refresh MatDev::tail8 of the left-side matrices from the bf16 gradients in the chunk
+hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, const MatDev* mats,
+                             hipStream_t stream);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);   // bytes % 4 == 0
 
 // fp32 MFMA grouped GEMM with selectable operands (k_gemm_f32.hip)
@@ -129,10 +139,14 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
 
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
-// sides: bit 0 = left-side matrices present, bit 1 = right-side ones (one kernel instance each)
-hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
-                               int max_r, int hist_bf16, int sides, hipStream_t stream);
 // zero16: 16 bytes of zeros in device memory (fetched in place of out-of-range operand chunks)
+// The projection's tile table has three runs, each with its own kernel: n_direct left-side tiles for
+// the direct-to-LDS kernel (see projection_tile_direct), then n_staged other left-side tiles, then
+// n_right right-side tiles.
+hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_direct,
+                               int n_staged, int n_right, int max_r, int hist_bf16, const void* zero16,
+                               hipStream_t stream);
+// sides: bit 0 = left-side matrices present, bit 1 = right-side ones (one kernel instance each)
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, const void* zero16, int sides, hipStream_t stream);
 

@@ -217,3 +217,44 @@ def test_full_1b_layer_set_sampled():
     _assert_all(errs, TOL_BF16, "c5 full")
     for i in (0, 83, 167):
         assert ls.counters(i) == (2, 2, 2, 1)
+
+
+@pytest.mark.parametrize("pad_g", [0, 3])
+@pytest.mark.parametrize("hist", ["f32", "bf16"])
+def test_bf16_projection_slot_small_and_ragged(hist, pad_g):
+    """The bf16 projection alone, against the oracle's R = P^T G on the projector the library holds
+    (rounded to bf16, as the kernel's operand is), at shapes where single rows and columns matter:
+    few contraction rows (the last row's share of the columns beyond the last whole 8-column chunk is
+    added separately), column counts that are not multiples of 8, and gradients that are column
+    slices of wider tensors whose other columns hold NaN.  The slot's columns n..ldn-1 must be zero."""
+    import oracle.natural_galore as ONG
+
+    shapes = [(9, 13), (24, 45), (40, 8), (16, 7), (33, 300), (70, 261), (2, 9), (1, 12)]
+    ranks = [4, 8, 8, 5, 16, 33, 2, 1]
+    gen = torch.Generator(device="cpu").manual_seed(77)
+    G, Gfull = [], []
+    for (m, n) in shapes:
+        g = torch.randn(m, n, generator=gen).to(torch.bfloat16).to(DEV)
+        if pad_g:
+            gf = torch.full((m, n + pad_g), float("nan"), dtype=torch.bfloat16, device=DEV)
+            gf[:, :n] = g
+            Gfull.append(gf)
+            g = gf[:, :n]
+        G.append(g)
+    W = [torch.zeros(m, n, dtype=torch.bfloat16, device=DEV) for (m, n) in shapes]
+    ls = B.LayerSet(shapes, ranks, s=2, dtype="bf16", device=DEV, hist_dtype=hist,
+                    ld_g=[n + pad_g for (m, n) in shapes] if pad_g else None)
+    ls.refresh(G)
+    ls.step(G, W, 1e-3)
+    assert ls.status() == B.NG_OK
+    torch.cuda.synchronize()
+    for i, (m, n) in enumerate(shapes):
+        _, head, count, _ = ls.counters(i)
+        slot = (head - 1) % 2
+        Hs = ls.H(i)[slot].double().cpu().numpy()
+        Pb = ls.P(i).to(torch.bfloat16).double().cpu().numpy()
+        R = ONG.project(Pb, G[i].double().cpu().numpy())
+        scale = np.abs(R).max()
+        tol = 1e-5 if hist == "f32" else 2.0 ** -8
+        assert np.abs(Hs[:, :n] - R).max() <= tol * scale, (i, shapes[i], np.abs(Hs[:, :n] - R).max() / scale)
+        assert not Hs[:, n:].any(), (i, shapes[i], "padding columns of the slot are not zero")

@@ -818,9 +818,12 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restri
 // touch a result before it has passed through that call.
 #define lds_read_tr16(dst, addr, off) \
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
+#define lds_read_b128(dst, addr, off) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 __device__ __forceinline__ void lds_read_tr16_done(u32x2_t& x, u32x2_t& y) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x), "+v"(y)::"memory");
 }
+__device__ __forceinline__ void lds_read_done(u32x4_t& x) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x)::"memory"); }
 
 template <class C, int DBK>
 struct GradSrc {
@@ -902,55 +905,105 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
         a_rm.issue(kt, stage, zp, wv);
         b_g.issue(kt, stage + D::A_BYTES, zp, wv);
     };
-    const int a_row = wm * C::WM + li;
-    const int a_sw = ARows::swz(li);
-    int b_off[C::NJ];
+    // fragment addresses inside a stage (LDS byte offsets; + 2048 per 32 A rows)
+    const unsigned smem_lds = (unsigned)(unsigned long long)(NG_AS3 unsigned char*)smem;
+    static_assert(KK == 2, "two 16-deep steps per stage");
+    unsigned a_off[KK], b_off[C::NJ];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) a_off[kk] = ARows::frag(wm * C::WM + li, ARows::swz(li), 2 * kk + h);
 #pragma unroll
     for (int nj = 0; nj < C::NJ; ++nj) b_off[nj] = D::A_BYTES + BGrad::frag(wn * C::WN + 32 * nj, li, h);
 
-    // the ring protocol of k_update_bf16_dl
-    constexpr int PER_STAGE = D::A_INSTR + D::B_INSTR;
-    static_assert(NST == 3, "ring depth");
-    for (int q = 0; q < NST - 1; ++q)
-        if (q < nk) issue(q);
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) wait_vmcnt<PER_STAGE>();
-        else wait_vmcnt<0>();
-        asm volatile("s_barrier" ::: "memory");
-        if (kt + NST - 1 < nk) issue(kt + NST - 1);
-        const unsigned char* cur = smem + (kt % NST) * D::STAGE;
-        const unsigned cur_lds = (unsigned)(unsigned long long)(NG_AS3 unsigned char*)cur;   // LDS byte address
-        u32x4_t a[KK][C::MI], b[KK][C::NJ];
-        u32x2_t blo[KK][C::NJ], bhi[KK][C::NJ];
+    // One 16-deep step's fragments.  They are read by inline assembly (see lds_read_tr16) and may
+    // only be used after done(): the reads of step kk of stage kt + 1 are issued right after the
+    // MFMAs of step kk of stage kt, into the registers those MFMAs have just read, and complete
+    // while the other step's MFMAs run.
+    struct Frag {
+        u32x4_t a[C::MI];
+        u32x2_t blo[C::NJ], bhi[C::NJ];
+    };
+    Frag f[KK];
+    auto read_frags = [&](int kt) {
+        const unsigned cur = smem_lds + (unsigned)(kt % NST) * D::STAGE;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi)
-                a[kk][mi] = *reinterpret_cast<const u32x4_t*>(cur + ARows::frag(a_row + 32 * mi, a_sw, 2 * kk + h));
+            for (int mi = 0; mi < C::MI; ++mi) lds_read_b128(f[kk].a[mi], cur + a_off[kk], mi * 32 * ARows::KC * 16);
 #pragma unroll
             for (int nj = 0; nj < C::NJ; ++nj) {
-                const unsigned bp = cur_lds + b_off[nj];
-                lds_read_tr16(blo[kk][nj], bp, kk * 16 * BGrad::ROW_BYTES);
-                lds_read_tr16(bhi[kk][nj], bp, kk * 16 * BGrad::ROW_BYTES + 4 * BGrad::ROW_BYTES);
+                lds_read_tr16(f[kk].blo[nj], cur + b_off[nj], kk * 16 * BGrad::ROW_BYTES);
+                lds_read_tr16(f[kk].bhi[nj], cur + b_off[nj], kk * 16 * BGrad::ROW_BYTES + 4 * BGrad::ROW_BYTES);
             }
         }
+    };
+    auto read_step = [&](int kt, int kk) {   // kk is a literal at every call
+        const unsigned cur = smem_lds + (unsigned)(kt % NST) * D::STAGE;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
+        for (int mi = 0; mi < C::MI; ++mi) lds_read_b128(f[kk].a[mi], cur + a_off[kk], mi * 32 * ARows::KC * 16);
+#pragma unroll
+        for (int nj = 0; nj < C::NJ; ++nj) {
+            lds_read_tr16(f[kk].blo[nj], cur + b_off[nj], kk * 16 * BGrad::ROW_BYTES);
+            lds_read_tr16(f[kk].bhi[nj], cur + b_off[nj], kk * 16 * BGrad::ROW_BYTES + 4 * BGrad::ROW_BYTES);
+        }
+    };
+    auto done = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi) lds_read_done(f[kk].a[mi]);
+#pragma unroll
+            for (int nj = 0; nj < C::NJ; ++nj) lds_read_tr16_done(f[kk].blo[nj], f[kk].bhi[nj]);
+        }
+    };
+    auto mma_step = [&](int kk) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
             for (int nj = 0; nj < C::NJ; ++nj) {
-                lds_read_tr16_done(blo[kk][nj], bhi[kk][nj]);
-                b[kk][nj] = (u32x4_t){blo[kk][nj].x, blo[kk][nj].y, bhi[kk][nj].x, bhi[kk][nj].y};
+                const u32x4_t b = {f[kk].blo[nj].x, f[kk].blo[nj].y, f[kk].bhi[nj].x, f[kk].bhi[nj].y};
+                acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(&f[kk].a[mi]),
+                                                                      *reinterpret_cast<const bf16x8_t*>(&b), acc[mi][nj],
+                                                                      0, 0, 0);
             }
+    };
+
+    // Ring of NST stages, stage kt in buffer kt % NST.  At the top of iteration kt this wave holds the
+    // fragments of stage kt (its reads are awaited there), so after the barrier buffer kt % NST is
+    // free for stage kt + NST, stage kt + 1 has landed (each wave waited for its own loads of it;
+    // loads complete in order) and the stages up to kt + NST - 1 are in flight.
+    constexpr int PER_STAGE = D::A_INSTR + D::B_INSTR;
+    static_assert(NST >= 2 && NST <= 4 && (NST - 1) * PER_STAGE <= 15, "ring depth / wait counter");
+    auto wait_all_but = [&](int stages) {   // at most `stages` stages' worth of this lane's loads in flight
+        if (stages <= 0) wait_vmcnt<0>();
+        else if (stages == 1) wait_vmcnt<PER_STAGE>();
+        else if (stages == 2) wait_vmcnt<(NST > 2 ? 2 : 1) * PER_STAGE>();
+        else wait_vmcnt<(NST > 3 ? 3 : 1) * PER_STAGE>();
+    };
+    for (int q = 0; q < NST; ++q)
+        if (q < nk) issue(q);
+    wait_all_but((nk < NST ? nk : NST) - 1);
+    asm volatile("s_barrier" ::: "memory");
+    read_frags(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const bool more = kt + 1 < nk;
+        if (more) {
+            const int ahead = nk - kt - 2;   // stages issued beyond kt + 1
+            wait_all_but(ahead < NST - 2 ? ahead : NST - 2);
+        }
+        done();
+        if (more) {
+            // a bare barrier: __syncthreads() would also wait for the loads in flight
+            asm volatile("s_barrier" ::: "memory");
+            if (kt + NST < nk) issue(kt + NST);
+        }
+        mma_step(0);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-                for (int nj = 0; nj < C::NJ; ++nj)
-                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        *reinterpret_cast<const bf16x8_t*>(&a[kk][mi]), *reinterpret_cast<const bf16x8_t*>(&b[kk][nj]),
-                        acc[mi][nj], 0, 0, 0);
+        if (more) read_step(kt + 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) read_step(kt + 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();   // every wave is done with the ring: the bf16 epilogue stages C through the same LDS
 
@@ -964,36 +1017,37 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
 // back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half empty).
 typedef Cfg<128, 128, 64, 64, 64> Cfg0;
 typedef Cfg<256, 128, 128, 64, 64> Cfg2;
-typedef Cfg<128, 256, 64, 128, 64> Cfg3;   // projection: twice the gradient bytes per stage
+typedef Cfg<256, 256, 128, 64, 64> Cfg4;   // eight wavefronts
 
 static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
 
 // The tile table has three runs: left-side tiles for the direct-to-LDS kernel, the other left-side
 // tiles (gradients of fewer than 8 columns) and right-side tiles (register-staged kernel, one
 // instance per side).
-template <class C, bool HB>
+// CD / NST: tile configuration and ring depth of the direct-to-LDS kernel; CS: of the register-staged one.
+template <class CD, int NST, class CS, bool HB>
 static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_direct, int n_staged,
                               int n_right, const void* zero16, hipStream_t stream) {
-    constexpr int DBK = 32, NST = 3;   // as in the update: two workgroups per CU
-    constexpr int lds_dl = DlCfg<C, DBK, NST>::LDS_BYTES;
+    constexpr int DBK = 32;
+    constexpr int lds_dl = DlCfg<CD, DBK, NST>::LDS_BYTES;
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<C, HB, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16_dl<C, DBK, NST, HB>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<CS, HB, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, CS::LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16<CS, HB, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, CS::LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_project_bf16_dl<CD, DBK, NST, HB>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_dl);
         attr = true;
     }
     if (n_direct > 0)
-        hipLaunchKernelGGL((k_project_bf16_dl<C, DBK, NST, HB>), dim3(n_direct), dim3(C::NT), lds_dl, stream, mats, dyn,
-                           tiles, zero16);
+        hipLaunchKernelGGL((k_project_bf16_dl<CD, DBK, NST, HB>), dim3(n_direct), dim3(CD::NT), lds_dl, stream, mats,
+                           dyn, tiles, zero16);
     if (n_staged > 0)
-        hipLaunchKernelGGL((k_project_bf16<C, HB, false>), dim3(n_staged), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
-                           tiles + n_direct);
+        hipLaunchKernelGGL((k_project_bf16<CS, HB, false>), dim3(n_staged), dim3(CS::NT), CS::LDS_BYTES, stream, mats,
+                           dyn, tiles + n_direct);
     if (n_right > 0)
-        hipLaunchKernelGGL((k_project_bf16<C, HB, true>), dim3(n_right), dim3(C::NT), C::LDS_BYTES, stream, mats, dyn,
+        hipLaunchKernelGGL((k_project_bf16<CS, HB, true>), dim3(n_right), dim3(CS::NT), CS::LDS_BYTES, stream, mats, dyn,
                            tiles + n_direct + n_staged);
     return hipGetLastError();
 }
@@ -1001,10 +1055,11 @@ static hipError_t run_project(const MatDev* mats, const MatDyn* dyn, const TileR
 hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_direct, int n_staged,
                                int n_right, int max_r, int hist_bf16, const void* zero16, hipStream_t stream) {
     if (project_cfg(max_r) == 0)
-        return hist_bf16 ? run_project<Cfg0, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
-                         : run_project<Cfg0, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
-    return hist_bf16 ? run_project<Cfg3, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
-                     : run_project<Cfg3, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
+        return hist_bf16
+                   ? run_project<Cfg0, 3, Cfg0, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
+                   : run_project<Cfg0, 3, Cfg0, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
+    return hist_bf16 ? run_project<Cfg4, 4, Cfg2, true>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream)
+                     : run_project<Cfg4, 4, Cfg2, false>(mats, dyn, tiles, n_direct, n_staged, n_right, zero16, stream);
 }
 
 // sides: bit 0 = the layer set has left-side matrices, bit 1 = right-side ones.  Each side has its own
@@ -1033,11 +1088,19 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
     return hipGetLastError();
 }
 
-// which: 0 = projection (needs the largest rank of the layer set), 1 = update
+// which: 0 = projection, direct-to-LDS kernel; 1 = update; 2 = projection, register-staged kernel
+// (the projection's shapes depend on the largest rank of the layer set)
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
-    const bool small = which == 0 && project_cfg(max_r) == 0;
-    *bm = small ? Cfg0::BM : (which == 0 ? Cfg3::BM : Cfg2::BM);
-    *bn = small ? Cfg0::BN : (which == 0 ? Cfg3::BN : Cfg2::BN);
+    if (which == 1) {
+        *bm = Cfg2::BM;
+        *bn = Cfg2::BN;
+    } else if (project_cfg(max_r) == 0) {
+        *bm = Cfg0::BM;
+        *bn = Cfg0::BN;
+    } else {
+        *bm = which == 0 ? Cfg4::BM : Cfg2::BM;
+        *bn = which == 0 ? Cfg4::BN : Cfg2::BN;
+    }
 }
 
 }  // namespace ng

@@ -353,7 +353,7 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
     const bool big = max_m >= 128 && max_n >= 128 && max_k >= 64;
     const int ts = big ? 128 : 64;
     dim3 g((max_n + ts - 1) / ts, (max_m + ts - 1) / ts, n_mats);
-    if (big) k_gemm_f32<128, 32><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
+    if (big) k_gemm_f32<128, 16><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
     else k_gemm_f32<64, 16><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
     return hipGetLastError();
 }

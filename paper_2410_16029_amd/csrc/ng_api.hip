@@ -146,8 +146,9 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     p->sz.resize(n_mats);
     int max_r = 0;
     for (int i = 0; i < n_mats; ++i) max_r = d[i].r > max_r ? d[i].r : max_r;
-    int pbm = 128, pbn = 128, ubm = 128, ubn = 128;
+    int pbm = 128, pbn = 128, sbm = 128, sbn = 128, ubm = 128, ubn = 128;
     bf16_tile_shape(0, max_r, &pbm, &pbn);
+    bf16_tile_shape(2, max_r, &sbm, &sbn);
     bf16_tile_shape(1, max_r, &ubm, &ubn);
     std::vector<TileRef> proj_direct, proj_staged, proj_right, upd;
     p->dots.clear();
@@ -156,13 +157,11 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         derive(d[i], hp, &p->sz[i]);
         const Sizes& z = p->sz[i];
         if (hp.grad_dtype == NG_BF16) {
-            const int n_eff = effective(d[i]).n;
-            for (int tj = 0; tj < ceil_div(z.ldn, pbn); ++tj) {
-                std::vector<TileRef>& run = d[i].side == NG_SIDE_RIGHT      ? proj_right
-                                            : projection_tile_direct(n_eff) ? proj_direct
-                                                                            : proj_staged;
-                for (int ti = 0; ti < ceil_div(d[i].r, pbm); ++ti) run.push_back(TileRef{i, ti, tj, 0});
-            }
+            const bool direct = d[i].side != NG_SIDE_RIGHT && projection_tile_direct(effective(d[i]).n);
+            std::vector<TileRef>& run = direct ? proj_direct : d[i].side == NG_SIDE_RIGHT ? proj_right : proj_staged;
+            const int bm = direct ? pbm : sbm, bn = direct ? pbn : sbn;
+            for (int tj = 0; tj < ceil_div(z.ldn, bn); ++tj)
+                for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) run.push_back(TileRef{i, ti, tj, 0});
             // update tiles cover the weight in the caller's orientation on either side
             for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
                 for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});

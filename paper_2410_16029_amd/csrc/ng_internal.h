@@ -138,7 +138,8 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
                            hipStream_t stream);
 
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
-void bf16_tile_shape(int which, int max_r, int* bm, int* bn);   // which: 0 projection, 1 update
+// which: 0 projection (direct-to-LDS kernel), 1 update, 2 projection (register-staged kernel)
+void bf16_tile_shape(int which, int max_r, int* bm, int* bn);
 // zero16: 16 bytes of zeros in device memory (fetched in place of out-of-range operand chunks)
 // The projection's tile table has three runs, each with its own kernel: n_direct left-side tiles for
 // the direct-to-LDS kernel (see projection_tile_direct), then n_staged other left-side tiles, then

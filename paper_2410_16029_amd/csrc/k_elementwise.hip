@@ -474,8 +474,10 @@ hipError_t launch_transform_adam(const MatDev* mats, const MatDyn* dyn, const Ti
 }
 
 // ------------------------------------------------------------------ bf16 copies of P
-// Pb[i][rho] = bf16(P[i][rho]) (zero for r <= rho < ldr), PbT[rho][i] = bf16(P[i][rho])
-// (zero for m <= i < ldk).  32 x 32 tiles through LDS so both writes are row-contiguous.
+// Both copies are k-blocked, [k / 32][rows][32] with the contraction index k split into blocks of 32:
+//   Pb  (rows = i < m,   k = rho < ldr): Pb[((rho / 32) * m + i) * 32 + rho % 32] = bf16(P[i][rho]), zero for rho >= r
+//   PbT (rows = rho < r, k = i < ldk):   PbT[((i / 32) * r + rho) * 32 + i % 32]  = bf16(P[i][rho]), zero for i >= m
+// One workgroup converts a 32 x 32 tile through LDS: both writes are 2 KB of consecutive memory.
 __global__ __launch_bounds__(256) void k_make_bf16_copies(const MatDev* __restrict__ mats) {
     __shared__ float tile[32][33];
     const MatDev& md = mats[blockIdx.z];
@@ -487,12 +489,12 @@ __global__ __launch_bounds__(256) void k_make_bf16_copies(const MatDev* __restri
         float v = 0.f;
         if (i < md.m && rho < md.r) v = md.P[(long long)i * md.r + rho];
         tile[yy][tx] = v;
-        if (i < md.m && rho < md.ldr) md.Pb[(long long)i * md.ldr + rho] = f32_to_bf16_rne(v);
+        if (i < md.m) md.Pb[((long long)(r0 >> 5) * md.m + i) * 32 + tx] = f32_to_bf16_rne(v);
     }
     __syncthreads();
     for (int yy = ty; yy < 32; yy += 8) {
-        const int rho = r0 + yy, i = i0 + tx;
-        if (rho < md.r && i < md.ldk) md.PbT[(long long)rho * md.ldk + i] = f32_to_bf16_rne(tile[tx][yy]);
+        const int rho = r0 + yy;
+        if (rho < md.r) md.PbT[((long long)(i0 >> 5) * md.r + rho) * 32 + tx] = f32_to_bf16_rne(tile[tx][yy]);
     }
 }
 

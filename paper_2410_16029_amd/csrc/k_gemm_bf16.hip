@@ -79,34 +79,38 @@ struct Cfg {
 };
 
 // ------------------------------------------------------------------ A operand
-// bf16 [rows][ld], contraction contiguous.  Chunk c = t + NT*p: row c / KC, k-chunk c % KC
-// (the same k-chunk for every p).  Rows >= row_lim and k >= k_lim are zero (k_lim % 8 == 0).
+// bf16 copy of P^T in the k-blocked layout [k / 32][rows][32] (see MatDev::PbT): element (row, k) at
+// ((k / 32) * rows + row) * 32 + k % 32.  Chunk c = t + NT*p: row c / KC, k-chunk c % KC (the same
+// k-chunk for every p).  Rows >= row_lim and k >= k_lim are zero (k_lim % 32 == 0).
 template <class C>
 struct ALoader {
     gbf16_cptr base;
     unsigned rowoff[C::A_CHUNKS];
     unsigned rowok;    // bit p
+    unsigned blk;      // elements per 32-deep k-block = rows * 32
     int kofs, k_lim;
     u32x4_t r[C::A_CHUNKS];
     bool kok;
 
-    __device__ __forceinline__ void init(const bf16_t* A, int ld, int row0, int row_lim, int k_lim_, int t) {
+    __device__ __forceinline__ void init(const bf16_t* A, int rows, int row0, int k_lim_, int t) {
         base = (gbf16_cptr)A;
         kofs = (t % C::KC) * 8;
         k_lim = k_lim_;
+        blk = (unsigned)rows * 32u;
         rowok = 0;
 #pragma unroll
         for (int p = 0; p < C::A_CHUNKS; ++p) {
             const int row = row0 + (t + C::NT * p) / C::KC;
-            const bool ok = row < row_lim;
+            const bool ok = row < rows;
             rowok |= ok ? (1u << p) : 0u;
-            rowoff[p] = (unsigned)(ok ? row : row_lim - 1) * (unsigned)ld;
+            rowoff[p] = (unsigned)(ok ? row : rows - 1) * 32u;
         }
     }
     __device__ __forceinline__ void load(int k0) {
         const int k = k0 + kofs;
         kok = k < k_lim;
-        const unsigned kc = (unsigned)(kok ? k : k_lim - 8);
+        const unsigned kk = (unsigned)(kok ? k : k_lim - 8);
+        const unsigned kc = (kk >> 5) * blk + (kk & 31u);
 #pragma unroll
         for (int p = 0; p < C::A_CHUNKS; ++p) r[p] = *(const NG_AS1 u32x4_t*)(base + (rowoff[p] + kc));
     }
@@ -458,7 +462,7 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16(const MatDev* __restrict
     zero_acc<C>(acc);
 
     ALoader<C> la;
-    la.init(md.PbT, md.ldk, i0, r, md.ldk, t);
+    la.init(md.PbT, r, i0, md.ldk, t);
     const int nk = (m + C::BK - 1) / C::BK;
     if (!RIGHT) {
         BTLoader<C> lb;
@@ -616,42 +620,48 @@ __device__ __forceinline__ void wait_vmcnt() {   // at most N vector-memory load
 }
 
 // One operand of the update as a source of 16-byte chunks, R tile rows (of A) or columns (of B):
-//   RowMajorSrc: bf16 [rows][ldr], contraction contiguous (Pb).  A wave-instruction covers 64 / KC
-//                rows; chunk kc of a row sits at slot row * KC + (kc ^ swz(row)).
+//   RowMajorSrc: the k-blocked bf16 layout [k / 32][rows][32] of Pb / PbT: the 64 bytes a row gives to
+//                one 32-deep stage lie next to those of the neighbouring rows, so a wave-instruction
+//                (64 / KC rows) reads 1 KB of consecutive memory; chunk kc of a row sits at LDS slot
+//                row * KC + (kc ^ swz(row)).
 //   OctetSrc:    the octet layout [r/8][ldn][8] of N.  A wave-instruction covers 64 consecutive
 //                rows of one octet; slot kc * R + row.
 template <class C, int DBK, int R>
 struct RowMajorSrc {
     static constexpr int KC = DBK / 8, INSTR = R * KC / C::NT, RPI = 64 / KC;
+    static_assert(DBK == 32, "one 32-deep k-block of the blocked layout per stage");
     const NG_AS1 unsigned char* ptr[INSTR];
     unsigned ok;
-    int kc, ldr;
-    __device__ __forceinline__ void init(const bf16_t* base, int ldr_, int row0, int row_lim, int lane, int wv) {
+    int kc, k_lim;
+    long long step;   // bytes from one k-block to the next
+    // base: [k_lim / 32][rows][32] bf16; the tile takes rows row0 .. row0 + R - 1
+    __device__ __forceinline__ void init(const bf16_t* base, int rows, int k_lim_, int row0, int lane, int wv) {
         const int lrow = lane / KC;
-        kc = KC == 8 ? ((lane & 7) ^ (lrow & 7)) : ((lane & 3) ^ ((lrow >> 2) & 3));
-        ldr = ldr_;
+        kc = (lane & 3) ^ ((lrow >> 2) & 3);
+        k_lim = k_lim_;
+        step = (long long)rows * 64;
         ok = 0;
 #pragma unroll
         for (int p = 0; p < INSTR; ++p) {
             const int row = row0 + (p * C::NW + wv) * RPI + lrow;
-            const bool in = row < row_lim;
+            const bool in = row < rows;
             ok |= in ? (1u << p) : 0u;
-            ptr[p] = (const NG_AS1 unsigned char*)base + ((long long)(in ? row : 0) * ldr + kc * 8) * 2;
+            ptr[p] = (const NG_AS1 unsigned char*)base + ((long long)(in ? row : 0) * 32 + kc * 8) * 2;
         }
     }
     __device__ __forceinline__ void issue(int kt, unsigned char* stage, const NG_AS1 unsigned char* zp, int wv) const {
-        const bool kok = kt * DBK + kc * 8 < ldr;
+        const bool kok = kt * DBK + kc * 8 < k_lim;
 #pragma unroll
         for (int p = 0; p < INSTR; ++p) {
             const bool in = kok && ((ok >> p) & 1u);
-            const NG_AS1 unsigned char* g = in ? ptr[p] + (long long)kt * (DBK * 2) : zp;
+            const NG_AS1 unsigned char* g = in ? ptr[p] + kt * step : zp;
             __builtin_amdgcn_global_load_lds((const NG_AS1 void*)g, (NG_AS3 void*)(stage + (p * C::NW + wv) * 1024), 16,
                                              0, 0);
         }
     }
     // byte offset of the fragment (tile row `row`, k-slot ks) inside the operand's stage
     static __device__ __forceinline__ int frag(int row, int sw, int ks) { return (row * KC + (ks ^ sw)) * 16; }
-    static __device__ __forceinline__ int swz(int li) { return KC == 8 ? (li & 7) : ((li >> 2) & 3); }
+    static __device__ __forceinline__ int swz(int li) { return (li >> 2) & 3; }
 };
 
 template <class C, int DBK, int R>
@@ -724,11 +734,11 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restri
     BRows b_rm;
     BOct b_oc;
     if (!RIGHT) {
-        a_rm.init(md.Pb, md.ldr, i0, m, lane, wv);
+        a_rm.init(md.Pb, m, md.ldr, i0, lane, wv);
         b_oc.init(md.N, md.ldn, md.roct, j0, lane, wv);
     } else {
         a_oc.init(md.N, md.ldn, md.roct, i0, lane, wv);
-        b_rm.init(md.Pb, md.ldr, j0, n, lane, wv);
+        b_rm.init(md.Pb, n, md.ldr, j0, lane, wv);
     }
     auto issue = [&](int kt) {
         unsigned char* stage = smem + (kt % NST) * D::STAGE;
@@ -898,7 +908,7 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
     const NG_AS1 unsigned char* zp = (const NG_AS1 unsigned char*)zero16;
     ARows a_rm;
     BGrad b_g;
-    a_rm.init(md.PbT, md.ldk, i0, md.r, lane, wv);
+    a_rm.init(md.PbT, md.r, md.ldk, i0, lane, wv);
     b_g.init(dy.g, md.ld_g, md.m, md.n, j0, lane, wv, md.tail8, zp);
     auto issue = [&](int kt) {
         unsigned char* stage = smem + (kt % NST) * D::STAGE;
@@ -1013,10 +1023,13 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
 }
 
 // =================================================================== launchers
-// Tile configurations: 256 x 128 workgroup tiles (128 x 64 per wavefront); the projection falls
-// back to 128 x 128 when the rank is at most 128 (a 256-row tile would be half empty).
+// Tile configurations (BM x BN workgroup tile, WM x WN per wavefront).  Update: Cfg3 -- the weight tile
+// has 512-byte rows and the operand with 64-byte chunks per row (Pb) is the smaller one.  Projection:
+// Cfg4 for the direct-to-LDS kernel, Cfg2 for the register-staged one, Cfg0 for both when the rank is at
+// most 128 (a 256-row tile would be half empty).
 typedef Cfg<128, 128, 64, 64, 64> Cfg0;
 typedef Cfg<256, 128, 128, 64, 64> Cfg2;
+typedef Cfg<128, 256, 64, 128, 64> Cfg3;
 typedef Cfg<256, 256, 128, 64, 64> Cfg4;   // eight wavefronts
 
 static int project_cfg(int max_r) { return max_r > 128 ? 2 : 0; }
@@ -1068,7 +1081,7 @@ hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const Tile
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, const void* zero16, int sides, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    typedef Cfg2 C;
+    typedef Cfg3 C;
     constexpr int DBK = 32, NST = 3;   // 72 KiB of LDS: two workgroups per CU
     constexpr int lds = DlCfg<C, DBK, NST>::LDS_BYTES;
     static bool attr = false;
@@ -1092,8 +1105,8 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
 // (the projection's shapes depend on the largest rank of the layer set)
 void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
     if (which == 1) {
-        *bm = Cfg2::BM;
-        *bn = Cfg2::BN;
+        *bm = Cfg3::BM;
+        *bn = Cfg3::BN;
     } else if (project_cfg(max_r) == 0) {
         *bm = Cfg0::BM;
         *bn = Cfg0::BN;

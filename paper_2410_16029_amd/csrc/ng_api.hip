@@ -80,8 +80,8 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
     if (l > d.m) l = d.m;
     if (l > d.n) l = d.n;
     z->l = l;
-    z->ldk = (int)align_up((size_t)d.m, 8);
-    z->ldr = (int)align_up((size_t)d.r, 8);
+    z->ldk = (int)align_up((size_t)d.m, 32);
+    z->ldr = (int)align_up((size_t)d.r, 32);
     z->roct = ceil_div(d.r, 8);
     int jb = 16;
     for (; jb > 4; jb >>= 1) {

@@ -25,8 +25,8 @@ struct MatDev {
     int m, n, r, ldn;
     int side;
     int l;            // refresh sketch width
-    int ldk;          // row length of PbT (m rounded up to 8)
-    int ldr;          // row length of Pb (r rounded up to 8)
+    int ldk;          // contraction length of PbT (m rounded up to 32)
+    int ldr;          // contraction length of Pb (r rounded up to 32)
     int roct;         // ceil(r/8): octets of N in the bf16 layout
     long long ld_w, ld_g;
     long long slot_elems;   // r * ldn
@@ -38,8 +38,10 @@ struct MatDev {
     double* w64;      // s
     float* w32;       // s
     void* N;
-    bf16_t* Pb;       // [m][ldr]   bf16 copy of P      (A operand of the update GEMM)
-    bf16_t* PbT;      // [r][ldk]   bf16 copy of P^T    (A operand of the projection GEMM)
+    bf16_t* Pb;       // [ldr/32][m][32]  bf16 copy of P,   k-blocked: (i, rho) at ((rho/32) m + i) 32 + rho%32
+    bf16_t* PbT;      // [ldk/32][r][32]  bf16 copy of P^T, k-blocked: (rho, i) at ((i/32) r + rho) 32 + i%32
+                      // (operands of the update / projection GEMMs: the 64 bytes one row gives to a 32-deep
+                      // stage lie next to its neighbours', so a tile's stage is one run of whole cache lines)
     double* dot_parts;   // [kDotPartsMax][s]
     int dot_nparts;      // workgroups of the Gram-row reduction for this matrix
     int dot_iters;       // grid-stride iterations per workgroup

@@ -5,7 +5,8 @@
 // strided views A(i,k), B(k,j) so one kernel covers all transpositions; an
 // operand may be stored as float or bf16 (gradients).
 //
-// Tile 128 x 128 per workgroup (4 wavefronts of 64 x 64), BK = 16.
+// Tile 128 x 128 per workgroup (4 wavefronts of 64 x 64), BK = 16, two LDS tile buffers (one barrier
+// per k-step) and two register sets (a tile's loads are issued two k-steps ahead).
 // MFMA 32x32x2 f32 operand layout: lane L supplies A[i = L%32][k = L/32] and
 // B[k = L/32][j = L%32]; the 16 accumulators of lane L are
 // D[8*g + 4*(L/32) + e][L%32], index 4*g + e.
@@ -194,22 +195,38 @@ __device__ __forceinline__ f32x4_t load_vec4(const NG_AS1 void* p, long long bas
     return o;
 }
 
+// Four consecutive operand elements (float or bf16) from a byte address, as floats.
+template <bool BF>
+__device__ __forceinline__ f32x4_t load4(const NG_AS1 unsigned char* p) {
+    if (BF) {
+        const u16x4_t u = *reinterpret_cast<const NG_AS1 u16x4_a2*>(p);
+        f32x4_t o;
+        o.x = __uint_as_float((unsigned int)u.x << 16);
+        o.y = __uint_as_float((unsigned int)u.y << 16);
+        o.z = __uint_as_float((unsigned int)u.z << 16);
+        o.w = __uint_as_float((unsigned int)u.w << 16);
+        return o;
+    }
+    return *reinterpret_cast<const NG_AS1 f32x4_a4*>(p);
+}
+
 // Tile TS x TS per workgroup (128: four wavefronts of 64 x 64 = 2 x 2 MFMA blocks of 32 x 32; 64: one
 // block per wavefront, for products with a short side or a short contraction), BK = 16.  Each
 // thread moves 4-element vectors per operand and k-step, taken along the operand's contiguous
 // dimension (tile index or contraction index, whichever has stride 1).
-template <int TS, int BK>
+// ABF / BBF: operand A / B is stored as bf16.  zero16: 16 bytes of zeros in device memory.
+template <int TS, int BK, bool ABF, bool BBF>
 __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn, int grad_dtype,
-                                                  StepScalars sc) {
+                                                  StepScalars sc, const void* zero16) {
     constexpr int LDT = TS + 4;
     constexpr int NB = TS / 64;          // 32 x 32 blocks per wavefront and dimension
     constexpr int NV = TS * BK / 1024;   // vectors per thread, operand and k-step
     constexpr int KT = BK / 4;           // threads along the contraction index (k-fast mapping)
     constexpr int RPP = 256 / KT;        // tile rows per pass of the k-fast mapping
     constexpr int TPR = TS / 4;          // threads along the tile index (tile-fast mapping)
-    __shared__ __attribute__((aligned(16))) float As[BK][LDT];
-    __shared__ __attribute__((aligned(16))) float Bs[BK][LDT];
+    __shared__ __attribute__((aligned(16))) float Asm[2][BK][LDT];   // two tile buffers: one barrier per k-step
+    __shared__ __attribute__((aligned(16))) float Bsm[2][BK][LDT];
     const MatDev& md = mats[blockIdx.z];
     const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype, sc.slot, sc.hist_bf16);
     const int i0 = blockIdx.y * TS, j0 = blockIdx.x * TS;
@@ -239,27 +256,84 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
 #pragma unroll
             for (int x = 0; x < 16; ++x) acc[a][b][x] = 0.f;
 
-    f32x4_t ra[NV], rb[NV];
-    auto fetch = [&](int k0) {
+    // Per-thread, per-vector state of the loads, fixed over the contraction: byte offset in k-step 0,
+    // whether the vector lies wholly inside the operand along the dimension that does not move
+    // (whole), or straddles its end there (part, tile-fast only).  Inside the loop a whole vector is
+    // one load from its address (or from the block of zeros once k runs out); only vectors that
+    // straddle an operand's end take the element-wise path.
+    const NG_AS1 unsigned char* zp = (const NG_AS1 unsigned char*)zero16;
+    constexpr int AES = ABF ? 2 : 4, BES = BBF ? 2 : 4;
+    long long a_off[NV], b_off[NV];
+    unsigned a_whole = 0, a_part = 0, b_whole = 0, b_part = 0;   // bit q
+    const long long a_step = (a_i_fast ? (long long)BK * v.sAk : (long long)BK) * AES;
+    const long long b_step = (b_j_fast ? (long long)BK * v.sBk : (long long)BK) * BES;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        if (a_i_fast) {
+            const int i = i0 + tf;
+            a_whole |= (i + 4 <= v.M) ? (1u << q) : 0u;
+            a_part |= (i < v.M && i + 4 > v.M) ? (1u << q) : 0u;
+            a_off[q] = ((long long)i + (long long)(tk + KSTEP * q) * v.sAk) * AES;
+        } else {
+            const int i = i0 + kt_ + RPP * q;
+            a_whole |= (i < v.M) ? (1u << q) : 0u;
+            a_off[q] = ((long long)i * v.sAi + kf) * AES;
+        }
+        if (b_j_fast) {
+            const int j = j0 + tf;
+            b_whole |= (j + 4 <= v.Nvalid) ? (1u << q) : 0u;
+            b_part |= (j < v.Nvalid && j + 4 > v.Nvalid) ? (1u << q) : 0u;
+            b_off[q] = ((long long)(tk + KSTEP * q) * v.sBk + (long long)j) * BES;
+        } else {
+            const int j = j0 + kt_ + RPP * q;
+            b_whole |= (j < v.Nvalid) ? (1u << q) : 0u;
+            b_off[q] = ((long long)kf + (long long)j * v.sBj) * BES;
+        }
+    }
+    // Two register sets: a tile's loads are issued two k-steps before it is written to LDS (one step
+    // ahead is not enough for operands that stream from HBM).
+    f32x4_t ra0[NV], rb0[NV], ra1[NV], rb1[NV];
+    auto fetch = [&](int kt, f32x4_t (&ra)[NV], f32x4_t (&rb)[NV]) {
+        const int k0 = kt * BK;
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
-            if (a_i_fast) {
-                const int i = i0 + tf, k = k0 + tk + KSTEP * q;
-                ra[q] = load_vec4(Ap, (long long)i + (long long)k * v.sAk, i, v.M, k < v.K, v.a_bf16);
-            } else {
-                const int i = i0 + kt_ + RPP * q, k = k0 + kf;
-                ra[q] = load_vec4(Ap, (long long)i * v.sAi + (long long)k, k, v.K, i < v.M, v.a_bf16);
+            {
+                const int k = a_i_fast ? k0 + tk + KSTEP * q : k0 + kf;
+                const bool w = (a_whole >> q) & 1u;
+                const bool ok = w && (a_i_fast ? k < v.K : k + 4 <= v.K);
+                const bool part = a_i_fast ? (((a_part >> q) & 1u) && k < v.K) : (w && k < v.K && k + 4 > v.K);
+                ra[q] = load4<ABF>(ok ? (const NG_AS1 unsigned char*)Ap + (a_off[q] + kt * a_step) : zp);
+                if (part) {
+                    if (a_i_fast) {
+                        const int i = i0 + tf;
+                        ra[q] = load_vec4(Ap, (long long)i + (long long)k * v.sAk, i, v.M, true, ABF);
+                    } else {
+                        const int i = i0 + kt_ + RPP * q;
+                        ra[q] = load_vec4(Ap, (long long)i * v.sAi + (long long)k, k, v.K, true, ABF);
+                    }
+                }
             }
-            if (b_j_fast) {
-                const int j = j0 + tf, k = k0 + tk + KSTEP * q;
-                rb[q] = load_vec4(Bp, (long long)k * v.sBk + (long long)j, j, v.Nvalid, k < v.K, v.b_bf16);
-            } else {
-                const int j = j0 + kt_ + RPP * q, k = k0 + kf;
-                rb[q] = load_vec4(Bp, (long long)k + (long long)j * v.sBj, k, v.K, j < v.Nvalid, v.b_bf16);
+            {
+                const int k = b_j_fast ? k0 + tk + KSTEP * q : k0 + kf;
+                const bool w = (b_whole >> q) & 1u;
+                const bool ok = w && (b_j_fast ? k < v.K : k + 4 <= v.K);
+                const bool part = b_j_fast ? (((b_part >> q) & 1u) && k < v.K) : (w && k < v.K && k + 4 > v.K);
+                rb[q] = load4<BBF>(ok ? (const NG_AS1 unsigned char*)Bp + (b_off[q] + kt * b_step) : zp);
+                if (part) {
+                    if (b_j_fast) {
+                        const int j = j0 + tf;
+                        rb[q] = load_vec4(Bp, (long long)k * v.sBk + (long long)j, j, v.Nvalid, true, BBF);
+                    } else {
+                        const int j = j0 + kt_ + RPP * q;
+                        rb[q] = load_vec4(Bp, (long long)k + (long long)j * v.sBj, k, v.K, true, BBF);
+                    }
+                }
             }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](const f32x4_t (&ra)[NV], const f32x4_t (&rb)[NV], int buf) {
+        float (*As)[LDT] = Asm[buf];
+        float (*Bs)[LDT] = Bsm[buf];
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             if (a_i_fast) {
@@ -289,13 +363,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
         vx[x] = i0 + wm * (TS / 2) + 32 * x < v.M;
         vy[x] = j0 + wn * (TS / 2) + 32 * x < v.N;
     }
-
-    const int nk = (v.K + BK - 1) / BK;
-    fetch(0);
-    stage();
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) fetch((kt + 1) * BK);
+    auto multiply = [&](int buf) {
+        const float (*As)[LDT] = Asm[buf];
+        const float (*Bs)[LDT] = Bsm[buf];
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float a[NB], b[NB];
@@ -311,8 +381,26 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
                     if (vx[x] && vy[y])
                         acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
         }
+    };
+
+    // Iteration kt: tile kt + 1 goes from its register set into the LDS buffer that tile kt - 1 was read
+    // from (everyone has passed the barrier that ended that step), the set is refilled with the loads
+    // of tile kt + 3, tile kt is multiplied, one barrier.
+    const int nk = (v.K + BK - 1) / BK;
+    fetch(0, ra0, rb0);
+    stage(ra0, rb0, 0);
+    if (nk > 1) fetch(1, ra1, rb1);
+    if (nk > 2) fetch(2, ra0, rb0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+        if (kt + 1 < nk) stage(ra1, rb1, 1);
+        if (kt + 3 < nk) fetch(kt + 3, ra1, rb1);
+        multiply(0);
         __syncthreads();
-        if (kt + 1 < nk) stage();
+        if (kt + 1 >= nk) break;
+        if (kt + 2 < nk) stage(ra0, rb0, 0);
+        if (kt + 4 < nk) fetch(kt + 4, ra0, rb0);
+        multiply(1);
         __syncthreads();
     }
 
@@ -348,13 +436,27 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
 // max_m, max_n, max_k: the largest dimensions of this product over the layer set.  The 128 tile is used
 // when neither side nor the contraction is short (a short side wastes most of a big tile, a short
 // contraction leaves only the read-modify-write of the output, which wants many small workgroups).
+template <int TS, int BK>
+static void run_gemm_f32(dim3 g, int op, const MatDev* mats, const MatDyn* dyn, int grad_dtype, StepScalars sc,
+                         const void* zero16, bool a_bf16, bool b_bf16, hipStream_t stream) {
+    if (a_bf16)
+        k_gemm_f32<TS, BK, true, false><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+    else if (b_bf16)
+        k_gemm_f32<TS, BK, false, true><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+    else
+        k_gemm_f32<TS, BK, false, false><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+}
+
 hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m, int max_n,
-                           int max_k, int grad_dtype, StepScalars sc, hipStream_t stream) {
+                           int max_k, int grad_dtype, StepScalars sc, const void* zero16, hipStream_t stream) {
     const bool big = max_m >= 128 && max_n >= 128 && max_k >= 64;
     const int ts = big ? 128 : 64;
     dim3 g((max_n + ts - 1) / ts, (max_m + ts - 1) / ts, n_mats);
-    if (big) k_gemm_f32<128, 16><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
-    else k_gemm_f32<64, 16><<<g, dim3(256), 0, stream>>>((int)op, mats, dyn, grad_dtype, sc);
+    // which operand is stored as bf16 is a property of the product (the same for every matrix)
+    const MatDev probe{};
+    const GemmView v = gemm_view((int)op, probe, nullptr, grad_dtype, sc.slot, sc.hist_bf16);
+    if (big) run_gemm_f32<128, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, stream);
+    else run_gemm_f32<64, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, stream);
     return hipGetLastError();
 }
 

@@ -300,7 +300,7 @@ int clear_history(ng_state* st, hipStream_t stream) {
 
 int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
     NG_HIP(launch_gemm_f32(op, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], st->max_tk[op],
-                           st->hp.grad_dtype, sc, stream));
+                           st->hp.grad_dtype, sc, (const char*)st->d_status + 64, stream));
     return NG_OK;
 }
 

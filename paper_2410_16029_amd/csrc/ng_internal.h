@@ -137,7 +137,7 @@ void gemm_f32_dims(int op, const MatDev& md, int* M, int* N, int* K);
 // max_m, max_n, max_k: largest dimensions of the product over the layer set (grid and tile choice)
 hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats,
                            int max_m, int max_n, int max_k, int grad_dtype, StepScalars sc,
-                           hipStream_t stream);
+                           const void* zero16, hipStream_t stream);
 
 // bf16 MFMA GEMMs of the step (k_gemm_bf16.hip)
 // which: 0 projection (direct-to-LDS kernel), 1 update, 2 projection (register-staged kernel)

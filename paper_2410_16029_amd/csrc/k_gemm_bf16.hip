@@ -1,33 +1,38 @@
 // bf16 MFMA GEMMs of the Natural GaLore step for bf16 gradients / weights.
 //
-//   k_project_bf16   R = P^T G        (paper Sec. 1, projection equation)
-//                    A = PbT [r][ldk] (bf16 copy of P^T, contraction index contiguous)
-//                    B = G   [m][ld_g] (caller's gradient: contraction index is the ROW, so the tile
-//                                       is transposed in registers on its way into LDS; on the right
-//                                       side the problem is transposed and the gradient's rows are
-//                                       contraction-contiguous columns: no transpose)
+//   k_project_bf16_dl  R = P^T G      (paper Sec. 1, projection equation), left side
+//                    A = PbT (bf16 copy of P^T, k-blocked [ldk/32][r][32]), B = the caller's gradient
+//                    G [m][ld_g] (contraction index = row).  16-byte chunks of both go from memory
+//                    straight into LDS; the gradient's MFMA fragments (8 consecutive k of one
+//                    column) are assembled by transposing LDS reads.
 //                    C -> ring slot `head` of H, float or bf16 [r][ldn]
+//   k_project_bf16   the same product with register-staged operands: the right side (the problem is
+//                    transposed and the gradient's rows are contraction-contiguous columns) and
+//                    left-side gradients of fewer than 8 columns (tile transposed in registers)
 //   k_update_bf16_dl W <- W - lr (scale P N + wd W)   (paper Sec. 2.2, update equation)
-//                    A = Pb [m][ldr], B = N in the octet layout [r/8][ldn][8] written by the
-//                    transform+Adam kernel (both k-packed: 16-byte chunks go from memory straight
-//                    into LDS, no register pass), epilogue read-modify-writes W through an
-//                    LDS-staged tile so every lane touches 16 contiguous bytes of a weight row.
+//                    A = Pb (k-blocked [ldr/32][m][32]), B = N in the octet layout [r/8][ldn][8]
+//                    written by the transform+Adam kernel (both k-packed: 16-byte chunks go from
+//                    memory straight into LDS, no register pass), epilogue read-modify-writes W
+//                    through an LDS-staged tile so every lane touches 16 contiguous bytes of a
+//                    weight row.
 //
 // v_mfma_f32_32x32x16_bf16: lane L supplies 8 bf16 of A row (L%32) and 8 bf16 of B column (L%32),
 // both for the k-slots 8*(L/32)..+7 of the 16-deep step (any k assignment works as long as A and B
 // agree); accumulator index 4*g+e of lane L is D[8*g + 4*(L/32) + e][L%32].
 //
-// LDS tiles of the projection are [row][BK + 8] bf16: the 16-byte pad makes the 16-byte fragment
-// reads of 16 consecutive rows hit disjoint banks.
+// LDS tiles of the register-staged projection are [row][BK + 8] bf16: the 16-byte pad makes the
+// 16-byte fragment reads of 16 consecutive rows hit disjoint banks.
 //
 // Memory access rules followed here (each was measured to matter):
 //   * every pointer read out of a table is cast to the global address space, so loads are
 //     global_load (not flat_load, which also ticks the LDS counter);
 //   * loads are branch-free: an out-of-range row / k / column is clamped to a valid address and
-//     the value is zeroed later, when it is written to LDS -- a guarded load in its own branch,
+//     the value is zeroed later, when it is written to LDS (register-staged kernel), or fetched
+//     from a 16-byte block of zeros (direct-to-LDS kernels) -- a guarded load in its own branch,
 //     or a select right after the load, makes the compiler wait for the load before the MFMAs
 //     of the current tile instead of after them;
-//   * offsets are 32-bit (the host checks that every matrix is below 2 GiB).
+//   * offsets are 32-bit in the register-staged kernel (the host checks that every matrix is
+//     below 2 GiB).
 #include "ng_internal.h"
 
 namespace ng {

@@ -219,18 +219,21 @@ def test_full_1b_layer_set_sampled():
         assert ls.counters(i) == (2, 2, 2, 1)
 
 
+@pytest.mark.parametrize("rank_cap", [None, 16, 8])
 @pytest.mark.parametrize("pad_g", [0, 3])
 @pytest.mark.parametrize("hist", ["f32", "bf16"])
-def test_bf16_projection_slot_small_and_ragged(hist, pad_g):
+def test_bf16_projection_slot_small_and_ragged(hist, pad_g, rank_cap):
     """The bf16 projection alone, against the oracle's R = P^T G on the projector the library holds
     (rounded to bf16, as the kernel's operand is), at shapes where single rows and columns matter:
     few contraction rows (the last row's share of the columns beyond the last whole 8-column chunk is
-    added separately), column counts that are not multiples of 8, and gradients that are column
+    taken from a padded copy), column counts that are not multiples of 8, and gradients that are column
     slices of wider tensors whose other columns hold NaN.  The slot's columns n..ldn-1 must be zero."""
     import oracle.natural_galore as ONG
 
     shapes = [(9, 13), (24, 45), (40, 8), (16, 7), (33, 300), (70, 261), (2, 9), (1, 12)]
     ranks = [4, 8, 8, 5, 16, 33, 2, 1]
+    if rank_cap:   # every rank at most 16 / 8: the fine-tuning regime (row tiles almost empty)
+        ranks = [min(r, rank_cap) for r in ranks]
     gen = torch.Generator(device="cpu").manual_seed(77)
     G, Gfull = [], []
     for (m, n) in shapes:

@@ -96,7 +96,8 @@ typedef struct ng_hparams {
     int32_t grad_dtype;      /* NG_F32 | NG_BF16                                                   */
     int32_t adam_mode;       /* NG_ADAM_STANDARD | NG_ADAM_PRINTED                                 */
     int32_t refresh_power_iters;  /* subspace-iteration passes q >= 0 of the refresh               */
-    int32_t refresh_oversample;   /* extra sketch columns p >= 0; sketch width l = min(r+p, m, n)  */
+    int32_t refresh_oversample;   /* extra sketch columns p >= 0; sketch width l = min(r+p, m, n), trimmed
+                                   * to the next lower multiple of 32 when that is still >= r       */
     int32_t refresh_sweeps;       /* maximum Jacobi sweeps of the l x l eigen-solve, >= 1          */
     int32_t hist_dtype;           /* storage type of the history slots: NG_F32 (default) or NG_BF16
                                      (NG_BF16 gradients only).  bf16 slots halve the ring's memory and

@@ -79,6 +79,10 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
     int l = d.r + hp.refresh_oversample;
     if (l > d.m) l = d.m;
     if (l > d.n) l = d.n;
+    // the refresh's products and its eigen-solve work on 32-wide blocks: a sketch width just above a
+    // multiple of 32 (r = 512, p = 8) would pay for a whole block to carry a few columns, so the
+    // width is trimmed to that multiple when it still holds the r columns wanted
+    if (l / 32 * 32 >= d.r) l = l / 32 * 32;
     z->l = l;
     z->ldk = (int)align_up((size_t)d.m, 32);
     z->ldr = (int)align_up((size_t)d.r, 32);

@@ -218,7 +218,7 @@ __device__ __forceinline__ f32x4_t load4(const NG_AS1 unsigned char* p) {
 template <int TS, int BK, bool ABF, bool BBF>
 __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restrict__ mats,
                                                   const MatDyn* __restrict__ dyn, int grad_dtype,
-                                                  StepScalars sc, const void* zero16) {
+                                                  StepScalars sc, const void* zero16, int nx, int ny) {
     constexpr int LDT = TS + 4;
     constexpr int NB = TS / 64;          // 32 x 32 blocks per wavefront and dimension
     constexpr int NV = TS * BK / 1024;   // vectors per thread, operand and k-step
@@ -229,8 +229,16 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     __shared__ __attribute__((aligned(16))) float Bsm[2][BK][LDT];
     const MatDev& md = mats[blockIdx.z];
     const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype, sc.slot, sc.hist_bf16);
-    const int i0 = blockIdx.y * TS, j0 = blockIdx.x * TS;
-    if (i0 >= v.M || j0 >= v.N) return;
+    // The grid is 1-D over the tiles of the largest matrix, padded to a multiple of 8: hardware workgroup
+    // id w runs on XCD w % 8, and it takes this matrix's tile with logical index (w % 8) per + w / 8, so
+    // each XCD works through a contiguous run of the matrix's tiles (the column tiles of one row tile
+    // share the rows of A through that XCD's L2).
+    const int nxm = (v.N + TS - 1) / TS, nym = (v.M + TS - 1) / TS;   // this matrix's own tiles
+    const int per = (nxm * nym + 7) / 8;
+    const int slot = (int)(blockIdx.x / 8);
+    const int tile = (int)(blockIdx.x % 8) * per + slot;
+    if (slot >= per || tile >= nxm * nym) return;
+    const int i0 = (tile / nxm) * TS, j0 = (tile % nxm) * TS;
 
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
@@ -439,12 +447,14 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
 template <int TS, int BK>
 static void run_gemm_f32(dim3 g, int op, const MatDev* mats, const MatDyn* dyn, int grad_dtype, StepScalars sc,
                          const void* zero16, bool a_bf16, bool b_bf16, hipStream_t stream) {
+    const int nx = (int)g.x, ny = (int)g.y;
+    const dim3 g1((unsigned)((nx * ny + 7) / 8 * 8), 1, g.z);
     if (a_bf16)
-        k_gemm_f32<TS, BK, true, false><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+        k_gemm_f32<TS, BK, true, false><<<g1, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16, nx, ny);
     else if (b_bf16)
-        k_gemm_f32<TS, BK, false, true><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+        k_gemm_f32<TS, BK, false, true><<<g1, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16, nx, ny);
     else
-        k_gemm_f32<TS, BK, false, false><<<g, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16);
+        k_gemm_f32<TS, BK, false, false><<<g1, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16, nx, ny);
 }
 
 hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m, int max_n,

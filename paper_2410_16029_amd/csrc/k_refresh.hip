@@ -442,9 +442,10 @@ __global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restri
                     xb[c] = sn * va[i] + cs * vb[i];
                 }
             }
-            // only a rotation by more than ~3e-5 rad keeps the sweep loop alive: after a sweep
-            // without one, what is left is quadratically smaller, below the float the result is stored in
-            if (lane == 0 && ga * ga > 1.0e-9 * al * be) ++nrot;
+            // only a coupling above ~3e-4 of the two rows' norms keeps the sweep loop alive: after a
+            // sweep without one, what is left is quadratically smaller, ~1e-7: the rounding of the float
+            // the result is stored in
+            if (lane == 0 && ga * ga > 1.0e-7 * al * be) ++nrot;
         }
         __syncthreads();
     }
@@ -644,10 +645,11 @@ __global__ __launch_bounds__(1024) void k_jacobi_round_gram(const MatDev* __rest
             if ((al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-15 * al * be)) {
                 rotation_params(al, be, ga, &cs, &sn);
                 // a coupling below the visit's own rounding noise (entries that went through
-                // rotations with much larger rows), or a rotation by less than ~3e-5 rad (what is left
-                // after a sweep of such rotations is quadratically smaller, below the float the result
-                // is stored in), is applied but does not keep the sweep loop alive
-                if (fabs(ga) > 8.0e-15 * smax_s && ga * ga > 1.0e-9 * al * be) ++nrot;
+                // rotations with much larger rows), or one below ~3e-4 of the two rows' norms (what is
+                // left after a sweep of such rotations is quadratically smaller, ~1e-7: the rounding
+                // of the float the result is stored in), is applied but does not keep the sweep loop
+                // alive
+                if (fabs(ga) > 8.0e-15 * smax_s && ga * ga > 1.0e-7 * al * be) ++nrot;
             }
             cc[a] = cs;
             cc[b] = cs;

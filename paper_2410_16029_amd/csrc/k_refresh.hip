@@ -248,13 +248,43 @@ __global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ 
     }
     // RB rows per step: their dot products with the rows already solved run together (one pass
     // over the block, one reduction), the RB x RB triangle that couples them is resolved in order
-    for (int i0 = c0; i0 < nn; i0 += RB) {
-        const int len = i0 - c0;                   // entries L[i][c0 .. i0-1] meet solved rows
+    // The rows of L a step needs do not depend on the steps before it: they are fetched into
+    // registers one step ahead (kTriPre entries per thread and row cover orders up to 256 kTriPre)
+    // and written to LDS at the start of their step, so their L2 latency overlaps the previous step.
+    constexpr int kTriPre = 3;
+    const bool pre_ok = nn - c0 + RB <= 256 * kTriPre;
+    double nxt[RB][kTriPre];
+    auto fetch_rows = [&](int i0) {
+        const int len = i0 - c0;
 #pragma unroll
         for (int q = 0; q < RB; ++q) {
             const int i = i0 + q;
-            if (i < nn)
-                for (int p = tid; p <= len + q; p += 256) lrow[q * lrs + p] = L[(long long)i * ld + c0 + p];
+#pragma unroll
+            for (int u = 0; u < kTriPre; ++u) {
+                const int p = tid + 256 * u;
+                nxt[q][u] = (i < nn && p <= len + q) ? L[(long long)i * ld + c0 + p] : 0.0;
+            }
+        }
+    };
+    if (pre_ok) fetch_rows(c0);
+    for (int i0 = c0; i0 < nn; i0 += RB) {
+        const int len = i0 - c0;                   // entries L[i][c0 .. i0-1] meet solved rows
+        if (pre_ok) {
+#pragma unroll
+            for (int q = 0; q < RB; ++q)
+#pragma unroll
+                for (int u = 0; u < kTriPre; ++u) {
+                    const int p = tid + 256 * u;
+                    if (i0 + q < nn && p <= len + q) lrow[q * lrs + p] = nxt[q][u];
+                }
+            if (i0 + RB < nn) fetch_rows(i0 + RB);
+        } else {
+#pragma unroll
+            for (int q = 0; q < RB; ++q) {
+                const int i = i0 + q;
+                if (i < nn)
+                    for (int p = tid; p <= len + q; p += 256) lrow[q * lrs + p] = L[(long long)i * ld + c0 + p];
+            }
         }
         __syncthreads();
         double acc[RB];

@@ -176,3 +176,17 @@ def test_workspace_too_small_and_misaligned():
     rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws, B.NG_INIT_NO_CLEAR, None,
                               C.byref(st))
     assert rc == B.NG_ERR_INVALID_ARG
+
+
+def test_sketch_width_is_trimmed_to_a_multiple_of_32_when_that_keeps_r_columns():
+    # l = min(r + p, m, n), then the next lower multiple of 32 if that is still >= r
+    cases = [((256, 512), 32, 8, 32),     # 40 -> 32
+             ((256, 512), 30, 8, 32),     # 38 -> 32 (>= 30)
+             ((256, 512), 33, 8, 41),     # 41 -> 32 would drop a wanted column: kept
+             ((256, 512), 4, 8, 12),      # 12 -> 0: kept
+             ((256, 512), 64, 32, 96),    # already a multiple
+             ((40, 512), 36, 8, 40)]      # clamped to m = 40 first; 32 < 36: kept
+    for shape, r, p, want in cases:
+        ls = B.LayerSet([shape], r, s=2, dtype="f32", device="cpu", no_clear=True, oversample=p)
+        assert B.ng_get_layout(ls.st, 0).l == want, (shape, r, p)
+        ls.close()

@@ -499,9 +499,8 @@ __global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restri
 // v_mfma_f64_16x16x4_f64: lane L supplies A[L%16][L/16] and B[L/16][L%16]; element e of its result is
 // D[4e + L/16][L%16] (checked on the device).
 typedef double double4_t __attribute__((ext_vector_type(4)));
-constexpr int kJgPad = 4;      // doubles of padding per LDS row of X: 16 rows land on distinct banks
-constexpr int kJgLdS = 36;     // row length of S and V in LDS (32 + 4, same reason)
-constexpr int kJgSeg = 9;      // ceil(544 / 64): 64-column segments of a row
+constexpr int kJgLdS = 36;     // row length of S and V in LDS (32 + 4: 16 rows land on distinct banks)
+constexpr int kJgParts = 8;    // wavefronts that share the Gram product (a slice of the columns each)
 
 // cs, sn of the rotation that orthogonalises two rows with squared norms al, be and inner product ga
 // (the same angle as the row-by-row kernel).  Reciprocal and reciprocal square root start from the
@@ -545,7 +544,7 @@ struct TournamentRow {
     }
 };
 
-__global__ __launch_bounds__(1024) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
+__global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
     extern __shared__ __attribute__((aligned(16))) double smem_d[];
     __shared__ double cc[32], tt[32];
     __shared__ int nrot_s;
@@ -560,87 +559,65 @@ __global__ __launch_bounds__(1024) void k_jacobi_round_gram(const MatDev* __rest
     tournament_pair(nb, round, blockIdx.x, &bp, &bq);
     if (bp * 16 >= md.l || bq * 16 >= md.l) return;   // a block of padding rows only: nothing to rotate
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int ldx = lp + kJgPad;
-    double* xs = smem_d;                    // [32][ldx]
-    double* Ss = xs + 32 * ldx;             // [32][kJgLdS]
-    double* Vs = Ss + 32 * kJgLdS;          // [32][kJgLdS]; first the Gram partials of the second K half
+    // The 32 rows of the pair stay in global memory (they sit in the L2 between rounds): the Gram
+    // product and X <- V X take their MFMA operands straight from there, so a workgroup needs only
+    // 68 KB of LDS and 64 registers per lane, and two visits share a CU -- one multiplies or
+    // streams while the other sits in the dependent rounds of its small sweep.
+    double* part = smem_d;                          // [kJgParts][3][256] Gram partials
+    double* Ss = part + kJgParts * 768;             // [32][kJgLdS]
+    double* Vs = Ss + 32 * kJgLdS;                  // [32][kJgLdS]
     double* __restrict__ X = md.T;
-
-    // rows 2 wv, 2 wv + 1 of the pair (rows 0..15 from block bp, 16..31 from block bq); all loads of
-    // both rows are in flight together
-    {
-        double v[2][kJgSeg];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int row = 2 * wv + u;
-            const double* src = X + ((long long)(row < 16 ? bp : bq) * 16 + (row & 15)) * lp;
-#pragma unroll
-            for (int g = 0; g < kJgSeg; ++g) {
-                const int c = lane + 64 * g;
-                v[u][g] = src[c < lp ? c : lp - 1];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int g = 0; g < kJgSeg; ++g) {
-                const int c = lane + 64 * g;
-                if (c < lp) xs[(2 * wv + u) * ldx + c] = v[u][g];
-            }
-    }
+    double* __restrict__ Xp = X + (long long)bp * 16 * lp;   // rows 0..15 of the pair
+    double* __restrict__ Xq = X + (long long)bq * 16 * lp;   // rows 16..31
     if (tid == 0) nrot_s = 0;
-    __syncthreads();
 
-    // ---- Gram: wavefronts 0..3 take a quarter of the columns each and compute the tiles (0,0), (1,0),
-    // (1,1) from the same two operands per k-step; (0,1) is the transpose of (1,0).  The partials of
-    // wavefronts 1..3 go through the S / V area (3 x 768 doubles) and are added by wavefront 0.
+    // ---- Gram: wavefronts 0..7 take an eighth of the columns each and compute the tiles (0,0), (1,0),
+    // (1,1) from the same two operands per k-step; (0,1) is the transpose of (1,0).  The partials are
+    // added in a fixed order.
     const int l16 = lane & 15, lq = lane >> 4;
-    double* part = Ss;                      // [3][3][256] while the Gram is reduced
-    double4_t g00 = {0.0, 0.0, 0.0, 0.0}, g10 = {0.0, 0.0, 0.0, 0.0}, g11 = {0.0, 0.0, 0.0, 0.0};
-    if (wv < 4) {
-        const int quarter = lp / 4;            // lp % 32 == 0: quarter % 8 == 0
-        const double* p0 = xs + l16 * ldx + wv * quarter + lq;
-        const double* p1 = xs + (16 + l16) * ldx + wv * quarter + lq;
-        for (int k = 0; k < quarter; k += 8) {
-            const double x0 = p0[k], x1 = p1[k], y0 = p0[k + 4], y1 = p1[k + 4];
-            g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(x0, x0, g00, 0, 0, 0);
-            g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, x0, g10, 0, 0, 0);
-            g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, x1, g11, 0, 0, 0);
-            g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(y0, y0, g00, 0, 0, 0);
-            g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(y1, y0, g10, 0, 0, 0);
-            g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(y1, y1, g11, 0, 0, 0);
-        }
-        if (wv > 0) {
-            double* dst = part + (wv - 1) * 768;
+    if (wv < kJgParts) {
+        double4_t g00 = {0.0, 0.0, 0.0, 0.0}, g10 = {0.0, 0.0, 0.0, 0.0}, g11 = {0.0, 0.0, 0.0, 0.0};
+        const int cols = lp / kJgParts;            // lp % 32 == 0: cols % 4 == 0
+        const double* p0 = Xp + (long long)l16 * lp + wv * cols + lq;   // A[L%16][k + L/16]
+        const double* p1 = Xq + (long long)l16 * lp + wv * cols + lq;
+        for (int k = 0; k < cols; k += 16) {       // up to 4 k-steps (4 columns each) in flight
+            double x0[4], x1[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                dst[e * 64 + lane] = g00[e];
-                dst[256 + e * 64 + lane] = g10[e];
-                dst[512 + e * 64 + lane] = g11[e];
+            for (int u = 0; u < 4; ++u) {
+                const bool in = k + 4 * u < cols;
+                x0[u] = in ? p0[k + 4 * u] : 0.0;
+                x1[u] = in ? p1[k + 4 * u] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(x0[u], x0[u], g00, 0, 0, 0);
+                g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1[u], x0[u], g10, 0, 0, 0);
+                g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1[u], x1[u], g11, 0, 0, 0);
             }
         }
-    }
-    __syncthreads();
-    if (wv == 0) {
-#pragma unroll
-        for (int w = 0; w < 3; ++w)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                g00[e] += part[w * 768 + e * 64 + lane];
-                g10[e] += part[w * 768 + 256 + e * 64 + lane];
-                g11[e] += part[w * 768 + 512 + e * 64 + lane];
-            }
-    }
-    __syncthreads();
-    if (wv == 0) {
-        // element e of lane L is entry (4e + L/16, L%16) of its tile
+        double* dst = part + wv * 768;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int ii = 4 * e + lq;
-            Ss[ii * kJgLdS + l16] = g00[e];
-            Ss[(16 + ii) * kJgLdS + l16] = g10[e];
-            Ss[l16 * kJgLdS + 16 + ii] = g10[e];
-            Ss[(16 + ii) * kJgLdS + 16 + l16] = g11[e];
+            dst[e * 64 + lane] = g00[e];
+            dst[256 + e * 64 + lane] = g10[e];
+            dst[512 + e * 64 + lane] = g11[e];
+        }
+    }
+    __syncthreads();
+    if (tid < 768) {
+        double v = 0.0;
+#pragma unroll
+        for (int w = 0; w < kJgParts; ++w) v += part[w * 768 + tid];
+        // element e of lane L is entry (4e + L/16, L%16) of its tile
+        const int tile = tid >> 8, e = (tid >> 6) & 3, ln = tid & 63;
+        const int ii = 4 * e + (ln >> 4), jj = ln & 15;
+        if (tile == 0) {
+            Ss[ii * kJgLdS + jj] = v;
+        } else if (tile == 1) {
+            Ss[(16 + ii) * kJgLdS + jj] = v;
+            Ss[jj * kJgLdS + 16 + ii] = v;
+        } else {
+            Ss[(16 + ii) * kJgLdS + 16 + jj] = v;
         }
     }
     __syncthreads();
@@ -698,28 +675,25 @@ __global__ __launch_bounds__(1024) void k_jacobi_round_gram(const MatDev* __rest
 
     // ---- X <- V X: wavefront wv takes the 16-column tiles wv, wv + 16, ...; both 16-row halves
     const int nct = lp / 16;
-    double a0[8], a1[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        a0[u] = Vs[l16 * kJgLdS + 4 * u + lq];                 // A[L%16][k + L/16] = V[L%16][k + L/16]
-        a1[u] = Vs[(16 + l16) * kJgLdS + 4 * u + lq];
-    }
+    const double* va0 = Vs + l16 * kJgLdS + lq;                // A[L%16][k + L/16] = V[L%16][k + L/16], k = 4u
+    const double* va1 = Vs + (16 + l16) * kJgLdS + lq;
     for (int ct = wv; ct < nct; ct += 16) {
         const int c0 = 16 * ct;
         double bx[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) bx[u] = xs[(4 * u + lq) * ldx + c0 + l16];   // B[k + L/16][L%16] = X[k + L/16][c0 + L%16]
+        for (int u = 0; u < 8; ++u)   // B[k + L/16][L%16] = X[k + L/16][c0 + L%16], k = 4u: rows 0..15 from Xp, 16..31 from Xq
+            bx[u] = (u < 4 ? Xp : Xq)[(long long)((4 * u + lq) & 15) * lp + c0 + l16];
         double4_t o0 = {0.0, 0.0, 0.0, 0.0}, o1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            o0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], bx[u], o0, 0, 0, 0);
-            o1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], bx[u], o1, 0, 0, 0);
+        for (int u = 0; u < 8; ++u) {   // (V is read from LDS for every tile: holding it would cost 32 registers)
+            o0 = __builtin_amdgcn_mfma_f64_16x16x4f64(va0[4 * u], bx[u], o0, 0, 0, 0);
+            o1 = __builtin_amdgcn_mfma_f64_16x16x4f64(va1[4 * u], bx[u], o1, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int r0 = 4 * e + lq;                          // row inside a 16-row half
-            X[((long long)bp * 16 + r0) * lp + c0 + l16] = o0[e];
-            X[((long long)bq * 16 + r0) * lp + c0 + l16] = o1[e];
+            Xp[(long long)r0 * lp + c0 + l16] = o0[e];
+            Xq[(long long)r0 * lp + c0 + l16] = o1[e];
         }
     }
     __syncthreads();
@@ -743,7 +717,7 @@ hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, in
                                int jb_mask, hipStream_t stream) {
     if (jb_mask & (1 << 4)) {
         static bool attr_done = false;
-        constexpr int lds16 = (32 * (544 + kJgPad) + 2 * 32 * kJgLdS) * (int)sizeof(double);
+        constexpr int lds16 = (kJgParts * 768 + 2 * 32 * kJgLdS) * (int)sizeof(double);
         if (!attr_done) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds16);

@@ -354,9 +354,10 @@ hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max
 // ------------------------------------------------------------------ blocked one-sided Jacobi
 // X (lp x lp, fp64, row-major) starts as the symmetric matrix T (rows/columns >= l zero).
 // Rotating ROWS until they are mutually orthogonal gives X = Lambda U^T: row i is
-// ritz_i * u_i^T.  Rows are grouped in blocks of jb; one workgroup holds two blocks in LDS and
-// sweeps all row pairs of the 2*jb rows; block pairs follow a round-robin tournament so the
-// lp/jb - 1 rounds of one sweep meet every block pair once.
+// ritz_i * u_i^T.  Rows are grouped in blocks of 16; one workgroup takes a pair of blocks (a
+// "visit"): it forms the 32 x 32 Gram matrix of the 32 rows, runs one cyclic Jacobi sweep on that
+// small matrix with the rotations accumulated in V, and applies X <- V X to the rows.  Block pairs
+// follow a round-robin tournament so the lp/16 - 1 rounds of one sweep meet every block pair once.
 __device__ __forceinline__ void tournament_pair(int players, int round, int k, int* a, int* b) {
     const int N = players - 1;
     if (k == 0) {
@@ -406,87 +407,6 @@ __device__ __forceinline__ double wave_allreduce(double v) {
     return v;
 }
 
-// One wavefront per row pair (blockDim = 64 * jb): the two rows are held in registers between
-// the three dot products and the rotation (each lane owns SEG columns, lane-contiguous in LDS).
-// JB is the row-block size the kernel is compiled for (matrices with another jb are skipped: the
-// host launches one instance per block size present in the layer set).
-template <int JB>
-__global__ __launch_bounds__(64 * JB) void k_jacobi_round(const MatDev* __restrict__ mats, int round) {
-    constexpr int SEG = JB == 16 ? 9 : (JB == 8 ? 18 : 32);   // ceil(largest lp of the class / 64)
-    extern __shared__ __attribute__((aligned(16))) double xs[];   // [2*jb][lp]
-    __shared__ int nrot_s;
-    const MatDev& md = mats[blockIdx.y];
-    if (md.jb != JB) return;
-    const int lp = md.lp;
-    constexpr int jb = JB;
-    const int nb = lp / jb;
-    if ((int)blockIdx.x >= nb / 2 || round >= nb - 1) return;
-    if (md.jflag[1] != 0) return;       // converged in an earlier sweep
-    int bp, bq;
-    tournament_pair(nb, round, blockIdx.x, &bp, &bq);
-    if (bp * jb >= md.l || bq * jb >= md.l) return;   // a block of padding rows only: nothing to rotate
-    const int tid = threadIdx.x, nthr = 64 * jb;
-    const int R = 2 * jb;
-    double* __restrict__ X = md.T;
-    for (int q = tid; q < jb * lp; q += nthr) {
-        xs[q] = X[(long long)bp * jb * lp + q];
-        xs[jb * lp + q] = X[(long long)bq * jb * lp + q];
-    }
-    if (tid == 0) nrot_s = 0;
-    __syncthreads();
-
-    const int pi = tid >> 6, lane = tid & 63;
-    int nrot = 0;
-    for (int ir = 0; ir < R - 1; ++ir) {
-        int a, b;
-        tournament_pair(R, ir, pi, &a, &b);
-        double* xa = xs + a * lp;
-        double* xb = xs + b * lp;
-        double va[SEG], vb[SEG];
-        double al = 0.0, be = 0.0, ga = 0.0;
-#pragma unroll
-        for (int i = 0; i < SEG; ++i) {
-            const int c = lane + 64 * i;
-            va[i] = c < lp ? xa[c] : 0.0;
-            vb[i] = c < lp ? xb[c] : 0.0;
-        }
-#pragma unroll
-        for (int i = 0; i < SEG; ++i) {
-            al += va[i] * va[i];
-            be += vb[i] * vb[i];
-            ga += va[i] * vb[i];
-        }
-        al = wave_allreduce(al);
-        be = wave_allreduce(be);
-        ga = wave_allreduce(ga);
-        const bool rot = (al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-15 * al * be);
-        if (rot) {
-            const double zeta = (be - al) / (2.0 * ga);
-            const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-            const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
-#pragma unroll
-            for (int i = 0; i < SEG; ++i) {
-                const int c = lane + 64 * i;
-                if (c < lp) {
-                    xa[c] = cs * va[i] - sn * vb[i];
-                    xb[c] = sn * va[i] + cs * vb[i];
-                }
-            }
-            // only a coupling above ~3e-4 of the two rows' norms keeps the sweep loop alive: after a
-            // sweep without one, what is left is quadratically smaller, ~1e-7: the rounding of the float
-            // the result is stored in
-            if (lane == 0 && ga * ga > 1.0e-7 * al * be) ++nrot;
-        }
-        __syncthreads();
-    }
-    if (nrot) atomicAdd(&nrot_s, nrot);
-    __syncthreads();
-    for (int q = tid; q < jb * lp; q += nthr) {
-        X[(long long)bp * jb * lp + q] = xs[q];
-        X[(long long)bq * jb * lp + q] = xs[jb * lp + q];
-    }
-    if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
-}
 
 // ------------------------------------------------------------------ block rotation through the Gram matrix
 // The 16-row class.  One visit of a block pair (32 rows of length lp, held in LDS):
@@ -550,7 +470,6 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     __shared__ int nrot_s;
     __shared__ double smax_s;
     const MatDev& md = mats[blockIdx.y];
-    if (md.jb != 16) return;
     const int lp = md.lp;
     const int nb = lp / 16;
     if ((int)blockIdx.x >= nb / 2 || round >= nb - 1) return;
@@ -700,33 +619,15 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     if (tid == 0 && nrot_s) atomicAdd(&md.jflag[0], nrot_s);
 }
 
-template <int JB>
-static void jacobi_round_launch(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
-                                hipStream_t stream) {
+hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, hipStream_t stream) {
     static bool attr_done = false;
+    constexpr int lds = (kJgParts * 768 + 2 * 32 * kJgLdS) * (int)sizeof(double);
     if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round<JB>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kJacobiLdsBudget);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_jacobi_round<JB>, dim3(max_pairs, n_mats), dim3(64 * JB), lds_bytes, stream, mats, round);
-}
-
-// jb_mask: bit log2(jb) set for every row-block size present in the layer set (4, 8, 16).
-hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
-                               int jb_mask, hipStream_t stream) {
-    if (jb_mask & (1 << 4)) {
-        static bool attr_done = false;
-        constexpr int lds16 = (kJgParts * 768 + 2 * 32 * kJgLdS) * (int)sizeof(double);
-        if (!attr_done) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
-            attr_done = true;
-        }
-        hipLaunchKernelGGL(k_jacobi_round_gram, dim3(max_pairs, n_mats), dim3(1024), lds16, stream, mats, round);
-    }
-    if (jb_mask & (1 << 3)) jacobi_round_launch<8>(mats, n_mats, max_pairs, round, lds_bytes, stream);
-    if (jb_mask & (1 << 2)) jacobi_round_launch<4>(mats, n_mats, max_pairs, round, lds_bytes, stream);
+    hipLaunchKernelGGL(k_jacobi_round_gram, dim3(max_pairs, n_mats), dim3(1024), lds, stream, mats, round);
     return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Sizes {   // per-matrix derived sizes
-    int ldn, l, ldk, ldr, roct, lp, jb;
+    int ldn, l, ldk, ldr, roct, lp;
     size_t bytes[NG_NBUF];
     size_t k_gram_off, k_w64_off, k_w32_off;
     size_t aux_pb_off, aux_pbt_off;
@@ -87,13 +87,7 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
     z->ldk = (int)align_up((size_t)d.m, 32);
     z->ldr = (int)align_up((size_t)d.r, 32);
     z->roct = ceil_div(d.r, 8);
-    int jb = 16;
-    for (; jb > 4; jb >>= 1) {
-        size_t lp = align_up((size_t)l, (size_t)2 * jb);
-        if ((size_t)2 * jb * lp * sizeof(double) <= (size_t)kJacobiLdsBudget) break;
-    }
-    z->jb = jb;
-    z->lp = (int)align_up((size_t)l, (size_t)2 * jb);
+    z->lp = (int)align_up((size_t)l, (size_t)2 * kJacobiBlock);
     const size_t rn = (size_t)d.r * z->ldn;
     z->bytes[NG_BUF_P] = align_up((size_t)d.m * d.r * 4, 256);
     z->bytes[NG_BUF_M] = align_up(rn * 4, 256);
@@ -227,9 +221,8 @@ struct ng_state {
     int n_dots;
     int max_m, max_n, max_r, max_l, max_lp, max_rows;
     int max_ti[OP_COUNT], max_tj[OP_COUNT], max_tk[OP_COUNT];   // largest M, N, K of each fp32 product
-    int max_jpairs, jb_mask;
+    int max_jpairs;
     int sides;       // bit 0: left-side matrices present, bit 1: right-side ones
-    size_t jacobi_lds;
     // profiling
     bool profiling;
     hipEvent_t ev[kProfRing][NG_NPHASE + 1];
@@ -451,9 +444,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         size_t off = pl.off_scratch;
         st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
         st->max_jpairs = 0;
-        st->jb_mask = 0;
         st->sides = 0;
-        st->jacobi_lds = 0;
         for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = st->max_tk[op] = 1;
         for (int i = 0; i < n_mats; ++i) {
             const Sizes& z = pl.sz[i];
@@ -492,7 +483,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.order = (int*)(ws + off); off += z.ws_order;
             md.jflag = (int*)(ws + off); off += z.ws_flag;
             md.carry = z.ws_carry ? (float*)(ws + off) : nullptr; off += z.ws_carry;
-            md.lp = z.lp; md.jb = z.jb;
+            md.lp = z.lp;
             // units of the Gram-row reduction: 16-byte vectors of a slot
             const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
             long long iters = (total4 + 256LL * kDotPartsMax - 1) / (256LL * kDotPartsMax);
@@ -508,11 +499,8 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             if (md.lp > st->max_lp) st->max_lp = md.lp;
             const int rows = md.m > md.n ? md.m : md.n;
             if (rows > st->max_rows) st->max_rows = rows;
-            const int pairs = md.lp / md.jb / 2;
+            const int pairs = md.lp / kJacobiBlock / 2;
             if (pairs > st->max_jpairs) st->max_jpairs = pairs;
-            st->jb_mask |= md.jb;   // jb is 4, 8 or 16: its own bit
-            const size_t jl = (size_t)2 * md.jb * md.lp * sizeof(double);
-            if (jl > st->jacobi_lds) st->jacobi_lds = jl;
             for (int op = 0; op < OP_COUNT; ++op) {
                 int M, N, K;
                 gemm_f32_dims(op, md, &M, &N, &K);
@@ -610,7 +598,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     for (int sw = 0; sw < st->hp.refresh_sweeps; ++sw) {
         const int max_rounds = 2 * st->max_jpairs - 1;
         for (int round = 0; round < (max_rounds > 0 ? max_rounds : 1); ++round)
-            NG_HIP(launch_jacobi_round(st->d_mats, st->n_mats, st->max_jpairs, round, st->jacobi_lds, st->jb_mask, stream));
+            NG_HIP(launch_jacobi_round(st->d_mats, st->n_mats, st->max_jpairs, round, stream));
         NG_HIP(launch_jacobi_sweep_end(st->d_mats, st->n_mats, stream));
     }
     NG_HIP(launch_jacobi_finish(st->d_mats, st->n_mats, st->d_status, stream));

@@ -15,8 +15,7 @@ constexpr int kMaxS = 64;        // history slots
 constexpr int kDotPartsMax = 256; // per-matrix partial sums of the Gram-row reduction
 constexpr int kAdamPatchCols = 128; // columns of one transform+Adam workgroup patch (32 rows)
 constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (by kernel argument)
-constexpr int kJacobiLdsBudget = 139264;   // bytes of LDS the blocked Jacobi may use for its two row blocks
-                                           // (16-row blocks up to lp = 544; the Gram variant adds 24 KiB)
+constexpr int kJacobiBlock = 16;  // rows per block of the blocked Jacobi (a visit rotates a pair of blocks)
 
 // Static per-matrix description, lives in the workspace (device) and in the handle (host).
 struct MatDev {
@@ -58,7 +57,7 @@ struct MatDev {
     float* carry;     // [r][ldn] scratch of the history carry-over (null unless enabled)
     bf16_t* tail8;    // 8 bf16 in the workspace: the last gradient row's columns from the last multiple of
                       // 8 on, zero-padded (rewritten every step, see launch_upload_dyn)
-    int lp, jb;       // padded size and row-block size of the blocked Jacobi
+    int lp;           // l rounded up to a whole number of Jacobi block pairs: order and row pitch of T, Linv
 };
 
 // Per-step values: uploaded into the workspace by a tiny kernel that receives them by value.
@@ -174,8 +173,7 @@ hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, int max_or
                            int* status, hipStream_t stream);
 hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream);
 hipError_t launch_jacobi_prepare(const MatDev* mats, int n_mats, hipStream_t stream);
-hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, size_t lds_bytes,
-                               int jb_mask, hipStream_t stream);
+hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, hipStream_t stream);
 hipError_t launch_jacobi_sweep_end(const MatDev* mats, int n_mats, hipStream_t stream);
 hipError_t launch_jacobi_finish(const MatDev* mats, int n_mats, int* status, hipStream_t stream);
 hipError_t launch_sign_fix(const MatDev* mats, int n_mats, int max_r, hipStream_t stream);

@@ -261,3 +261,11 @@ def test_bf16_projection_slot_small_and_ragged(hist, pad_g, rank_cap):
         tol = 1e-5 if hist == "f32" else 2.0 ** -8
         assert np.abs(Hs[:, :n] - R).max() <= tol * scale, (i, shapes[i], np.abs(Hs[:, :n] - R).max() / scale)
         assert not Hs[:, n:].any(), (i, shapes[i], "padding columns of the slot are not zero")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_rank_refresh_and_step(dtype):
+    # sketch width 608: more Jacobi block pairs than at the ranks of the benchmark layer sets, a
+    # triangular inverse that needs the narrow column blocks
+    ls, errs = _run([(700, 900), (640, 1000)], 600, 2, dtype, 3, seed=91, k=640)
+    _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "large rank " + dtype)

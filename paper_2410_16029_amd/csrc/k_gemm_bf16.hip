@@ -45,6 +45,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef u32x4_t __attribute__((aligned(2))) u32x4_a2;   // 16-byte access at 2-byte alignment
+typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access at 4-byte alignment
 typedef const NG_AS1 bf16_t* gbf16_cptr;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -1027,6 +1028,200 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
     project_epilogue<C, HB>(acc, md, dy, smem, i0, j0, t, wm, wn, li, h);
 }
 
+// =================================================================== refresh products with a bf16 gradient
+// The big products of the projector refresh multiply the bf16 gradient by an fp32 sketch matrix Y.
+// On the fp32 MFMA they run at a sixteenth of the bf16 rate, so Y is split on its way into LDS into
+// three bf16 planes, Y = Y0 + Y1 + Y2 with Y0 = bf16(Y), Y1 = bf16(Y - Y0), Y2 = bf16(Y - Y0 - Y1)
+// (24 mantissa bits: the float itself unless it spans more than three bf16 exponent windows), and the
+// product is three bf16 MFMA products accumulated in fp32 -- the arithmetic of an fp32 GEMM whose
+// gradient operand is exactly representable, at three sixteenths of its MFMA cost.
+//
+// YTLoader: Y stored [k][x] with x contiguous (the sketch matrices are [rows][l]).  One 4 (k) x 8 (x)
+// block per thread and 64-deep tile, transposed in registers like the gradient tile of the
+// register-staged projection, each value split, written as 8-byte LDS words (4 consecutive k).
+template <class C>
+struct YTLoader {
+    static_assert(C::KG * (C::BM / 8) == C::NT && C::BM == C::BN, "one block per thread");
+    const NG_AS1 float* base;
+    long long ld;
+    int k_lim, x_lim, kg4, xcol;
+    f32x4_t r[4][2];
+    unsigned rowok;
+
+    __device__ __forceinline__ void init(const float* Y, long long ld_, int k_lim_, int x_lim_, int x0, int t) {
+        base = (const NG_AS1 float*)Y;
+        ld = ld_;
+        k_lim = k_lim_;
+        x_lim = x_lim_;
+        kg4 = (t % C::KG) * 4;
+        xcol = x0 + 8 * (t / C::KG);
+    }
+    __device__ __forceinline__ void load(int k0) {
+        rowok = 0;
+        const bool whole = xcol + 8 <= x_lim;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = k0 + kg4 + q;
+            const bool ok = k < k_lim;
+            rowok |= ok ? (1u << q) : 0u;
+            const NG_AS1 float* row = base + (long long)(ok ? k : k_lim - 1) * ld;
+            if (whole) {
+                r[q][0] = *(const NG_AS1 f32x4_a4*)(row + xcol);
+                r[q][1] = *(const NG_AS1 f32x4_a4*)(row + xcol + 4);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) r[q][c >> 2][c & 3] = (xcol + c < x_lim) ? row[xcol + c] : 0.f;
+            }
+        }
+    }
+    // P0, P1, P2: the three plane tiles, [x][LDS_K] bf16 each
+    __device__ __forceinline__ void store(bf16_t* P0, bf16_t* P1, bf16_t* P2, int t) const {
+        const int xg = t / C::KG;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            unsigned short h0[4], h1[4], h2[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float v = ((rowok >> q) & 1u) ? r[q][c >> 2][c & 3] : 0.f;
+                const unsigned a = f2bf(v);
+                const float r1 = v - __uint_as_float(a << 16);
+                const unsigned b = f2bf(r1);
+                const float r2 = r1 - __uint_as_float(b << 16);
+                h0[q] = (unsigned short)a;
+                h1[q] = (unsigned short)b;
+                h2[q] = (unsigned short)f2bf(r2);
+            }
+            const int off = (xg * 8 + c) * C::LDS_K + kg4;
+            *reinterpret_cast<u32x2_t*>(P0 + off) = (u32x2_t){h0[0] | ((unsigned)h0[1] << 16), h0[2] | ((unsigned)h0[3] << 16)};
+            *reinterpret_cast<u32x2_t*>(P1 + off) = (u32x2_t){h1[0] | ((unsigned)h1[1] << 16), h1[2] | ((unsigned)h1[3] << 16)};
+            *reinterpret_cast<u32x2_t*>(P2 + off) = (u32x2_t){h2[0] | ((unsigned)h2[1] << 16), h2[2] | ((unsigned)h2[3] << 16)};
+        }
+    }
+};
+
+// One BK-deep sweep: the plain operand's fragments against the three planes'.  PA: the planes are the A
+// operand (rows of the result), else the B operand.
+template <class C, bool PA>
+__device__ __forceinline__ void mma_tile_x3(floatx16 (&acc)[C::MI][C::NJ], const bf16_t* Gs, const bf16_t* P0, int wm,
+                                            int wn, int li, int h) {
+    constexpr int KK = C::BK / 16, PL = C::BM * C::LDS_K;   // elements per plane tile
+    const int prow = (PA ? wm * C::WM : wn * C::WN) + li, grow = (PA ? wn * C::WN : wm * C::WM) + li;
+    constexpr int PN = PA ? C::MI : C::NJ, GN = PA ? C::NJ : C::MI;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        u32x4_t g[GN];
+#pragma unroll
+        for (int x = 0; x < GN; ++x)
+            g[x] = *reinterpret_cast<const u32x4_t*>(Gs + (grow + 32 * x) * C::LDS_K + kk * 16 + h * 8);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) {
+            u32x4_t y[PN];
+#pragma unroll
+            for (int x = 0; x < PN; ++x)
+                y[x] = *reinterpret_cast<const u32x4_t*>(P0 + pl * PL + (prow + 32 * x) * C::LDS_K + kk * 16 + h * 8);
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+                for (int nj = 0; nj < C::NJ; ++nj) {
+                    const u32x4_t& a = PA ? y[mi] : g[mi];
+                    const u32x4_t& b = PA ? g[nj] : y[nj];
+                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(&a),
+                                                                          *reinterpret_cast<const bf16x8_t*>(&b),
+                                                                          acc[mi][nj], 0, 0, 0);
+                }
+        }
+    }
+}
+
+// FORM 1: C = Ya [m][l] = G Y        (Y [n][l]; G rows are contraction-contiguous: chunk loader)
+// FORM 2: C = Yb [n][l] = G^T Y      (Y [m][l]; G through the transposing loader, as the A operand)
+// FORM 3: C = Bm [l][ldn] = Y^T G    (Y [m][l]: planes on the A side; G through the transposing
+//                                     loader; columns >= n of C are written as zero)
+// ysrc: which sketch buffer Y is (0 Ya, 1 Yb, 2 Yc).  One 128 x 128 tile per workgroup, 64-deep
+// k-steps, register-staged loads one step ahead.
+template <class C, int FORM>
+__global__ __launch_bounds__(C::NT) void k_refresh_x3(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
+                                                      int ysrc) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    static_assert(FORM >= 1 && FORM <= 3, "product form");
+    const MatDev& md = mats[blockIdx.z];
+    if (md.side == NG_SIDE_RIGHT) return;
+    const MatDyn dy = dyn[blockIdx.z];
+    const int M = FORM == 1 ? md.m : FORM == 2 ? md.n : md.l;
+    const int N = FORM == 3 ? md.ldn : md.l;
+    const int K = FORM == 1 ? md.n : md.m;
+    const int i0 = blockIdx.y * C::BM, j0 = blockIdx.x * C::BN;
+    if (i0 >= M || j0 >= N) return;
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int wm = wv / C::NWN, wn = wv % C::NWN, li = lane & 31, h = lane >> 5;
+    bf16_t* Gs = reinterpret_cast<bf16_t*>(smem);
+    bf16_t* P0 = Gs + C::BN * C::LDS_K;
+    bf16_t* P1 = P0 + C::BM * C::LDS_K;
+    bf16_t* P2 = P1 + C::BM * C::LDS_K;
+    const float* Y = ysrc == 0 ? md.Ya : ysrc == 1 ? md.Yb : md.Yc;
+
+    floatx16 acc[C::MI][C::NJ];
+    zero_acc<C>(acc);
+
+    // the planes' tile index runs over Y's columns (the l sketch columns): result rows in form 3,
+    // result columns otherwise
+    YTLoader<C> ly;
+    ly.init(Y, md.l, K, md.l, FORM == 3 ? i0 : j0, t);
+    BTLoader<C> lgt;   // forms 2, 3: tile index = gradient column
+    BKLoader<C> lgk;   // form 1: tile index = gradient row
+    const int g0 = FORM == 3 ? j0 : i0;
+    bool full = true, k8 = true;
+    if (FORM == 1) {
+        lgk.init(dy.g, md.ld_g, g0, md.m, md.n, t);
+        k8 = (md.n & 7) == 0;
+    } else {
+        lgt.init(dy.g, md.ld_g, md.m, md.n, g0, t);
+        full = (md.n >= 8) && ((md.n & 7) == 0 || g0 + C::BN <= md.n);
+    }
+    const int nk = (K + C::BK - 1) / C::BK;
+    auto loads = [&](int k0) {
+        ly.load(k0);
+        if (FORM == 1) {
+            if (k8) lgk.template load<true>(k0);
+            else lgk.template load<false>(k0);
+        } else {
+            if (full) lgt.template load<true>(k0);
+            else lgt.template load<false>(k0);
+        }
+    };
+    auto stores = [&]() {
+        ly.store(P0, P1, P2, t);
+        if (FORM == 1) lgk.store(Gs, t);
+        else if (full) lgt.template store<true>(Gs, t);
+        else lgt.template store<false>(Gs, t);
+    };
+    loads(0);
+    stores();
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) loads((kt + 1) * C::BK);
+        mma_tile_x3<C, FORM == 3>(acc, Gs, P0, wm, wn, li, h);
+        __syncthreads();
+        if (kt + 1 < nk) stores();
+        __syncthreads();
+    }
+    float* Cout = FORM == 1 ? md.Ya : FORM == 2 ? md.Yb : md.Bm;
+    const int ldc = FORM == 3 ? md.ldn : md.l;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < C::NJ; ++nj) {
+            const int col = j0 + wn * C::WN + nj * 32 + li;
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int row = i0 + wm * C::WM + mi * 32 + 8 * g + 4 * h + e;
+                    if (row < M && col < N) Cout[(long long)row * ldc + col] = acc[mi][nj][4 * g + e];
+                }
+        }
+}
+
 // =================================================================== launchers
 // Tile configurations (BM x BN workgroup tile, WM x WN per wavefront).  Update: Cfg3 -- the weight tile
 // has 512-byte rows and the operand with 64-byte chunks per row (Pb) is the smaller one.  Projection:
@@ -1119,6 +1314,28 @@ void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
         *bm = which == 0 ? Cfg4::BM : Cfg2::BM;
         *bn = which == 0 ? Cfg4::BN : Cfg2::BN;
     }
+}
+
+hipError_t launch_refresh_x3(int form, int ysrc, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m,
+                             int max_n, hipStream_t stream) {
+    typedef Cfg0 C;
+    constexpr int lds = (C::BN + 3 * C::BM) * C::LDS_K * 2;
+    static bool attr = false;
+    if (!attr) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr = true;
+    }
+    dim3 g((max_n + C::BN - 1) / C::BN, (max_m + C::BM - 1) / C::BM, n_mats);
+    if (form == 1) hipLaunchKernelGGL((k_refresh_x3<C, 1>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    else if (form == 2) hipLaunchKernelGGL((k_refresh_x3<C, 2>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    else if (form == 3) hipLaunchKernelGGL((k_refresh_x3<C, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 }  // namespace ng

@@ -152,6 +152,12 @@ hipError_t launch_project_bf16(const MatDev* mats, const MatDyn* dyn, const Tile
 hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles,
                               StepScalars sc, const void* zero16, int sides, hipStream_t stream);
 
+// Refresh products of a bf16 gradient with an fp32 sketch matrix Y as three bf16 MFMA products (left side).
+// form 1: Ya = G Y, form 2: Yb = G^T Y, form 3: Bm = Y^T G; ysrc: Y is 0 Ya, 1 Yb, 2 Yc;
+// max_m / max_n: largest row / column count of the result over the layer set
+hipError_t launch_refresh_x3(int form, int ysrc, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m,
+                             int max_n, hipStream_t stream);
+
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 // row_override >= 0: the Gram row of that slot instead of the step's head (history carry-over);
 // launch_solve then only stores the row and column of K and skips the solve

@@ -369,13 +369,20 @@ __device__ __forceinline__ void tournament_pair(int players, int round, int k, i
     }
 }
 
+// The rows that the Jacobi rotates are kept as floats (the result, a rotation stored as floats, needs
+// no more; every product and sum on them is still formed in fp64): X = T rounded, zero in the padding,
+// in the buffer of the inverse Cholesky factor, which is free between the last orthonormalisation
+// and the one of the new projector.
+__device__ __forceinline__ float* jacobi_rows(const MatDev& md) { return md.Linv; }
+
 __global__ __launch_bounds__(256) void k_jacobi_prepare(const MatDev* __restrict__ mats) {
     const MatDev& md = mats[blockIdx.y];
     const int lp = md.lp, l = md.l;
     const long long total = (long long)lp * lp;
+    float* __restrict__ X = jacobi_rows(md);
     for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256) {
         const int i = (int)(q / lp), j = (int)(q % lp);
-        if (i >= l || j >= l) md.T[q] = 0.0;
+        X[q] = (i < l && j < l) ? (float)md.T[q] : 0.f;
     }
     if (blockIdx.x == 0 && threadIdx.x < 4) md.jflag[threadIdx.x] = 0;
 }
@@ -409,16 +416,19 @@ __device__ __forceinline__ double wave_allreduce(double v) {
 
 
 // ------------------------------------------------------------------ block rotation through the Gram matrix
-// The 16-row class.  One visit of a block pair (32 rows of length lp, held in LDS):
-//   S = X X^T          32 x 32 Gram of the rows, fp64 MFMA (16x16x4), K split over two wavefront groups
-//   small sweep        the 31 x 16 rotations of one cyclic sweep over the 32 rows, applied two-sidedly to
-//                      S (S <- J S J^T) and accumulated in V (V <- J V): the same rotations, in the same
-//                      order, that the row-by-row kernel would apply, decided from S instead of fresh dots
+// One visit of a pair of 16-row blocks (32 rows of length lp, floats in global memory):
+//   S = X X^T          32 x 32 Gram of the rows, fp64 MFMA (16x16x4), the columns split over eight wavefronts
+//   small sweep        cyclic rounds of 16 disjoint rotations each, applied two-sidedly to S (S <- J S J^T)
+//                      and accumulated in V (V <- J V): the rotations that a row-by-row Jacobi would
+//                      apply, decided from S instead of fresh dot products.  Round 0 of a sweep takes
+//                      all 496 row pairs of the visit (31 rounds), every other round the 256 pairs
+//                      with a row in each block (16 rounds)
 //   X <- V X           fp64 MFMA, each wavefront owns 16-column tiles, written straight back to memory
-// so the 32 rows are read from LDS twice per visit instead of 2 x 31 times.
+// so the 32 rows are read twice per visit instead of 2 x 31 times.
 // v_mfma_f64_16x16x4_f64: lane L supplies A[L%16][L/16] and B[L/16][L%16]; element e of its result is
 // D[4e + L/16][L%16] (checked on the device).
 typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kJgLdS = 36;     // row length of S and V in LDS (32 + 4: 16 rows land on distinct banks)
 constexpr int kJgParts = 8;    // wavefronts that share the Gram product (a slice of the columns each)
 
@@ -476,18 +486,23 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     if (md.jflag[1] != 0) return;       // converged in an earlier sweep
     int bp, bq;
     tournament_pair(nb, round, blockIdx.x, &bp, &bq);
-    if (bp * 16 >= md.l || bq * 16 >= md.l) return;   // a block of padding rows only: nothing to rotate
+    // Round 0 of a sweep (every block is in exactly one pair) rotates all 496 row pairs of a visit;
+    // the other rounds only the 256 pairs with one row in each block: the pairs inside a block
+    // would otherwise be rotated again in each of its nb - 1 visits of the sweep.
+    const bool cross = round != 0;
+    // a block of padding rows only has nothing to rotate (in round 0 its partner still has its own pairs)
+    if (cross ? (bp * 16 >= md.l || bq * 16 >= md.l) : (bp * 16 >= md.l && bq * 16 >= md.l)) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    // The 32 rows of the pair stay in global memory (they sit in the L2 between rounds): the Gram
-    // product and X <- V X take their MFMA operands straight from there, so a workgroup needs only
+    // The 32 rows of the pair stay in global memory: the Gram product and X <- V X take their MFMA
+    // operands straight from there (the second read mostly from the L2), so a workgroup needs only
     // 68 KB of LDS and 64 registers per lane, and two visits share a CU -- one multiplies or
     // streams while the other sits in the dependent rounds of its small sweep.
     double* part = smem_d;                          // [kJgParts][3][256] Gram partials
     double* Ss = part + kJgParts * 768;             // [32][kJgLdS]
     double* Vs = Ss + 32 * kJgLdS;                  // [32][kJgLdS]
-    double* __restrict__ X = md.T;
-    double* __restrict__ Xp = X + (long long)bp * 16 * lp;   // rows 0..15 of the pair
-    double* __restrict__ Xq = X + (long long)bq * 16 * lp;   // rows 16..31
+    float* __restrict__ X = jacobi_rows(md);
+    float* __restrict__ Xp = X + (long long)bp * 16 * lp;   // rows 0..15 of the pair
+    float* __restrict__ Xq = X + (long long)bq * 16 * lp;   // rows 16..31
     if (tid == 0) nrot_s = 0;
 
     // ---- Gram: wavefronts 0..7 take an eighth of the columns each and compute the tiles (0,0), (1,0),
@@ -497,21 +512,22 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     if (wv < kJgParts) {
         double4_t g00 = {0.0, 0.0, 0.0, 0.0}, g10 = {0.0, 0.0, 0.0, 0.0}, g11 = {0.0, 0.0, 0.0, 0.0};
         const int cols = lp / kJgParts;            // lp % 32 == 0: cols % 4 == 0
-        const double* p0 = Xp + (long long)l16 * lp + wv * cols + lq;   // A[L%16][k + L/16]
-        const double* p1 = Xq + (long long)l16 * lp + wv * cols + lq;
-        for (int k = 0; k < cols; k += 16) {       // up to 4 k-steps (4 columns each) in flight
-            double x0[4], x1[4];
+        // A lane reads four consecutive columns of its row, 16 columns per 16 lanes and chunk; k-step
+        // u of a chunk contracts over element u of every lane, i.e. over the columns 4 (L/16) + u:
+        // both operands are the same rows, so any order of the contraction serves.
+        const float* p0 = Xp + (long long)l16 * lp + wv * cols + 4 * lq;
+        const float* p1 = Xq + (long long)l16 * lp + wv * cols + 4 * lq;
+        const f32x4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < cols; k += 16) {
+            const bool in = k + 4 * lq < cols;
+            const f32x4_t x0 = in ? *reinterpret_cast<const f32x4_t*>(p0 + k) : zero4;
+            const f32x4_t x1 = in ? *reinterpret_cast<const f32x4_t*>(p1 + k) : zero4;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const bool in = k + 4 * u < cols;
-                x0[u] = in ? p0[k + 4 * u] : 0.0;
-                x1[u] = in ? p1[k + 4 * u] : 0.0;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(x0[u], x0[u], g00, 0, 0, 0);
-                g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1[u], x0[u], g10, 0, 0, 0);
-                g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1[u], x1[u], g11, 0, 0, 0);
+                const double a0 = (double)x0[u], a1 = (double)x1[u];
+                g00 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, a0, g00, 0, 0, 0);
+                g10 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, a0, g10, 0, 0, 0);
+                g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, a1, g11, 0, 0, 0);
             }
         }
         double* dst = part + wv * 768;
@@ -557,15 +573,18 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     ri.init(vi);
     rj.init(vj);
     int nrot = 0;
-    for (int ir = 0; ir < 31; ++ir) {
+    const int nir = cross ? 16 : 31;
+    for (int ir = 0; ir < nir; ++ir) {
         // old values first (their addresses depend on the round only), rotation parameters meanwhile
-        const int pi = ri.partner(ir), pj = rj.partner(ir);
+        const int pi = cross ? (vi < 16 ? 16 + ((vi + ir) & 15) : ((vi - ir) & 15)) : ri.partner(ir);
+        const int pj = cross ? (vj < 16 ? 16 + ((vj + ir) & 15) : ((vj - ir) & 15)) : rj.partner(ir);
         const double s00 = Ss[vi * kJgLdS + vj], s10 = Ss[pi * kJgLdS + vj];
         const double s01 = Ss[vi * kJgLdS + pj], s11 = Ss[pi * kJgLdS + pj];
         const double v0 = Vs[vi * kJgLdS + vj], v1 = Vs[pi * kJgLdS + vj];
         if (tid < 16) {
             int a, b;
             tournament_pair(32, ir, tid, &a, &b);
+            if (cross) { a = tid; b = 16 + ((tid + ir) & 15); }
             const double al = Ss[a * kJgLdS + a], be = Ss[b * kJgLdS + b], ga = Ss[a * kJgLdS + b];
             double cs = 1.0, sn = 0.0;
             if ((al > 0.0) && (be > 0.0) && (ga * ga > 1.0e-15 * al * be)) {
@@ -596,23 +615,31 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     const int nct = lp / 16;
     const double* va0 = Vs + l16 * kJgLdS + lq;                // A[L%16][k + L/16] = V[L%16][k + L/16], k = 4u
     const double* va1 = Vs + (16 + l16) * kJgLdS + lq;
+    const unsigned rowoff = (unsigned)lq * (unsigned)lp + (unsigned)l16, lp4 = 4u * (unsigned)lp;
     for (int ct = wv; ct < nct; ct += 16) {
-        const int c0 = 16 * ct;
-        double bx[8];
+        // B[k + L/16][L%16] = X[k + L/16][c0 + L%16], k = 4u: rows 0..15 from Xp, 16..31 from Xq; element e
+        // of a result tile is row 4e + L/16 of its half: the same offsets
+        const unsigned base = rowoff + 16u * (unsigned)ct;
+        float bx[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)   // B[k + L/16][L%16] = X[k + L/16][c0 + L%16], k = 4u: rows 0..15 from Xp, 16..31 from Xq
-            bx[u] = (u < 4 ? Xp : Xq)[(long long)((4 * u + lq) & 15) * lp + c0 + l16];
+        for (int u = 0; u < 4; ++u) {
+            bx[u] = Xp[base + u * lp4];
+            bx[4 + u] = Xq[base + u * lp4];
+        }
         double4_t o0 = {0.0, 0.0, 0.0, 0.0}, o1 = {0.0, 0.0, 0.0, 0.0};
+        // V is read from LDS for every tile: held across tiles its 32 registers spill.  The offset is
+        // opaque to the compiler so that it does not hoist the reads out of the loop.
+        int vo = 0;
+        asm volatile("" : "+v"(vo));
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {   // (V is read from LDS for every tile: holding it would cost 32 registers)
-            o0 = __builtin_amdgcn_mfma_f64_16x16x4f64(va0[4 * u], bx[u], o0, 0, 0, 0);
-            o1 = __builtin_amdgcn_mfma_f64_16x16x4f64(va1[4 * u], bx[u], o1, 0, 0, 0);
+        for (int u = 0; u < 8; ++u) {
+            o0 = __builtin_amdgcn_mfma_f64_16x16x4f64(va0[4 * u + vo], (double)bx[u], o0, 0, 0, 0);
+            o1 = __builtin_amdgcn_mfma_f64_16x16x4f64(va1[4 * u + vo], (double)bx[u], o1, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int r0 = 4 * e + lq;                          // row inside a 16-row half
-            Xp[(long long)r0 * lp + c0 + l16] = o0[e];
-            Xq[(long long)r0 * lp + c0 + l16] = o1[e];
+            Xp[base + e * lp4] = (float)o0[e];
+            Xq[base + e * lp4] = (float)o1[e];
         }
     }
     __syncthreads();
@@ -653,9 +680,9 @@ __global__ __launch_bounds__(256) void k_ritz_sort(const MatDev* __restrict__ ma
     const int lp = md.lp;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     for (int i = wv; i < lp; i += 4) {
-        const double* __restrict__ row = md.T + (long long)i * lp;
+        const float* __restrict__ row = jacobi_rows(md) + (long long)i * lp;
         double a = 0.0;
-        for (int c = lane; c < lp; c += 64) a += row[c] * row[c];
+        for (int c = lane; c < lp; c += 64) a += (double)row[c] * (double)row[c];
         a = wave_sum_d(a);
         if (lane == 0) md.ritz[i] = sqrt(a);
     }
@@ -683,7 +710,7 @@ __global__ __launch_bounds__(256) void k_build_rotation(const MatDev* __restrict
         const int k = (int)(q / r), j = (int)(q % r);
         const int src = md.order[j];
         const double nrm = md.ritz[src];
-        md.Bm[q] = nrm > 0.0 ? (float)(md.T[(long long)src * lp + k] / nrm) : 0.f;
+        md.Bm[q] = nrm > 0.0 ? (float)((double)jacobi_rows(md)[(long long)src * lp + k] / nrm) : 0.f;
     }
 }
 

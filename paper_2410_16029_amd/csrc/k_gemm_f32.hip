@@ -27,6 +27,7 @@ struct GemmView {
     int Nvalid;       // columns j >= Nvalid of B read as zero (padding columns of the r x ldn space)
     int a_bf16, b_bf16;
     int epi;
+    int b_tri;        // B(k, j) = 0 for k > j (the transposed inverse Cholesky factor): a tile stops at its last column
 };
 
 __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const MatDyn* dy, int grad_dtype,
@@ -35,6 +36,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
     v.a_bf16 = 0;
     v.b_bf16 = 0;
     v.epi = EPI_F32;
+    v.b_tri = 0;
     const int gb = (grad_dtype == NG_BF16) ? 1 : 0;
     const void* G = dy ? dy->g : nullptr;
     // Strides of the m x n matrix the kernels see inside the caller's row-major gradient: for the
@@ -97,7 +99,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.B = md.Linv; v.sBk = 1; v.sBj = md.lp;          // B(k, j) = Linv[j][k]
             v.M = rows_m ? md.m : md.n; v.N = md.l; v.Nvalid = md.l; v.K = md.l;
             v.C = (op == OP_APPLY_C2A) ? md.Ya : (op == OP_APPLY_C2B) ? md.Yb : md.Yc;
-            v.ldc = md.l;
+            v.ldc = md.l; v.b_tri = 1;
             break;
         }
         case OP_QT_G:
@@ -144,7 +146,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.A = md.P; v.sAi = md.r; v.sAk = 1;
             v.B = md.Linv; v.sBk = 1; v.sBj = md.lp;
             v.M = md.m; v.N = md.r; v.Nvalid = md.r; v.K = md.r;
-            v.C = md.Ya; v.ldc = md.r;
+            v.C = md.Ya; v.ldc = md.r; v.b_tri = 1;
             break;
     }
     return v;
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     __shared__ __attribute__((aligned(16))) float Asm[2][BK][LDT];   // two tile buffers: one barrier per k-step
     __shared__ __attribute__((aligned(16))) float Bsm[2][BK][LDT];
     const MatDev& md = mats[blockIdx.z];
-    const GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype, sc.slot, sc.hist_bf16);
+    GemmView v = gemm_view(op, md, &dyn[blockIdx.z], grad_dtype, sc.slot, sc.hist_bf16);
     // The grid is 1-D over the tiles of the largest matrix, padded to a multiple of 8: hardware workgroup
     // id w runs on XCD w % 8, and it takes this matrix's tile with logical index (w % 8) per + w / 8, so
     // each XCD works through a contiguous run of the matrix's tiles (the column tiles of one row tile
@@ -239,6 +241,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     const int tile = (int)(blockIdx.x % 8) * per + slot;
     if (slot >= per || tile >= nxm * nym) return;
     const int i0 = (tile / nxm) * TS, j0 = (tile % nxm) * TS;
+    if (v.b_tri && j0 + TS < v.K) v.K = j0 + TS;   // rows k > j of B are zero
 
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;

@@ -213,146 +213,169 @@ hipError_t launch_cholesky(const MatDev* mats, int n_mats, int which, int max_or
 }
 
 // ------------------------------------------------------------------ inverse of the Cholesky factor
-// Linv = L^{-1} (lower triangular, float).  One workgroup owns a block of CB columns of the
-// inverse: forward substitution L X = E on those CB right-hand sides, the block of X kept in LDS
-// (rows above the block's first column are zero and skipped).  Thread (sub, c): column c of the
-// block, rows of the dot product split over the 256/CB values of sub.
-template <int CB>
-__global__ __launch_bounds__(256) void k_tri_inverse(const MatDev* __restrict__ mats, int which) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char tri_smem[];
-    constexpr int S = 256 / CB;
+// Linv = L^{-1} (lower triangular, float), by 32 x 32 blocks: X_ii = L_ii^{-1}, and below the diagonal
+//   X_ij = -L_ii^{-1} (sum_{k=j..i-1} L_ik X_kj),
+// so a block column of the inverse depends only on itself.  k_tri_diag_inverse inverts the diagonal
+// blocks by forward substitution (one lane per column); k_tri_inverse_blocks gives a workgroup one block
+// column and walks down its block rows: both products of a block run on fp64 MFMA (16x16x4; lane L
+// supplies A[L%16][L/16] and B[L/16][L%16], element e of its result is D[4e + L/16][L%16]), the sum
+// over k from L in global memory and the solved blocks above (LDS, floats), the multiplication by
+// the inverted diagonal block from that block (global, floats) and the sum (LDS, doubles).  16
+// dependent block steps at order 512 instead of the 128 four-row steps of a substitution over the
+// whole column.  A solved entry is rounded to float before anything reads it back, so the stored
+// inverse is what the rows below were computed from.  Rows and columns >= the order read as
+// those of an identity and are not written.
+typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kTriNB = 32;
+
+__global__ __launch_bounds__(64) void k_tri_diag_inverse(const MatDev* __restrict__ mats, int which) {
+    __shared__ double Ls[2][kTriNB][kTriNB + 1], Xl[2][kTriNB][kTriNB + 1];
     const MatDev& md = mats[blockIdx.y];
     const int nn = which == 0 ? md.l : md.r;
-    // Column block b costs (nn - b CB)^2.  Workgroup ids go round-robin over the 8 XCDs, so with a
-    // block count that is a multiple of 8 a plain b = blockIdx.x would give one XCD the two most
-    // expensive blocks of every matrix (order 512: 6.7 ms against 3.7 ms); rotating by the matrix
-    // index spreads them.
-    const int c0 = (int)((blockIdx.x + blockIdx.y) % gridDim.x) * CB;
-    if (c0 >= nn) return;
+    const long long ld = md.lp;
+    const int half = threadIdx.x >> 5, c = threadIdx.x & 31;
+    const int r0 = (2 * (int)blockIdx.x + half) * kTriNB;
+    const double* __restrict__ L = md.T;
+    // (no early return: both halves meet at the barrier; a half past the order works on an identity)
+    for (int i = 0; i < kTriNB; ++i) {
+        const int gi = r0 + i, gc = r0 + c;
+        double v = (i == c) ? 1.0 : 0.0;
+        if (gi < nn && gc < nn && c <= i) v = L[(long long)gi * ld + gc];
+        Ls[half][i][c] = v;
+    }
+    __syncthreads();
+    // column c of the inverse: x_i = (e_i - sum_{k=c..i-1} L_ik x_k) / L_ii, x_i = 0 above the diagonal
+    float* __restrict__ Xg = md.Linv;
+    for (int i = 0; i < kTriNB; ++i) {
+        double xi = 0.0;
+        if (i >= c) {
+            double tot = 0.0;
+            for (int k = c; k < i; ++k) tot += Ls[half][i][k] * Xl[half][k][c];
+            xi = (double)(float)(((i == c ? 1.0 : 0.0) - tot) / Ls[half][i][i]);
+        }
+        Xl[half][i][c] = xi;       // read back by this lane only
+        if (r0 + i < nn && r0 + c < nn) Xg[(long long)(r0 + i) * ld + r0 + c] = (float)xi;
+    }
+}
+
+// XLDS: the solved blocks of the column are kept in LDS (as two 16-column halves, [half][row][16]:
+// the four rows of an MFMA operand are 64 consecutive floats); otherwise they are read back from Linv
+// in global memory, which the barrier of each block step makes visible inside the workgroup.
+template <bool XLDS>
+__global__ __launch_bounds__(256) void k_tri_inverse_blocks(const MatDev* __restrict__ mats, int which) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char tri_smem[];
+    const MatDev& md = mats[blockIdx.y];
+    const int nn = which == 0 ? md.l : md.r;
+    const int nb = (nn + kTriNB - 1) / kTriNB;
+    // Block column b costs (nb - b)^2.  Workgroup ids go round-robin over the 8 XCDs, so with a block
+    // count that is a multiple of 8 a plain b = blockIdx.x would give one XCD the two most expensive
+    // columns of every matrix; rotating by the matrix index spreads them.
+    const int jb = (int)((blockIdx.x + blockIdx.y) % gridDim.x);
+    if (jb >= nb) return;
     const long long ld = md.lp;
     const double* __restrict__ L = md.T;
     float* __restrict__ Xg = md.Linv;
-    const int rows = nn - c0;                       // rows c0 .. nn-1 are non-trivial
-    constexpr int RB = 4;                           // rows resolved per step
-    const int lrs = (rows + RB + 1) & ~1;           // doubles per staged L row
-    double* lrow = reinterpret_cast<double*>(tri_smem);            // [RB][lrs]
-    double* red = lrow + RB * lrs;                                   // [RB][S][CB]
-    float* Xs = reinterpret_cast<float*>(red + RB * S * CB);        // [rows][CB]
-    const int tid = threadIdx.x, c = tid % CB, sub = tid / CB;
-    const bool col_ok = c0 + c < nn;
+    const int c0 = jb * kTriNB;
+    const int rows = (nb - jb) * kTriNB;                     // rows c0 .. of the block column, padded
+    double* Ssm = reinterpret_cast<double*>(tri_smem);       // [2][32][16]
+    float* Xs = reinterpret_cast<float*>(Ssm + 2 * kTriNB * 16);   // [2][rows][16] (XLDS)
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4, tr = wv >> 1, tc = wv & 1;
+    const int col = c0 + 16 * tc + l16;                      // this lane's column of the result tiles
+    const bool col_ok = col < nn;
 
-    // rows above the block: exact zeros
-    for (int q = tid; q < c0 * CB; q += 256) {
-        const int i = q / CB, cc = q % CB;
+    // rows above the block column: exact zeros
+    for (int q = tid; q < c0 * kTriNB; q += 256) {
+        const int i = q / kTriNB, cc = q % kTriNB;
         if (c0 + cc < nn) Xg[(long long)i * ld + c0 + cc] = 0.f;
     }
-    // RB rows per step: their dot products with the rows already solved run together (one pass
-    // over the block, one reduction), the RB x RB triangle that couples them is resolved in order
-    // The rows of L a step needs do not depend on the steps before it: they are fetched into
-    // registers one step ahead (kTriPre entries per thread and row cover orders up to 256 kTriPre)
-    // and written to LDS at the start of their step, so their L2 latency overlaps the previous step.
-    constexpr int kTriPre = 3;
-    const bool pre_ok = nn - c0 + RB <= 256 * kTriPre;
-    double nxt[RB][kTriPre];
-    auto fetch_rows = [&](int i0) {
-        const int len = i0 - c0;
+    if (XLDS) {
+        // the diagonal block, as the first kernel left it
+        for (int q = tid; q < kTriNB * kTriNB; q += 256) {
+            const int i = q / kTriNB, cc = q % kTriNB;
+            const bool in = c0 + i < nn && c0 + cc < nn;
+            Xs[((cc >> 4) * rows + i) * 16 + (cc & 15)] = in ? Xg[(long long)(c0 + i) * ld + c0 + cc] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    for (int ib = jb + 1; ib < nb; ++ib) {
+        const int r0 = ib * kTriNB;
+        // the inverted diagonal block of this block row (does not depend on the sum: fetched first)
+        float dinv[8];
+        {
+            const int gi = r0 + 16 * tr + l16;
 #pragma unroll
-        for (int q = 0; q < RB; ++q) {
-            const int i = i0 + q;
-#pragma unroll
-            for (int u = 0; u < kTriPre; ++u) {
-                const int p = tid + 256 * u;
-                nxt[q][u] = (i < nn && p <= len + q) ? L[(long long)i * ld + c0 + p] : 0.0;
+            for (int u = 0; u < 8; ++u) {
+                const int gk = r0 + 4 * u + lq;
+                dinv[u] = (gi < nn && gk < nn) ? Xg[(long long)gi * ld + gk] : 0.f;
             }
         }
-    };
-    if (pre_ok) fetch_rows(c0);
-    for (int i0 = c0; i0 < nn; i0 += RB) {
-        const int len = i0 - c0;                   // entries L[i][c0 .. i0-1] meet solved rows
-        if (pre_ok) {
+        // S = sum_k L[ib][k] X[k][jb] over the columns c0 .. r0-1 (all below the order): tile (tr, tc)
+        double4_t acc = {0.0, 0.0, 0.0, 0.0};
+        {
+            const int gi = r0 + 16 * tr + l16;
+            const bool rok = gi < nn;
+            const double* __restrict__ lrow = L + (long long)(rok ? gi : 0) * ld + c0 + lq;
+            const int nk = r0 - c0;
+            for (int k = 0; k < nk; k += 16) {              // nk % 32 == 0: four k-steps per pass
+                double a[4];
+                float b[4];
 #pragma unroll
-            for (int q = 0; q < RB; ++q)
-#pragma unroll
-                for (int u = 0; u < kTriPre; ++u) {
-                    const int p = tid + 256 * u;
-                    if (i0 + q < nn && p <= len + q) lrow[q * lrs + p] = nxt[q][u];
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = rok ? lrow[k + 4 * u] : 0.0;
+                    const int kr = k + 4 * u + lq;           // row of the block column, from c0
+                    b[u] = XLDS ? Xs[(tc * rows + kr) * 16 + l16]
+                                : (col_ok ? Xg[(long long)(c0 + kr) * ld + col] : 0.f);
                 }
-            if (i0 + RB < nn) fetch_rows(i0 + RB);
-        } else {
 #pragma unroll
-            for (int q = 0; q < RB; ++q) {
-                const int i = i0 + q;
-                if (i < nn)
-                    for (int p = tid; p <= len + q; p += 256) lrow[q * lrs + p] = L[(long long)i * ld + c0 + p];
+                for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], (double)b[u], acc, 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Ssm[(tc * kTriNB + 16 * tr + 4 * e + lq) * 16 + l16] = acc[e];
         __syncthreads();
-        double acc[RB];
+        // X[ib][jb] = -Dinv S
+        double4_t o = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int q = 0; q < RB; ++q) acc[q] = 0.0;
-        for (int p = sub; p < len; p += S) {
-            const double xv = (double)Xs[p * CB + c];
+        for (int u = 0; u < 8; ++u)
+            o = __builtin_amdgcn_mfma_f64_16x16x4f64((double)dinv[u], Ssm[(tc * kTriNB + 4 * u + lq) * 16 + l16], o, 0, 0, 0);
 #pragma unroll
-            for (int q = 0; q < RB; ++q) acc[q] += lrow[q * lrs + p] * xv;
-        }
-#pragma unroll
-        for (int q = 0; q < RB; ++q) red[(q * S + sub) * CB + c] = acc[q];
-        __syncthreads();
-        if (sub == 0) {
-            double x[RB];
-#pragma unroll
-            for (int q = 0; q < RB; ++q) {
-                const int i = i0 + q;
-                if (i < nn) {
-                    double tot = 0.0;
-#pragma unroll
-                    for (int w = 0; w < S; ++w) tot += red[(q * S + w) * CB + c];
-#pragma unroll
-                    for (int u = 0; u < q; ++u) tot += lrow[q * lrs + len + u] * x[u];
-                    x[q] = ((i == c0 + c ? 1.0 : 0.0) - tot) / lrow[q * lrs + len + q];
-                    // the solved entry goes through float, as every later row reads it back from Xs
-                    const float xf = (float)x[q];
-                    x[q] = (double)xf;
-                    Xs[(len + q) * CB + c] = xf;
-                    if (col_ok) Xg[(long long)i * ld + c0 + c] = xf;
-                }
-            }
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * tr + 4 * e + lq;              // row inside the block
+            const float xf = (float)(-o[e]);
+            if (XLDS) Xs[(tc * rows + (r0 - c0) + i) * 16 + l16] = xf;
+            if (r0 + i < nn && col_ok) Xg[(long long)(r0 + i) * ld + col] = xf;
         }
         __syncthreads();
     }
 }
 
 hipError_t launch_tri_inverse(const MatDev* mats, int n_mats, int which, int max_order, hipStream_t stream) {
-    // column-block width: the widest whose LDS block fits
-    auto lds_for = [&](int cb) {
-        return (size_t)4 * ((max_order + 5) & ~1) * 8 + (size_t)4 * 256 * 8 + (size_t)max_order * cb * 4;
-    };
+    const int nb = (max_order + kTriNB - 1) / kTriNB;
+    if (nb <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_tri_diag_inverse, dim3((nb + 1) / 2, n_mats), dim3(64), 0, stream, mats, which);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     static bool attr_done = false;
+    constexpr size_t kBudget = 150 * 1024;
     if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<64>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<32>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse<16>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse_blocks<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBudget);
         attr_done = true;
     }
-    const size_t budget = 150 * 1024;
-    if (lds_for(64) <= budget) {
-        hipLaunchKernelGGL(k_tri_inverse<64>, dim3((max_order + 63) / 64, n_mats), dim3(256), lds_for(64), stream,
-                           mats, which);
-    } else if (lds_for(32) <= budget) {
-        hipLaunchKernelGGL(k_tri_inverse<32>, dim3((max_order + 31) / 32, n_mats), dim3(256), lds_for(32), stream,
-                           mats, which);
-    } else {
-        hipLaunchKernelGGL(k_tri_inverse<16>, dim3((max_order + 15) / 16, n_mats), dim3(256), lds_for(16), stream,
-                           mats, which);
-    }
+    const size_t s_bytes = (size_t)2 * kTriNB * 16 * sizeof(double);
+    const size_t x_bytes = (size_t)2 * nb * kTriNB * 16 * sizeof(float);
+    if (s_bytes + x_bytes <= kBudget)
+        hipLaunchKernelGGL(k_tri_inverse_blocks<true>, dim3(nb, n_mats), dim3(256), s_bytes + x_bytes, stream, mats, which);
+    else
+        hipLaunchKernelGGL(k_tri_inverse_blocks<false>, dim3(nb, n_mats), dim3(256), s_bytes, stream, mats, which);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ blocked one-sided Jacobi
-// X (lp x lp, fp64, row-major) starts as the symmetric matrix T (rows/columns >= l zero).
+// X (lp x lp, row-major) starts as the symmetric matrix T (rows/columns >= l zero).
 // Rotating ROWS until they are mutually orthogonal gives X = Lambda U^T: row i is
 // ritz_i * u_i^T.  Rows are grouped in blocks of 16; one workgroup takes a pair of blocks (a
 // "visit"): it forms the 32 x 32 Gram matrix of the 32 rows, runs one cyclic Jacobi sweep on that
@@ -425,10 +448,8 @@ __device__ __forceinline__ double wave_allreduce(double v) {
 //                      with a row in each block (16 rounds)
 //   X <- V X           fp64 MFMA, each wavefront owns 16-column tiles, written straight back to memory
 // so the 32 rows are read twice per visit instead of 2 x 31 times.
-// v_mfma_f64_16x16x4_f64: lane L supplies A[L%16][L/16] and B[L/16][L%16]; element e of its result is
-// D[4e + L/16][L%16] (checked on the device).
-typedef double double4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
+// (operand and result layout of v_mfma_f64_16x16x4_f64 as stated at the triangular inverse; checked on
+// the device)
 constexpr int kJgLdS = 36;     // row length of S and V in LDS (32 + 4: 16 rows land on distinct banks)
 constexpr int kJgParts = 8;    // wavefronts that share the Gram product (a slice of the columns each)
 

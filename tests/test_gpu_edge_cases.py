@@ -265,7 +265,14 @@ def test_bf16_projection_slot_small_and_ragged(hist, pad_g, rank_cap):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_large_rank_refresh_and_step(dtype):
-    # sketch width 608: more Jacobi block pairs than at the ranks of the benchmark layer sets, a
-    # triangular inverse that needs the narrow column blocks
+    # sketch width 608: more Jacobi block pairs and more block rows of the triangular inverse than at
+    # the ranks of the benchmark layer sets
     ls, errs = _run([(700, 900), (640, 1000)], 600, 2, dtype, 3, seed=91, k=640)
     _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "large rank " + dtype)
+
+
+def test_rank_beyond_the_lds_resident_triangular_inverse():
+    # sketch width 1208 (38 blocks of 32): a block column of the inverse Cholesky factor no longer
+    # fits in LDS, so the solved blocks are read back from global memory
+    ls, errs = _run([(1300, 1400)], 1200, 2, "f32", 2, seed=92, k=1250)
+    _assert_all(errs, TOL_F32, "rank 1200")

@@ -79,6 +79,31 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// History ring and Gram block (K, weights) of every matrix in one launch.  h_elem_bytes: 4 or 2; both
+// buffers are whole multiples of 256 bytes (the sizes the library reports for them).
+__global__ __launch_bounds__(256) void k_clear_history(const MatDev* __restrict__ mats, int s, int h_elem_bytes,
+                                                       unsigned long long k_bytes) {
+    const MatDev& md = mats[blockIdx.y];
+    const unsigned long long hb =
+        ((unsigned long long)md.slot_elems * (unsigned)h_elem_bytes * (unsigned)(s > 0 ? s : 1) + 255ull) & ~255ull;
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    uint4* __restrict__ h = reinterpret_cast<uint4*>(md.H);
+    const unsigned long long n16 = hb / 16, stride = (unsigned long long)gridDim.x * 256;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) h[i] = z;
+    if (blockIdx.x == 0) {
+        uint4* __restrict__ k = reinterpret_cast<uint4*>(md.K);
+        for (unsigned long long i = threadIdx.x; i < k_bytes / 16; i += 256) k[i] = z;
+    }
+}
+
+hipError_t launch_clear_history(const MatDev* mats, int n_mats, int s, int h_elem_bytes, size_t k_bytes,
+                                hipStream_t stream) {
+    if (n_mats <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_clear_history, dim3(128, n_mats), dim3(256), 0, stream, mats, s, h_elem_bytes,
+                       (unsigned long long)k_bytes);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ Gram row
 // One workgroup = one contiguous part of the flat r*ldn range of one matrix.
 // Products and 4-term sums in fp32, running sums in fp64, fixed reduction order.

@@ -1074,7 +1074,8 @@ struct YTLoader {
             }
         }
     }
-    // P0, P1, P2: the three plane tiles, [x][LDS_K] bf16 each
+    // P0, P1, P2: the plane tiles, [x][LDS_K] bf16 each; NP = 1 writes the leading plane only
+    template <int NP>
     __device__ __forceinline__ void store(bf16_t* P0, bf16_t* P1, bf16_t* P2, int t) const {
         const int xg = t / C::KG;
 #pragma unroll
@@ -1093,6 +1094,7 @@ struct YTLoader {
             }
             const int off = (xg * 8 + c) * C::LDS_K + kg4;
             *reinterpret_cast<u32x2_t*>(P0 + off) = (u32x2_t){h0[0] | ((unsigned)h0[1] << 16), h0[2] | ((unsigned)h0[3] << 16)};
+            if (NP == 1) continue;
             *reinterpret_cast<u32x2_t*>(P1 + off) = (u32x2_t){h1[0] | ((unsigned)h1[1] << 16), h1[2] | ((unsigned)h1[3] << 16)};
             *reinterpret_cast<u32x2_t*>(P2 + off) = (u32x2_t){h2[0] | ((unsigned)h2[1] << 16), h2[2] | ((unsigned)h2[3] << 16)};
         }
@@ -1101,7 +1103,7 @@ struct YTLoader {
 
 // One BK-deep sweep: the plain operand's fragments against the three planes'.  PA: the planes are the A
 // operand (rows of the result), else the B operand.
-template <class C, bool PA>
+template <class C, bool PA, int NP>
 __device__ __forceinline__ void mma_tile_x3(floatx16 (&acc)[C::MI][C::NJ], const bf16_t* Gs, const bf16_t* P0, int wm,
                                             int wn, int li, int h) {
     constexpr int KK = C::BK / 16, PL = C::BM * C::LDS_K;   // elements per plane tile
@@ -1114,7 +1116,7 @@ __device__ __forceinline__ void mma_tile_x3(floatx16 (&acc)[C::MI][C::NJ], const
         for (int x = 0; x < GN; ++x)
             g[x] = *reinterpret_cast<const u32x4_t*>(Gs + (grow + 32 * x) * C::LDS_K + kk * 16 + h * 8);
 #pragma unroll
-        for (int pl = 0; pl < 3; ++pl) {
+        for (int pl = 0; pl < NP; ++pl) {
             u32x4_t y[PN];
 #pragma unroll
             for (int x = 0; x < PN; ++x)
@@ -1138,12 +1140,14 @@ __device__ __forceinline__ void mma_tile_x3(floatx16 (&acc)[C::MI][C::NJ], const
 // FORM 3: C = Bm [l][ldn] = Y^T G    (Y [m][l]: planes on the A side; G through the transposing
 //                                     loader; columns >= n of C are written as zero)
 // ysrc: which sketch buffer Y is (0 Ya, 1 Yb, 2 Yc).  One 128 x 128 tile per workgroup, 64-deep
-// k-steps, register-staged loads one step ahead.
-template <class C, int FORM>
+// k-steps, register-staged loads one step ahead.  NP = 1 keeps only the leading plane of Y: for the
+// first product of a refresh, whose Y is the random test matrix (rounding its entries to bf16
+// leaves it as good a test matrix as before).
+template <class C, int FORM, int NP>
 __global__ __launch_bounds__(C::NT) void k_refresh_x3(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
                                                       int ysrc) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    static_assert(FORM >= 1 && FORM <= 3, "product form");
+    static_assert(FORM >= 1 && FORM <= 3 && (NP == 1 || NP == 3), "product form");
     const MatDev& md = mats[blockIdx.z];
     if (md.side == NG_SIDE_RIGHT) return;
     const MatDyn dy = dyn[blockIdx.z];
@@ -1190,7 +1194,7 @@ __global__ __launch_bounds__(C::NT) void k_refresh_x3(const MatDev* __restrict__
         }
     };
     auto stores = [&]() {
-        ly.store(P0, P1, P2, t);
+        ly.template store<NP>(P0, P1, P2, t);
         if (FORM == 1) lgk.store(Gs, t);
         else if (full) lgt.template store<true>(Gs, t);
         else lgt.template store<false>(Gs, t);
@@ -1200,7 +1204,7 @@ __global__ __launch_bounds__(C::NT) void k_refresh_x3(const MatDev* __restrict__
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) loads((kt + 1) * C::BK);
-        mma_tile_x3<C, FORM == 3>(acc, Gs, P0, wm, wn, li, h);
+        mma_tile_x3<C, FORM == 3, NP>(acc, Gs, P0, wm, wn, li, h);
         __syncthreads();
         if (kt + 1 < nk) stores();
         __syncthreads();
@@ -1316,24 +1320,27 @@ void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
     }
 }
 
-hipError_t launch_refresh_x3(int form, int ysrc, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m,
-                             int max_n, hipStream_t stream) {
+hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
+                             int max_m, int max_n, hipStream_t stream) {
     typedef Cfg0 C;
-    constexpr int lds = (C::BN + 3 * C::BM) * C::LDS_K * 2;
+    constexpr int lds = (C::BN + 3 * C::BM) * C::LDS_K * 2, lds1 = (C::BN + C::BM) * C::LDS_K * 2;
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 1>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 1, 3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 2>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 2, 3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 3>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 3, 3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr = true;
     }
     dim3 g((max_n + C::BN - 1) / C::BN, (max_m + C::BM - 1) / C::BM, n_mats);
-    if (form == 1) hipLaunchKernelGGL((k_refresh_x3<C, 1>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
-    else if (form == 2) hipLaunchKernelGGL((k_refresh_x3<C, 2>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
-    else if (form == 3) hipLaunchKernelGGL((k_refresh_x3<C, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    if (form == 1 && planes == 1)
+        hipLaunchKernelGGL((k_refresh_x3<C, 1, 1>), g, dim3(C::NT), lds1, stream, mats, dyn, ysrc);
+    else if (planes != 3) return hipErrorInvalidValue;
+    else if (form == 1) hipLaunchKernelGGL((k_refresh_x3<C, 1, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    else if (form == 2) hipLaunchKernelGGL((k_refresh_x3<C, 2, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
+    else if (form == 3) hipLaunchKernelGGL((k_refresh_x3<C, 3, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -288,10 +288,9 @@ StepScalars make_scalars(const ng_state* st, float lr) {
 }
 
 int clear_history(ng_state* st, hipStream_t stream) {
-    for (int i = 0; i < st->n_mats; ++i) {
-        NG_HIP(launch_fill_zero(st->bufs[i].buf[NG_BUF_H], st->plan.sz[i].bytes[NG_BUF_H], stream));
-        NG_HIP(launch_fill_zero(st->bufs[i].buf[NG_BUF_K], st->plan.sz[i].bytes[NG_BUF_K], stream));
-    }
+    if (st->n_mats == 0) return NG_OK;
+    NG_HIP(launch_clear_history(st->d_mats, st->n_mats, st->hp.s, hist_is_bf16(st->hp) ? 2 : 4,
+                                st->plan.sz[0].bytes[NG_BUF_K], stream));
     return NG_OK;
 }
 
@@ -301,9 +300,9 @@ int clear_history(ng_state* st, hipStream_t stream) {
 int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc);
 int gradient_product(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
     if (st->hp.grad_dtype == NG_BF16 && !(st->sides & 2)) {
-        int form = 0, ysrc = 0;
+        int form = 0, ysrc = 0, planes = 3;
         switch (op) {
-            case OP_G_B2A: form = 1; ysrc = 1; break;
+            case OP_G_B2A: form = 1; ysrc = 1; planes = 1; break;   // Y is the random test matrix
             case OP_G_C2A: form = 1; ysrc = 2; break;
             case OP_GT_A2B: form = 2; ysrc = 0; break;
             case OP_GT_C2B: form = 2; ysrc = 2; break;
@@ -311,7 +310,7 @@ int gradient_product(ng_state* st, GemmOp op, hipStream_t stream, const StepScal
             default: break;
         }
         if (form != 0) {
-            NG_HIP(launch_refresh_x3(form, ysrc, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], stream));
+            NG_HIP(launch_refresh_x3(form, ysrc, planes, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], stream));
             return NG_OK;
         }
     }

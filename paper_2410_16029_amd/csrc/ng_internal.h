@@ -106,6 +106,9 @@ __host__ __device__ inline bool projection_tile_direct(int n) { return n >= 8; }
 hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, const MatDev* mats,
                              hipStream_t stream);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);   // bytes % 4 == 0
+// zero the history ring and the Gram block of every matrix (buffer sizes as ng_query_sizes reports them)
+hipError_t launch_clear_history(const MatDev* mats, int n_mats, int s, int h_elem_bytes, size_t k_bytes,
+                                hipStream_t stream);
 
 // fp32 MFMA grouped GEMM with selectable operands (k_gemm_f32.hip)
 enum GemmOp {
@@ -154,9 +157,10 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
 
 // Refresh products of a bf16 gradient with an fp32 sketch matrix Y as three bf16 MFMA products (left side).
 // form 1: Ya = G Y, form 2: Yb = G^T Y, form 3: Bm = Y^T G; ysrc: Y is 0 Ya, 1 Yb, 2 Yc;
-// max_m / max_n: largest row / column count of the result over the layer set
-hipError_t launch_refresh_x3(int form, int ysrc, const MatDev* mats, const MatDyn* dyn, int n_mats, int max_m,
-                             int max_n, hipStream_t stream);
+// planes: 3, or 1 (form 1 only: Y rounded to bf16); max_m / max_n: largest row / column count of
+// the result over the layer set
+hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
+                             int max_m, int max_n, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 // row_override >= 0: the Gram row of that slot instead of the step's head (history carry-over);

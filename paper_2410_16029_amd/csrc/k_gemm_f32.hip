@@ -28,6 +28,8 @@ struct GemmView {
     int a_bf16, b_bf16;
     int epi;
     int b_tri;        // B(k, j) = 0 for k > j (the transposed inverse Cholesky factor): a tile stops at its last column
+    int sym;          // C = X^T X (fp64): only tiles on or below the diagonal are computed, each as two halves of
+                      // the contraction added into a zeroed C
 };
 
 __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const MatDyn* dy, int grad_dtype,
@@ -37,6 +39,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
     v.b_bf16 = 0;
     v.epi = EPI_F32;
     v.b_tri = 0;
+    v.sym = 0;
     const int gb = (grad_dtype == NG_BF16) ? 1 : 0;
     const void* G = dy ? dy->g : nullptr;
     // Strides of the m x n matrix the kernels see inside the caller's row-major gradient: for the
@@ -86,7 +89,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.B = Y; v.sBk = md.l; v.sBj = 1;
             v.M = md.l; v.N = md.l; v.Nvalid = md.l;
             v.K = (op == OP_GRAM_A || op == OP_GRAM_CA) ? md.m : md.n;
-            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64;
+            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64; v.sym = 1;
             break;
         }
         case OP_APPLY_A2C:
@@ -112,7 +115,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.A = md.Bm; v.sAi = md.ldn; v.sAk = 1;
             v.B = md.Bm; v.sBk = 1; v.sBj = md.ldn;
             v.M = md.l; v.N = md.l; v.Nvalid = md.l; v.K = md.n;
-            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64;
+            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64; v.sym = 1;
             break;
         case OP_ROTATE:   // P = Ya * Urot, Urot (l x r, float) staged in Bm
             v.A = md.Ya; v.sAi = md.l; v.sAk = 1;
@@ -124,7 +127,7 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.A = md.P; v.sAi = 1; v.sAk = md.r;
             v.B = md.P; v.sBk = md.r; v.sBj = 1;
             v.M = md.r; v.N = md.r; v.Nvalid = md.r; v.K = md.m;
-            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64;
+            v.C = md.T; v.ldc = md.lp; v.epi = EPI_F64; v.sym = 1;
             break;
         case OP_T_CARRY:   // change of basis T = P_new^T P_old, P_old saved in Yc
             v.A = md.P; v.sAi = 1; v.sAk = md.r;
@@ -236,19 +239,45 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
     // each XCD works through a contiguous run of the matrix's tiles (the column tiles of one row tile
     // share the rows of A through that XCD's L2).
     const int nxm = (v.N + TS - 1) / TS, nym = (v.M + TS - 1) / TS;   // this matrix's own tiles
-    const int per = (nxm * nym + 7) / 8;
+    // symmetric results: nym (nym + 1) / 2 tiles, two work items each (the halves of the contraction)
+    const int items = v.sym ? nym * (nym + 1) : nxm * nym;
+    const int per = (items + 7) / 8;
     const int slot = (int)(blockIdx.x / 8);
-    const int tile = (int)(blockIdx.x % 8) * per + slot;
-    if (slot >= per || tile >= nxm * nym) return;
-    const int i0 = (tile / nxm) * TS, j0 = (tile % nxm) * TS;
+    int tile = (int)(blockIdx.x % 8) * per + slot;
+    if (slot >= per || tile >= items) return;
+    int i0, j0;
+    const NG_AS1 void* Ap = (const NG_AS1 void*)v.A;
+    const NG_AS1 void* Bp = (const NG_AS1 void*)v.B;
+    if (v.sym) {
+        const int half = tile & 1;
+        tile >>= 1;
+        int ti = 0;
+        while (tile >= ti + 1) {      // row ti of the triangle holds ti + 1 tiles
+            tile -= ti + 1;
+            ++ti;
+        }
+        i0 = ti * TS;
+        j0 = tile * TS;
+        // second half: the operands start kh further along the contraction
+        const int kh = ((v.K + 1) / 2 + BK - 1) / BK * BK;
+        if (half) {
+            if (kh >= v.K) return;
+            Ap = (const NG_AS1 unsigned char*)Ap + (long long)kh * v.sAk * (ABF ? 2 : 4);
+            Bp = (const NG_AS1 unsigned char*)Bp + (long long)kh * v.sBk * (BBF ? 2 : 4);
+            v.K -= kh;
+        } else if (kh < v.K) {
+            v.K = kh;
+        }
+    } else {
+        i0 = (tile / nxm) * TS;
+        j0 = (tile % nxm) * TS;
+    }
     if (v.b_tri && j0 + TS < v.K) v.K = j0 + TS;   // rows k > j of B are zero
 
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
     const int wm = wv >> 1, wn = wv & 1;
     const int li = lane & 31, h = lane >> 5;
-    const NG_AS1 void* Ap = (const NG_AS1 void*)v.A;
-    const NG_AS1 void* Bp = (const NG_AS1 void*)v.B;
 
     // loader mappings: vector q of this thread covers 4 consecutive positions of the stride-1
     // dimension.  tile-fast: positions 4 (t % TPR) of the tile index at k = t / TPR + (256 / TPR) q;
@@ -432,7 +461,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
                         if (v.epi == EPI_F32) {
                             reinterpret_cast<float*>(v.C)[idx] = x;
                         } else if (v.epi == EPI_F64) {
-                            reinterpret_cast<double*>(v.C)[idx] = (double)x;
+                            // two addends onto zero: the same sum in either order
+                            if (v.sym) unsafeAtomicAdd(reinterpret_cast<double*>(v.C) + idx, (double)x);
+                            else reinterpret_cast<double*>(v.C)[idx] = (double)x;
                         } else {
                             float* W = reinterpret_cast<float*>(v.C);
                             const float w = W[idx];
@@ -444,14 +475,23 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int op, const MatDev* __restri
         }
 }
 
+// T (lp x lp doubles) of every matrix, the target of the symmetric products
+__global__ __launch_bounds__(256) void k_zero_sym_result(const MatDev* __restrict__ mats) {
+    const MatDev& md = mats[blockIdx.y];
+    const long long total = (long long)md.lp * md.lp;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256)
+        md.T[q] = 0.0;
+}
+
 // max_m, max_n, max_k: the largest dimensions of this product over the layer set.  The 128 tile is used
 // when neither side nor the contraction is short (a short side wastes most of a big tile, a short
 // contraction leaves only the read-modify-write of the output, which wants many small workgroups).
 template <int TS, int BK>
 static void run_gemm_f32(dim3 g, int op, const MatDev* mats, const MatDyn* dyn, int grad_dtype, StepScalars sc,
-                         const void* zero16, bool a_bf16, bool b_bf16, hipStream_t stream) {
+                         const void* zero16, bool a_bf16, bool b_bf16, bool sym, hipStream_t stream) {
     const int nx = (int)g.x, ny = (int)g.y;
-    const dim3 g1((unsigned)((nx * ny + 7) / 8 * 8), 1, g.z);
+    const int items = sym ? ny * (ny + 1) : nx * ny;
+    const dim3 g1((unsigned)((items + 7) / 8 * 8), 1, g.z);
     if (a_bf16)
         k_gemm_f32<TS, BK, true, false><<<g1, dim3(256), 0, stream>>>(op, mats, dyn, grad_dtype, sc, zero16, nx, ny);
     else if (b_bf16)
@@ -468,8 +508,11 @@ hipError_t launch_gemm_f32(GemmOp op, const MatDev* mats, const MatDyn* dyn, int
     // which operand is stored as bf16 is a property of the product (the same for every matrix)
     const MatDev probe{};
     const GemmView v = gemm_view((int)op, probe, nullptr, grad_dtype, sc.slot, sc.hist_bf16);
-    if (big) run_gemm_f32<128, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, stream);
-    else run_gemm_f32<64, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, stream);
+    if (v.sym) {   // the halves of the contraction are added into C
+        hipLaunchKernelGGL(k_zero_sym_result, dim3(32, n_mats), dim3(256), 0, stream, mats);
+    }
+    if (big) run_gemm_f32<128, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, v.sym != 0, stream);
+    else run_gemm_f32<64, 16>(g, (int)op, mats, dyn, grad_dtype, sc, zero16, v.a_bf16, v.b_bf16, v.sym != 0, stream);
     return hipGetLastError();
 }
 

@@ -405,7 +405,9 @@ __global__ __launch_bounds__(256) void k_jacobi_prepare(const MatDev* __restrict
     float* __restrict__ X = jacobi_rows(md);
     for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long long)gridDim.x * 256) {
         const int i = (int)(q / lp), j = (int)(q % lp);
-        X[q] = (i < l && j < l) ? (float)md.T[q] : 0.f;
+        // (the product that made T wrote only its tiles on and below the diagonal)
+        const long long src = i >= j ? q : (long long)j * lp + i;
+        X[q] = (i < l && j < l) ? (float)md.T[src] : 0.f;
     }
     if (blockIdx.x == 0 && threadIdx.x < 4) md.jflag[threadIdx.x] = 0;
 }

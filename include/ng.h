@@ -50,7 +50,9 @@ enum { NG_ADAM_STANDARD = 0, NG_ADAM_PRINTED = 1 };
 enum {
     NG_OK = 0,
     NG_ERR_INVALID_ARG = -1,   /* null pointer, bad index, bad count                  */
-    NG_ERR_SHAPE = -2,         /* m,n,r <= 0, r > min(m,n), ld < n, s out of range    */
+    NG_ERR_SHAPE = -2,         /* m,n,r <= 0, r > min(m,n), ld < n, s out of range,
+                                  r + refresh_oversample > 2048, m or n > 2^24, a weight
+                                  or gradient of 2 GiB or more (m * ld * 4 bytes)       */
     NG_ERR_DTYPE = -3,         /* unknown grad_dtype / adam_mode                      */
     NG_ERR_HPARAM = -4,        /* lambda <= 0, beta outside [0,1), eps <= 0, ...      */
     NG_ERR_NO_PROJECTOR = -5,  /* ng_step before any refresh / commit                 */

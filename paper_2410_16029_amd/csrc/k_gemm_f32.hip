@@ -73,10 +73,9 @@ __host__ __device__ inline GemmView gemm_view(int op, const MatDev& md, const Ma
             v.M = md.m; v.N = md.l; v.Nvalid = md.l; v.K = md.n;
             v.C = md.Ya; v.ldc = md.l;
             break;
-        case OP_GT_A2B:
         case OP_GT_C2B:
             v.A = G; v.sAi = g_col; v.sAk = g_row; v.a_bf16 = gb;
-            v.B = (op == OP_GT_A2B) ? md.Ya : md.Yc; v.sBk = md.l; v.sBj = 1;
+            v.B = md.Yc; v.sBk = md.l; v.sBj = 1;
             v.M = md.n; v.N = md.l; v.Nvalid = md.l; v.K = md.m;
             v.C = md.Yb; v.ldc = md.l;
             break;

@@ -49,7 +49,7 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
         if (x.ld_w < x.n || x.ld_g < x.n) return NG_ERR_SHAPE;
         if (x.side != NG_SIDE_LEFT && x.side != NG_SIDE_RIGHT) return NG_ERR_INVALID_ARG;
         if ((long long)x.m > (1 << 24) || (long long)x.n > (1 << 24)) return NG_ERR_SHAPE;
-        if ((long long)x.r + hp->refresh_oversample > 2048) return NG_ERR_SHAPE;   // LDS budget of the Jacobi blocks
+        if ((long long)x.r + hp->refresh_oversample > 2048) return NG_ERR_SHAPE;   // widest sketch the refresh is specified for
         // the kernels address one matrix with 32-bit offsets
         const long long ldmax = x.ld_w > x.ld_g ? x.ld_w : x.ld_g;
         if ((long long)x.m * ldmax * 4 >= (1LL << 31)) return NG_ERR_SHAPE;
@@ -294,8 +294,8 @@ int clear_history(ng_state* st, hipStream_t stream) {
     return NG_OK;
 }
 
-// The refresh's products with the gradient: OP_G_B2A / OP_G_C2A (Ya = G Y), OP_GT_A2B / OP_GT_C2B
-// (Yb = G^T Y), OP_QT_G (Bm = Ya^T G).  bf16 gradients on the left side take three bf16 MFMA
+// The refresh's products with the gradient: OP_G_B2A / OP_G_C2A (Ya = G Y), OP_GT_C2B (Yb = G^T Y),
+// OP_QT_G (Bm = Ya^T G).  bf16 gradients on the left side take three bf16 MFMA
 // products (launch_refresh_x3), everything else the fp32 GEMM.
 int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc);
 int gradient_product(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
@@ -304,7 +304,6 @@ int gradient_product(ng_state* st, GemmOp op, hipStream_t stream, const StepScal
         switch (op) {
             case OP_G_B2A: form = 1; ysrc = 1; planes = 1; break;   // Y is the random test matrix
             case OP_G_C2A: form = 1; ysrc = 2; break;
-            case OP_GT_A2B: form = 2; ysrc = 0; break;
             case OP_GT_C2B: form = 2; ysrc = 2; break;
             case OP_QT_G: form = 3; ysrc = 0; break;
             default: break;

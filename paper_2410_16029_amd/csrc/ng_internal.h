@@ -115,9 +115,8 @@ enum GemmOp {
     OP_PROJECT_F32 = 0,   // R(slot head) = P^T G                     (step, NG_F32)
     OP_UPDATE_F32,        // W -= lr*(scale * P N + wd W)             (step, NG_F32)
     OP_G_B2A,             // Ya = G Yb     (m x l)
-    OP_GT_A2B,            // Yb = G^T Ya   (n x l)
     OP_G_C2A,             // Ya = G Yc
-    OP_GT_C2B,            // Yb = G^T Yc
+    OP_GT_C2B,            // Yb = G^T Yc   (n x l)
     OP_GRAM_A,            // T = Ya^T Ya   (rows m) -> double
     OP_GRAM_B,            // T = Yb^T Yb   (rows n)
     OP_GRAM_CA,           // T = Yc^T Yc   (rows m)

@@ -1074,7 +1074,7 @@ struct YTLoader {
             }
         }
     }
-    // P0, P1, P2: the plane tiles, [x][LDS_K] bf16 each; NP = 1 writes the leading plane only
+    // P0, P1, P2: the plane tiles, [x][LDS_K] bf16 each; only the leading NP planes are written
     template <int NP>
     __device__ __forceinline__ void store(bf16_t* P0, bf16_t* P1, bf16_t* P2, int t) const {
         const int xg = t / C::KG;
@@ -1096,6 +1096,7 @@ struct YTLoader {
             *reinterpret_cast<u32x2_t*>(P0 + off) = (u32x2_t){h0[0] | ((unsigned)h0[1] << 16), h0[2] | ((unsigned)h0[3] << 16)};
             if (NP == 1) continue;
             *reinterpret_cast<u32x2_t*>(P1 + off) = (u32x2_t){h1[0] | ((unsigned)h1[1] << 16), h1[2] | ((unsigned)h1[3] << 16)};
+            if (NP == 2) continue;
             *reinterpret_cast<u32x2_t*>(P2 + off) = (u32x2_t){h2[0] | ((unsigned)h2[1] << 16), h2[2] | ((unsigned)h2[3] << 16)};
         }
     }
@@ -1140,14 +1141,16 @@ __device__ __forceinline__ void mma_tile_x3(floatx16 (&acc)[C::MI][C::NJ], const
 // FORM 3: C = Bm [l][ldn] = Y^T G    (Y [m][l]: planes on the A side; G through the transposing
 //                                     loader; columns >= n of C are written as zero)
 // ysrc: which sketch buffer Y is (0 Ya, 1 Yb, 2 Yc).  One 128 x 128 tile per workgroup, 64-deep
-// k-steps, register-staged loads one step ahead.  NP = 1 keeps only the leading plane of Y: for the
+// k-steps, register-staged loads one step ahead.  NP: planes of Y that enter the product.  1 for the
 // first product of a refresh, whose Y is the random test matrix (rounding its entries to bf16
-// leaves it as good a test matrix as before).
+// leaves it as good a test matrix as before); 2 (16 significant bits) for the products inside the
+// subspace iteration, whose results are re-orthonormalised and multiplied again; 3 for the last
+// basis and for B = Q^T G, which the Rayleigh-Ritz step takes at face value.
 template <class C, int FORM, int NP>
 __global__ __launch_bounds__(C::NT) void k_refresh_x3(const MatDev* __restrict__ mats, const MatDyn* __restrict__ dyn,
                                                       int ysrc) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    static_assert(FORM >= 1 && FORM <= 3 && (NP == 1 || NP == 3), "product form");
+    static_assert(FORM >= 1 && FORM <= 3 && NP >= 1 && NP <= 3, "product form");
     const MatDev& md = mats[blockIdx.z];
     if (md.side == NG_SIDE_RIGHT) return;
     const MatDyn dy = dyn[blockIdx.z];
@@ -1320,29 +1323,31 @@ void bf16_tile_shape(int which, int max_r, int* bm, int* bn) {
     }
 }
 
-hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
-                             int max_m, int max_n, hipStream_t stream) {
+template <int FORM, int NP>
+static hipError_t run_refresh_x3(dim3 g, const MatDev* mats, const MatDyn* dyn, int ysrc, hipStream_t stream) {
     typedef Cfg0 C;
-    constexpr int lds = (C::BN + 3 * C::BM) * C::LDS_K * 2, lds1 = (C::BN + C::BM) * C::LDS_K * 2;
+    constexpr int lds = (C::BN + NP * C::BM) * C::LDS_K * 2;
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 1, 3>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 2, 3>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, 3, 3>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_refresh_x3<C, FORM, NP>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr = true;
     }
-    dim3 g((max_n + C::BN - 1) / C::BN, (max_m + C::BM - 1) / C::BM, n_mats);
-    if (form == 1 && planes == 1)
-        hipLaunchKernelGGL((k_refresh_x3<C, 1, 1>), g, dim3(C::NT), lds1, stream, mats, dyn, ysrc);
-    else if (planes != 3) return hipErrorInvalidValue;
-    else if (form == 1) hipLaunchKernelGGL((k_refresh_x3<C, 1, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
-    else if (form == 2) hipLaunchKernelGGL((k_refresh_x3<C, 2, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
-    else if (form == 3) hipLaunchKernelGGL((k_refresh_x3<C, 3, 3>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
-    else return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_refresh_x3<C, FORM, NP>), g, dim3(C::NT), lds, stream, mats, dyn, ysrc);
     return hipGetLastError();
+}
+
+hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
+                             int max_m, int max_n, hipStream_t stream) {
+    typedef Cfg0 C;
+    const dim3 g((max_n + C::BN - 1) / C::BN, (max_m + C::BM - 1) / C::BM, n_mats);
+    if (form == 1 && planes == 1) return run_refresh_x3<1, 1>(g, mats, dyn, ysrc, stream);
+    if (form == 1 && planes == 2) return run_refresh_x3<1, 2>(g, mats, dyn, ysrc, stream);
+    if (form == 1 && planes == 3) return run_refresh_x3<1, 3>(g, mats, dyn, ysrc, stream);
+    if (form == 2 && planes == 2) return run_refresh_x3<2, 2>(g, mats, dyn, ysrc, stream);
+    if (form == 2 && planes == 3) return run_refresh_x3<2, 3>(g, mats, dyn, ysrc, stream);
+    if (form == 3 && planes == 3) return run_refresh_x3<3, 3>(g, mats, dyn, ysrc, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace ng

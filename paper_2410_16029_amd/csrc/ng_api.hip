@@ -298,14 +298,16 @@ int clear_history(ng_state* st, hipStream_t stream) {
 // OP_QT_G (Bm = Ya^T G).  bf16 gradients on the left side take three bf16 MFMA
 // products (launch_refresh_x3), everything else the fp32 GEMM.
 int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc);
-int gradient_product(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
+int gradient_product(ng_state* st, GemmOp op, bool last, hipStream_t stream, const StepScalars& sc) {
     if (st->hp.grad_dtype == NG_BF16 && !(st->sides & 2)) {
-        int form = 0, ysrc = 0, planes = 3;
+        // planes of the sketch that enter: the random test matrix needs one, the last basis and
+        // B = Q^T G all three, the products inside the subspace iteration two
+        int form = 0, ysrc = 0, planes = last ? 3 : 2;
         switch (op) {
-            case OP_G_B2A: form = 1; ysrc = 1; planes = 1; break;   // Y is the random test matrix
+            case OP_G_B2A: form = 1; ysrc = 1; planes = 1; break;
             case OP_G_C2A: form = 1; ysrc = 2; break;
             case OP_GT_C2B: form = 2; ysrc = 2; break;
-            case OP_QT_G: form = 3; ysrc = 0; break;
+            case OP_QT_G: form = 3; ysrc = 0; planes = 3; break;
             default: break;
         }
         if (form != 0) {
@@ -603,17 +605,17 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     NG_HIP(launch_fill_gaussian(st->d_mats, st->n_mats, st->max_n, st->hp.seed,
                                 (unsigned long long)st->n_refresh[0], stream));
     const int q = st->hp.refresh_power_iters;
-    if ((rc = gradient_product(st, OP_G_B2A, stream, sc)) != NG_OK) return rc;
+    if ((rc = gradient_product(st, OP_G_B2A, q == 0, stream, sc)) != NG_OK) return rc;
     if ((rc = orthonormalise(st, true, q == 0, stream, sc)) != NG_OK) return rc;
     for (int it = 0; it < q; ++it) {
         // intermediate bases live in Yc (single-pass orthonormalisation)
-        if ((rc = gradient_product(st, OP_GT_C2B, stream, sc)) != NG_OK) return rc;
+        if ((rc = gradient_product(st, OP_GT_C2B, false, stream, sc)) != NG_OK) return rc;
         if ((rc = orthonormalise(st, false, false, stream, sc)) != NG_OK) return rc;
-        if ((rc = gradient_product(st, OP_G_C2A, stream, sc)) != NG_OK) return rc;
+        if ((rc = gradient_product(st, OP_G_C2A, it + 1 == q, stream, sc)) != NG_OK) return rc;
         if ((rc = orthonormalise(st, true, it + 1 == q, stream, sc)) != NG_OK) return rc;
     }
     // Rayleigh-Ritz: B = Q^T G, T = B B^T = U diag(ritz^2) U^T, P = Q U[:, top r]
-    if ((rc = gradient_product(st, OP_QT_G, stream, sc)) != NG_OK) return rc;
+    if ((rc = gradient_product(st, OP_QT_G, true, stream, sc)) != NG_OK) return rc;
     if ((rc = gemm(st, OP_B_BT, stream, sc)) != NG_OK) return rc;
     NG_HIP(launch_jacobi_prepare(st->d_mats, st->n_mats, stream));
     for (int sw = 0; sw < st->hp.refresh_sweeps; ++sw) {

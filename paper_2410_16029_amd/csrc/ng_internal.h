@@ -156,8 +156,8 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
 
 // Refresh products of a bf16 gradient with an fp32 sketch matrix Y as three bf16 MFMA products (left side).
 // form 1: Ya = G Y, form 2: Yb = G^T Y, form 3: Bm = Y^T G; ysrc: Y is 0 Ya, 1 Yb, 2 Yc;
-// planes: 3, or 1 (form 1 only: Y rounded to bf16); max_m / max_n: largest row / column count of
-// the result over the layer set
+// planes: how many of Y's three bf16 planes enter (1: form 1 only; 2: forms 1 and 2; 3: any form);
+// max_m / max_n: largest row / column count of the result over the layer set
 hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
                              int max_m, int max_n, hipStream_t stream);
 

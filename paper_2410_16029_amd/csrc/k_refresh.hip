@@ -1,13 +1,14 @@
 // Small dense linear algebra of the projector refresh (paper Sec. 1: P = leading
 // left singular vectors of the gradient, recomputed every ~200 steps).  The
-// large products run on the grouped fp32 MFMA GEMM; this file holds what sits
-// between them, one launch for all matrices of the layer set:
+// large products run on the grouped fp32 MFMA GEMM (or, for bf16 gradients, on the
+// split-sketch bf16 MFMA kernel); this file holds what sits between them, one launch for all matrices of the layer set:
 //
 //   k_fill_gaussian     random sketch Omega (counter-based generator, Box-Muller)
 //   k_chol_*            T = L L^T in place (fp64, right-looking, panels of 32 columns)
-//   k_tri_inverse       Linv = L^{-1} as float (the GEMM then applies X <- X Linv^T)
+//   k_tri_*             Linv = L^{-1} as float, by 32 x 32 blocks (the GEMM then applies X <- X Linv^T)
 //   k_jacobi_*          blocked one-sided Jacobi on the rows of the l x l Rayleigh-Ritz matrix
-//                       T = (Q^T G)(Q^T G)^T: at convergence row i = ritz_i * u_i^T
+//                       T = (Q^T G)(Q^T G)^T (a float copy in the Linv buffer): at convergence
+//                       row i = ritz_i * u_i^T
 //   k_ritz_sort / k_build_rotation   order by descending Ritz value, stage U[:, top r]
 //   k_sign_fix          copy the orthonormalised basis into P, largest-magnitude entry of each
 //                       column made positive

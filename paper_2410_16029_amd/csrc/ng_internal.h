@@ -50,7 +50,8 @@ struct MatDev {
     float* Yc;        // [max(m,n)][l]
     float* Bm;        // [l][ldn]   B = Q^T G; later the l x r rotation
     double* T;        // [lp][lp]   Gram / Cholesky factor / Rayleigh-Ritz matrix
-    float* Linv;      // [lp][lp]   inverse Cholesky factor (float)
+    float* Linv;      // [lp][lp]   inverse Cholesky factor (float); during the Rayleigh-Ritz step the rows
+                      //            that the Jacobi rotates
     double* ritz;     // [lp]
     int* order;       // [lp]
     int* jflag;       // [0] rotations this sweep, [1] converged

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libng.so")
-SOURCES = ["ng_api.hip", "k_elementwise.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_refresh.hip"]
+SOURCES = ["ng_api.hip", "k_elementwise.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_refresh.hip", "k_skinny.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

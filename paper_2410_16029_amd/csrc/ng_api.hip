@@ -24,7 +24,7 @@ struct Sizes {   // per-matrix derived sizes
     size_t k_gram_off, k_w64_off, k_w32_off;
     size_t aux_pb_off, aux_pbt_off;
     // refresh scratch
-    size_t ws_y, ws_bm, ws_t, ws_linv, ws_ritz, ws_order, ws_flag, ws_parts, ws_carry;
+    size_t ws_y, ws_bm, ws_t, ws_linv, ws_ritz, ws_order, ws_flag, ws_parts, ws_carry, ws_skinny;
 };
 
 int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
@@ -71,7 +71,8 @@ ng_matrix_desc effective(const ng_matrix_desc& u) {
     return d;
 }
 
-void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
+// skinny_rk: 0, or the rank class (4, 8, 16) of a layer set that takes the small-rank kernels
+void derive(const ng_matrix_desc& user, const ng_hparams& hp, int skinny_rk, Sizes* z) {
     const ng_matrix_desc d = effective(user);
     memset(z, 0, sizeof(*z));
     const int s = hp.s;
@@ -116,14 +117,16 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, Sizes* z) {
     z->ws_flag = 256;
     z->ws_carry = hp.carry_history ? align_up(rn * 4, 256) : 0;
     z->ws_parts = align_up((size_t)kDotPartsMax * (s > 0 ? s : 1) * 8, 256);
+    z->ws_skinny = skinny_rk ? align_up((size_t)ceil_div(d.m, kSkinnyRows) * skinny_rk * z->ldn * 4, 256) : 0;
 }
 
 // Tables that live at the front of the workspace.
 struct Plan {
     std::vector<Sizes> sz;
-    std::vector<TileRef> proj, upd, dots, patches;
+    std::vector<TileRef> proj, upd, dots, patches, skinny;
+    int skinny_rk;                              // 0: the MFMA / fp32-GEMM projection and update
     int proj_direct, proj_staged, proj_right;   // lengths of the three runs of proj
-    size_t off_status, off_mats, off_dyn, off_tail8, off_proj, off_upd, off_dots, off_patches, off_scratch;
+    size_t off_status, off_mats, off_dyn, off_tail8, off_proj, off_upd, off_dots, off_patches, off_skinny, off_scratch;
     size_t total;
 };
 
@@ -151,10 +154,19 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     std::vector<TileRef> proj_direct, proj_staged, proj_right, upd;
     p->dots.clear();
     p->patches.clear();
+    p->skinny.clear();
+    // fp32 gradients, ranks far below an MFMA tile, all matrices on the left side: the vector-ALU
+    // projection and update
+    bool all_left = true;
+    for (int i = 0; i < n_mats; ++i) all_left = all_left && d[i].side == NG_SIDE_LEFT;
+    p->skinny_rk = (hp.grad_dtype == NG_F32 && all_left && max_r <= kSkinnyMaxRank) ? (max_r <= 4 ? 4 : max_r <= 8 ? 8 : 16) : 0;
     for (int i = 0; i < n_mats; ++i) {
-        derive(d[i], hp, &p->sz[i]);
+        derive(d[i], hp, p->skinny_rk, &p->sz[i]);
         const Sizes& z = p->sz[i];
-        if (hp.grad_dtype == NG_BF16) {
+        if (p->skinny_rk) {
+            for (int ti = 0; ti < ceil_div(d[i].m, kSkinnyRows); ++ti)
+                for (int tj = 0; tj < ceil_div(z.ldn, kSkinnyCols); ++tj) p->skinny.push_back(TileRef{i, ti, tj, 0});
+        } else if (hp.grad_dtype == NG_BF16) {
             const bool direct = d[i].side != NG_SIDE_RIGHT && projection_tile_direct(effective(d[i]).n);
             std::vector<TileRef>& run = direct ? proj_direct : d[i].side == NG_SIDE_RIGHT ? proj_right : proj_staged;
             const int bm = direct ? pbm : sbm, bn = direct ? pbn : sbn;
@@ -190,11 +202,12 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     p->off_upd = off;    off += align_up(sizeof(TileRef) * p->upd.size(), 256);
     p->off_dots = off;   off += align_up(sizeof(TileRef) * (size_t)n_mats * kDotPartsMax, 256);
     p->off_patches = off; off += align_up(sizeof(TileRef) * p->patches.size(), 256);
+    p->off_skinny = off;  off += align_up(sizeof(TileRef) * p->skinny.size(), 256);
     p->off_scratch = off;
     for (int i = 0; i < n_mats; ++i) {
         const Sizes& z = p->sz[i];
         off += z.ws_parts + 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag +
-               z.ws_carry;
+               z.ws_carry + z.ws_skinny;
     }
     p->total = off;
 }
@@ -217,9 +230,9 @@ struct ng_state {
     MatDev* d_mats;
     MatDyn* d_dyn;
     int* d_status;
-    TileRef *d_proj, *d_upd, *d_dots, *d_patches;
+    TileRef *d_proj, *d_upd, *d_dots, *d_patches, *d_skinny;
     int n_dots;
-    int max_m, max_n, max_r, max_l, max_lp, max_rows;
+    int max_m, max_n, max_r, max_l, max_lp, max_rows, max_ldn;
     int max_ti[OP_COUNT], max_tj[OP_COUNT], max_tk[OP_COUNT];   // largest M, N, K of each fp32 product
     int max_jpairs;
     int sides;       // bit 0: left-side matrices present, bit 1: right-side ones
@@ -461,11 +474,12 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         st->d_upd = (TileRef*)(ws + pl.off_upd);
         st->d_dots = (TileRef*)(ws + pl.off_dots);
         st->d_patches = (TileRef*)(ws + pl.off_patches);
+        st->d_skinny = (TileRef*)(ws + pl.off_skinny);
 
         st->mats.resize(n_mats);
         std::vector<TileRef> dots;
         size_t off = pl.off_scratch;
-        st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = 0;
+        st->max_m = st->max_n = st->max_r = st->max_l = st->max_lp = st->max_rows = st->max_ldn = 0;
         st->max_jpairs = 0;
         st->sides = 0;
         for (int op = 0; op < OP_COUNT; ++op) st->max_ti[op] = st->max_tj[op] = st->max_tk[op] = 1;
@@ -506,6 +520,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.order = (int*)(ws + off); off += z.ws_order;
             md.jflag = (int*)(ws + off); off += z.ws_flag;
             md.carry = z.ws_carry ? (float*)(ws + off) : nullptr; off += z.ws_carry;
+            md.skinny_parts = z.ws_skinny ? (float*)(ws + off) : nullptr; off += z.ws_skinny;
             md.lp = z.lp;
             // units of the Gram-row reduction: 16-byte vectors of a slot
             const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
@@ -519,6 +534,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             if (md.n > st->max_n) st->max_n = md.n;
             if (md.r > st->max_r) st->max_r = md.r;
             if (md.l > st->max_l) st->max_l = md.l;
+            if (md.ldn > st->max_ldn) st->max_ldn = md.ldn;
             if (md.lp > st->max_lp) st->max_lp = md.lp;
             const int rows = md.m > md.n ? md.m : md.n;
             if (rows > st->max_rows) st->max_rows = rows;
@@ -549,6 +565,8 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             e = hipMemcpy(st->d_dots, dots.data(), sizeof(TileRef) * dots.size(), hipMemcpyHostToDevice);
         if (e == hipSuccess && !pl.patches.empty())
             e = hipMemcpy(st->d_patches, pl.patches.data(), sizeof(TileRef) * pl.patches.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pl.skinny.empty())
+            e = hipMemcpy(st->d_skinny, pl.skinny.data(), sizeof(TileRef) * pl.skinny.size(), hipMemcpyHostToDevice);
         if (e != hipSuccess && !(flags & NG_INIT_NO_CLEAR)) {
             delete st;
             return NG_ERR_HIP;
@@ -681,9 +699,12 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, st->plan.proj_direct, st->plan.proj_staged,
-                                       st->plan.proj_right, st->max_r, sc.hist_bf16, (const char*)st->d_status + 64,
-                                       stream));
+    const int skinny_rk = st->plan.skinny_rk;
+    if (skinny_rk) NG_HIP(launch_project_skinny(st->d_mats, st->d_dyn, st->d_skinny, (int)st->plan.skinny.size(), st->n_mats,
+                                                st->max_ldn, skinny_rk, stream));
+    else if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, st->plan.proj_direct, st->plan.proj_staged,
+                                            st->plan.proj_right, st->max_r, sc.hist_bf16, (const char*)st->d_status + 64,
+                                            stream));
     else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
@@ -697,8 +718,10 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
                                  st->hp.grad_dtype, st->d_status, stream));
 
     if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
-    if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc,
-                                      (const char*)st->d_status + 64, st->sides, stream));
+    if (skinny_rk) NG_HIP(launch_update_skinny(st->d_mats, st->d_dyn, st->d_skinny, (int)st->plan.skinny.size(), skinny_rk,
+                                               sc, stream));
+    else if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc,
+                                           (const char*)st->d_status + 64, st->sides, stream));
     else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc)) != NG_OK) return rc;
 
     if (prof) {

@@ -15,6 +15,9 @@ constexpr int kMaxS = 64;        // history slots
 constexpr int kDotPartsMax = 256; // per-matrix partial sums of the Gram-row reduction
 constexpr int kAdamPatchCols = 128; // columns of one transform+Adam workgroup patch (32 rows)
 constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (by kernel argument)
+constexpr int kSkinnyMaxRank = 16;   // fp32 layer sets with ranks up to this take the vector-ALU projection / update
+constexpr int kSkinnyRows = 128;     // rows and columns of the gradient / weight one of their workgroups takes
+constexpr int kSkinnyCols = 256;
 constexpr int kJacobiBlock = 16;  // rows per block of the blocked Jacobi (a visit rotates a pair of blocks)
 
 // Static per-matrix description, lives in the workspace (device) and in the handle (host).
@@ -56,6 +59,7 @@ struct MatDev {
     int* order;       // [lp]
     int* jflag;       // [0] rotations this sweep, [1] converged
     float* carry;     // [r][ldn] scratch of the history carry-over (null unless enabled)
+    float* skinny_parts;   // [ceil(m/kSkinnyRows)][rk][ldn] row-chunk sums of the small-rank projection (else null)
     bf16_t* tail8;    // 8 bf16 in the workspace: the last gradient row's columns from the last multiple of
                       // 8 on, zero-padded (rewritten every step, see launch_upload_dyn)
     int lp;           // l rounded up to a whole number of Jacobi block pairs: order and row pitch of T, Linv
@@ -161,6 +165,14 @@ hipError_t launch_update_bf16(const MatDev* mats, const MatDyn* dyn, const TileR
 // max_m / max_n: largest row / column count of the result over the layer set
 hipError_t launch_refresh_x3(int form, int ysrc, int planes, const MatDev* mats, const MatDyn* dyn, int n_mats,
                              int max_m, int max_n, hipStream_t stream);
+
+// Projection and update of fp32 layer sets with ranks <= kSkinnyMaxRank, left side (k_skinny.hip).
+// tiles: one entry per kSkinnyRows x kSkinnyCols block of the m x ldn range of every matrix; rk: 4, 8
+// or 16, at least the largest rank of the set (the row pitch of MatDev::skinny_parts).
+hipError_t launch_project_skinny(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles, int n_mats,
+                                 int max_ldn, int rk, hipStream_t stream);
+hipError_t launch_update_skinny(const MatDev* mats, const MatDyn* dyn, const TileRef* tiles, int n_tiles, int rk,
+                                StepScalars sc, hipStream_t stream);
 
 // Gram row, solve, fused transform + Adam (k_elementwise.hip)
 // row_override >= 0: the Gram row of that slot instead of the step's head (history carry-over);

@@ -135,6 +135,17 @@ def test_fine_tuning_shaped_block(name, dtype):
     _assert_all(errs, TOL_F32 if dtype == "f32" else TOL_BF16, "%s %s" % (name, dtype), skip=("dW",))
 
 
+@pytest.mark.parametrize("ranks,s", [([3, 4, 2, 1], 4), ([5, 8, 7, 6], 3), ([13, 16, 9, 11], 0)])
+def test_small_rank_f32_ragged_strided(ranks, s):
+    # fp32 layer sets with every rank <= 16 take the vector-ALU projection / update: ranks that are
+    # not the kernel's 4 / 8 / 16 classes, row counts that are not multiples of a 128-row chunk,
+    # column counts that are not multiples of 4, strided weights (rest untouched) and gradients
+    # (NaN beyond column n), with and without the Fisher history
+    shapes = [(300, 517), (129, 66), (1000, 30), (64, 1030)]
+    ls, errs = _run(shapes, ranks, s, "f32", 6, seed=83, k=12, pad_w=3, pad_g=5)
+    _assert_all(errs, TOL_F32, "small ranks %s" % ranks)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_right_side_projection(dtype):
     # R = G Q with the n x r factor (the usual choice for m > n), mixed with left-side matrices in

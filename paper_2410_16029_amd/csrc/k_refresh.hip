@@ -498,7 +498,7 @@ struct TournamentRow {
     }
 };
 
-__global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
+__global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
     extern __shared__ __attribute__((aligned(16))) double smem_d[];
     __shared__ double cc[32], tt[32];
     __shared__ int nrot_s;
@@ -518,22 +518,23 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     if (cross ? (bp * 16 >= md.l || bq * 16 >= md.l) : (bp * 16 >= md.l && bq * 16 >= md.l)) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     // The 32 rows of the pair stay in global memory: the Gram product and X <- V X take their MFMA
-    // operands straight from there (the second read mostly from the L2), so a workgroup needs only
-    // 68 KB of LDS and 64 registers per lane, and two visits share a CU -- one multiplies or
-    // streams while the other sits in the dependent rounds of its small sweep.
+    // operands straight from there (the second read mostly from the L2).  More than half of a visit
+    // is the dependent rounds of its small sweep, in which a CU is mostly idle, so what counts is
+    // how many visits a CU holds: eight wavefronts and 48 KB of LDS per visit (S and V take the place
+    // of the Gram partials once those are summed) make it three.
     double* part = smem_d;                          // [kJgParts][3][256] Gram partials
-    double* Ss = part + kJgParts * 768;             // [32][kJgLdS]
+    double* Ss = smem_d;                            // [32][kJgLdS], after the partials are summed
     double* Vs = Ss + 32 * kJgLdS;                  // [32][kJgLdS]
     float* __restrict__ X = jacobi_rows(md);
     float* __restrict__ Xp = X + (long long)bp * 16 * lp;   // rows 0..15 of the pair
     float* __restrict__ Xq = X + (long long)bq * 16 * lp;   // rows 16..31
     if (tid == 0) nrot_s = 0;
 
-    // ---- Gram: wavefronts 0..7 take an eighth of the columns each and compute the tiles (0,0), (1,0),
+    // ---- Gram: each wavefront takes an eighth of the columns and computes the tiles (0,0), (1,0),
     // (1,1) from the same two operands per k-step; (0,1) is the transpose of (1,0).  The partials are
     // added in a fixed order.
     const int l16 = lane & 15, lq = lane >> 4;
-    if (wv < kJgParts) {
+    {
         double4_t g00 = {0.0, 0.0, 0.0, 0.0}, g10 = {0.0, 0.0, 0.0, 0.0}, g11 = {0.0, 0.0, 0.0, 0.0};
         const int cols = lp / kJgParts;            // lp % 32 == 0: cols % 4 == 0
         // A lane reads four consecutive columns of its row, 16 columns per 16 lanes and chunk; k-step
@@ -563,27 +564,41 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
         }
     }
     __syncthreads();
-    if (tid < 768) {
-        double v = 0.0;
+    {
+        // entries tid and tid + 512 (the latter below 768) of the three tiles; the sums wait in
+        // registers until every partial has been read, because S overwrites them
+        double v0 = 0.0, v1 = 0.0;
 #pragma unroll
-        for (int w = 0; w < kJgParts; ++w) v += part[w * 768 + tid];
-        // element e of lane L is entry (4e + L/16, L%16) of its tile
-        const int tile = tid >> 8, e = (tid >> 6) & 3, ln = tid & 63;
-        const int ii = 4 * e + (ln >> 4), jj = ln & 15;
-        if (tile == 0) {
-            Ss[ii * kJgLdS + jj] = v;
-        } else if (tile == 1) {
-            Ss[(16 + ii) * kJgLdS + jj] = v;
-            Ss[jj * kJgLdS + 16 + ii] = v;
-        } else {
-            Ss[(16 + ii) * kJgLdS + 16 + jj] = v;
+        for (int w = 0; w < kJgParts; ++w) v0 += part[w * 768 + tid];
+        if (tid < 256) {
+#pragma unroll
+            for (int w = 0; w < kJgParts; ++w) v1 += part[w * 768 + 512 + tid];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (k == 1 && tid >= 256) break;
+            const int idx = tid + 512 * k;
+            const double v = k ? v1 : v0;
+            // element e of lane L is entry (4e + L/16, L%16) of its tile
+            const int tile = idx >> 8, e = (idx >> 6) & 3, ln = idx & 63;
+            const int ii = 4 * e + (ln >> 4), jj = ln & 15;
+            if (tile == 0) {
+                Ss[ii * kJgLdS + jj] = v;
+            } else if (tile == 1) {
+                Ss[(16 + ii) * kJgLdS + jj] = v;
+                Ss[jj * kJgLdS + 16 + ii] = v;
+            } else {
+                Ss[(16 + ii) * kJgLdS + 16 + jj] = v;
+            }
         }
     }
+    // ---- V = I (its place held no partials that anyone still needs: all were read before the barrier)
+    const int pk = tid >> 5, vj = tid & 31;        // thread (pk, vj): row pair pk of a round, column vj
+    Vs[pk * kJgLdS + vj] = pk == vj ? 1.0 : 0.0;
+    Vs[(16 + pk) * kJgLdS + vj] = 16 + pk == vj ? 1.0 : 0.0;
     __syncthreads();
-
-    // ---- V = I; largest diagonal entry of S (scale of the rounding noise inside this visit)
-    const int vi = tid >> 5, vj = tid & 31;
-    Vs[vi * kJgLdS + vj] = vi == vj ? 1.0 : 0.0;
+    // largest diagonal entry of S (scale of the rounding noise inside this visit)
     if (wv == 0) {
         double d = lane < 32 ? Ss[lane * kJgLdS + lane] : 0.0;
 #pragma unroll
@@ -592,20 +607,22 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
     }
     __syncthreads();
 
-    // ---- one cyclic sweep over the 32 rows on S, accumulated in V; thread (vi, vj) owns S[vi][vj], V[vi][vj]
-    TournamentRow ri, rj;
-    ri.init(vi);
+    // ---- the small sweep on S, accumulated in V.  A round rotates 16 disjoint row pairs (a, b);
+    // thread (pk, vj) owns both rows of pair pk in column vj: S[a][vj], S[b][vj], V[a][vj], V[b][vj].
+    TournamentRow rj;
     rj.init(vj);
     int nrot = 0;
     const int nir = cross ? 16 : 31;
     for (int ir = 0; ir < nir; ++ir) {
-        // old values first (their addresses depend on the round only), rotation parameters meanwhile
-        const int pi = cross ? (vi < 16 ? 16 + ((vi + ir) & 15) : ((vi - ir) & 15)) : ri.partner(ir);
+        int a, b;
+        tournament_pair(32, ir, pk, &a, &b);
+        if (cross) { a = pk; b = 16 + ((pk + ir) & 15); }
         const int pj = cross ? (vj < 16 ? 16 + ((vj + ir) & 15) : ((vj - ir) & 15)) : rj.partner(ir);
-        const double s00 = Ss[vi * kJgLdS + vj], s10 = Ss[pi * kJgLdS + vj];
-        const double s01 = Ss[vi * kJgLdS + pj], s11 = Ss[pi * kJgLdS + pj];
-        const double v0 = Vs[vi * kJgLdS + vj], v1 = Vs[pi * kJgLdS + vj];
-        if (tid < 16) {
+        // old values first (their addresses depend on the round only), rotation parameters meanwhile
+        const double sav = Ss[a * kJgLdS + vj], sbv = Ss[b * kJgLdS + vj];
+        const double sap = Ss[a * kJgLdS + pj], sbp = Ss[b * kJgLdS + pj];
+        const double va = Vs[a * kJgLdS + vj], vb = Vs[b * kJgLdS + vj];
+        if (tid < 16) {      // one thread per pair, all in one wavefront
             int a, b;
             tournament_pair(32, ir, tid, &a, &b);
             if (cross) { a = tid; b = 16 + ((tid + ir) & 15); }
@@ -626,21 +643,22 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
             tt[b] = sn;      // row b <- sn * a + cs * b
         }
         __syncthreads();     // every old value has been read; the parameters are published
-        const double ci = cc[vi], ti_ = tt[vi], cj = cc[vj], tj_ = tt[vj];
-        Ss[vi * kJgLdS + vj] = cj * (ci * s00 + ti_ * s10) + tj_ * (ci * s01 + ti_ * s11);
-        Vs[vi * kJgLdS + vj] = ci * v0 + ti_ * v1;
-        ri.advance();
+        const double cs = cc[a], sn = tt[b], cj = cc[vj], tj_ = tt[vj];
+        Ss[a * kJgLdS + vj] = cj * (cs * sav - sn * sbv) + tj_ * (cs * sap - sn * sbp);
+        Ss[b * kJgLdS + vj] = cj * (sn * sav + cs * sbv) + tj_ * (sn * sap + cs * sbp);
+        Vs[a * kJgLdS + vj] = cs * va - sn * vb;
+        Vs[b * kJgLdS + vj] = sn * va + cs * vb;
         rj.advance();
         __syncthreads();
     }
     if (nrot) atomicAdd(&nrot_s, nrot);
 
-    // ---- X <- V X: wavefront wv takes the 16-column tiles wv, wv + 16, ...; both 16-row halves
+    // ---- X <- V X: wavefront wv takes the 16-column tiles wv, wv + 8, ...; both 16-row halves
     const int nct = lp / 16;
     const double* va0 = Vs + l16 * kJgLdS + lq;                // A[L%16][k + L/16] = V[L%16][k + L/16], k = 4u
     const double* va1 = Vs + (16 + l16) * kJgLdS + lq;
     const unsigned rowoff = (unsigned)lq * (unsigned)lp + (unsigned)l16, lp4 = 4u * (unsigned)lp;
-    for (int ct = wv; ct < nct; ct += 16) {
+    for (int ct = wv; ct < nct; ct += 8) {
         // B[k + L/16][L%16] = X[k + L/16][c0 + L%16], k = 4u: rows 0..15 from Xp, 16..31 from Xq; element e
         // of a result tile is row 4e + L/16 of its half: the same offsets
         const unsigned base = rowoff + 16u * (unsigned)ct;
@@ -672,13 +690,14 @@ __global__ __launch_bounds__(1024, 8) void k_jacobi_round_gram(const MatDev* __r
 
 hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, hipStream_t stream) {
     static bool attr_done = false;
-    constexpr int lds = (kJgParts * 768 + 2 * 32 * kJgLdS) * (int)sizeof(double);
+    constexpr int lds = kJgParts * 768 * (int)sizeof(double);   // S and V (2 x 32 x kJgLdS doubles) fit inside
+    static_assert(2 * 32 * kJgLdS <= kJgParts * 768, "S and V take the place of the Gram partials");
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_jacobi_round_gram, dim3(max_pairs, n_mats), dim3(1024), lds, stream, mats, round);
+    hipLaunchKernelGGL(k_jacobi_round_gram, dim3(max_pairs, n_mats), dim3(512), lds, stream, mats, round);
     return hipGetLastError();
 }
 

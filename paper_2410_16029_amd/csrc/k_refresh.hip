@@ -498,7 +498,7 @@ struct TournamentRow {
     }
 };
 
-__global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
+__global__ __launch_bounds__(512, 8) void k_jacobi_round_gram(const MatDev* __restrict__ mats, int round) {
     extern __shared__ __attribute__((aligned(16))) double smem_d[];
     __shared__ double cc[32], tt[32];
     __shared__ int nrot_s;
@@ -522,7 +522,7 @@ __global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __re
     // is the dependent rounds of its small sweep, in which a CU is mostly idle, so what counts is
     // how many visits a CU holds: eight wavefronts and 48 KB of LDS per visit (S and V take the place
     // of the Gram partials once those are summed) make it three.
-    double* part = smem_d;                          // [kJgParts][3][256] Gram partials
+    double* part = smem_d;                          // [kJgParts / 2][3][256] Gram partials
     double* Ss = smem_d;                            // [32][kJgLdS], after the partials are summed
     double* Vs = Ss + 32 * kJgLdS;                  // [32][kJgLdS]
     float* __restrict__ X = jacobi_rows(md);
@@ -555,12 +555,31 @@ __global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __re
                 g11 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, a1, g11, 0, 0, 0);
             }
         }
-        double* dst = part + wv * 768;
+        // wavefronts 4..7 hand their tiles to wavefronts 0..3, which add their own and publish the four
+        // sums: half the LDS of eight partial sets
+        double* dst = part + (wv & 3) * 768;
+        if (wv >= 4) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            dst[e * 64 + lane] = g00[e];
-            dst[256 + e * 64 + lane] = g10[e];
-            dst[512 + e * 64 + lane] = g11[e];
+            for (int e = 0; e < 4; ++e) {
+                dst[e * 64 + lane] = g00[e];
+                dst[256 + e * 64 + lane] = g10[e];
+                dst[512 + e * 64 + lane] = g11[e];
+            }
+        }
+        __syncthreads();
+        if (wv < 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                g00[e] += dst[e * 64 + lane];
+                g10[e] += dst[256 + e * 64 + lane];
+                g11[e] += dst[512 + e * 64 + lane];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {     // (each lane overwrites exactly what it has just read)
+                dst[e * 64 + lane] = g00[e];
+                dst[256 + e * 64 + lane] = g10[e];
+                dst[512 + e * 64 + lane] = g11[e];
+            }
         }
     }
     __syncthreads();
@@ -569,10 +588,10 @@ __global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __re
         // registers until every partial has been read, because S overwrites them
         double v0 = 0.0, v1 = 0.0;
 #pragma unroll
-        for (int w = 0; w < kJgParts; ++w) v0 += part[w * 768 + tid];
+        for (int w = 0; w < kJgParts / 2; ++w) v0 += part[w * 768 + tid];
         if (tid < 256) {
 #pragma unroll
-            for (int w = 0; w < kJgParts; ++w) v1 += part[w * 768 + 512 + tid];
+            for (int w = 0; w < kJgParts / 2; ++w) v1 += part[w * 768 + 512 + tid];
         }
         __syncthreads();
 #pragma unroll
@@ -690,8 +709,8 @@ __global__ __launch_bounds__(512, 6) void k_jacobi_round_gram(const MatDev* __re
 
 hipError_t launch_jacobi_round(const MatDev* mats, int n_mats, int max_pairs, int round, hipStream_t stream) {
     static bool attr_done = false;
-    constexpr int lds = kJgParts * 768 * (int)sizeof(double);   // S and V (2 x 32 x kJgLdS doubles) fit inside
-    static_assert(2 * 32 * kJgLdS <= kJgParts * 768, "S and V take the place of the Gram partials");
+    constexpr int lds = kJgParts / 2 * 768 * (int)sizeof(double);   // S and V (2 x 32 x kJgLdS doubles) fit inside
+    static_assert(2 * 32 * kJgLdS <= kJgParts / 2 * 768, "S and V take the place of the Gram partials");
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_round_gram),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);

@@ -17,7 +17,9 @@
  *     HOST pointer.
  *   - All matrices are row-major.  ld_* are in elements.
  *   - All device memory is owned by the caller and must outlive the handle.  The
- *     library allocates no device memory and frees none.
+ *     library allocates no device memory and frees none.  `workspace` is ordinary
+ *     (coarse-grained) device memory as hipMalloc returns it: the refresh adds into it
+ *     with hardware floating-point atomics.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
  *     that take a stream only enqueue work on it and do not synchronise, except
  *     where stated.  Calls on one handle must not overlap.

@@ -127,12 +127,13 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
 #pragma unroll
     for (int j = 0; j < SMAX; ++j) acc[j] = 0.0;
 
-    if (!HB) {
-        // Four positions per thread and pass (q, q + 256, q + 512, q + 768), one slot at a time: the
-        // four loads of a slot are issued together and the compiler is kept from mixing the slots
-        // (a workgroup streaming 16 KB of one slot after the other reads at 6.96 TB/s; with the
-        // loads of all slots for one position in flight at once it was 6.74).  The order of the
-        // additions into acc[j] is that of q, as in a plain loop over the positions.
+    if (!HB && (md.dot_iters & 3) == 0) {
+        // Large float slots (the host makes a workgroup's span a whole number of 1024-vector passes):
+        // four positions per thread and pass (q, q + 256, q + 512, q + 768), one slot at a time -- the
+        // four loads of a slot are issued together and the compiler is kept from mixing the slots.
+        // A workgroup streaming 16 KB of one slot after the other reads at 6.96 TB/s; with the loads
+        // of all slots for one position in flight at once it was 6.74.  The order of the additions
+        // into acc[j] is that of q, as in the loop below.
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
         for (long long q = q0 + threadIdx.x; q < q1; q += 1024) {
             u32x4_t rv[4];
@@ -162,9 +163,11 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
             }
         }
     } else {
-        // bf16 slots (8 elements per vector): all slots of one position together, R widened once per
-        // position (the slot-at-a-time order would widen it once per slot: 1.36 against 1.25 ms).
-        // Branch-free: a slot index beyond s is clamped to s-1 (its sum is never written out).
+        // Small slots (a workgroup has one or a few positions per thread: latency, not bandwidth) and
+        // bf16 slots (8 elements per vector; R is widened once per position, which the slot-at-a-time
+        // order would do once per slot: 1.36 against 1.25 ms): all slots of one position together.
+        // Branch-free: a slot index beyond s is clamped to s-1 (its sum is never written out), so
+        // all SMAX loads of one position are issued back to back.
         long long slot_off[SMAX];
 #pragma unroll
         for (int j = 0; j < SMAX; ++j) slot_off[j] = (long long)(j < s ? j : s - 1) * totalv;
@@ -173,21 +176,32 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
             u32x4_t hv[SMAX];
 #pragma unroll
             for (int j = 0; j < SMAX; ++j) hv[j] = __builtin_nontemporal_load(H + (slot_off[j] + q));
-            float rf[8];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                rf[2 * d] = __uint_as_float(rv[d] << 16);
-                rf[2 * d + 1] = __uint_as_float(rv[d] & 0xffff0000u);
-            }
-#pragma unroll
-            for (int j = 0; j < SMAX; ++j) {
-                float p = 0.f;
+            if (HB) {
+                float rf[8];
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    p = fmaf(__uint_as_float(hv[j][d] << 16), rf[2 * d], p);
-                    p = fmaf(__uint_as_float(hv[j][d] & 0xffff0000u), rf[2 * d + 1], p);
+                    rf[2 * d] = __uint_as_float(rv[d] << 16);
+                    rf[2 * d + 1] = __uint_as_float(rv[d] & 0xffff0000u);
                 }
-                acc[j] += (double)p;
+#pragma unroll
+                for (int j = 0; j < SMAX; ++j) {
+                    float p = 0.f;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        p = fmaf(__uint_as_float(hv[j][d] << 16), rf[2 * d], p);
+                        p = fmaf(__uint_as_float(hv[j][d] & 0xffff0000u), rf[2 * d + 1], p);
+                    }
+                    acc[j] += (double)p;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < SMAX; ++j) {
+                    float p = __uint_as_float(hv[j].x) * __uint_as_float(rv.x);
+                    p = fmaf(__uint_as_float(hv[j].y), __uint_as_float(rv.y), p);
+                    p = fmaf(__uint_as_float(hv[j].z), __uint_as_float(rv.z), p);
+                    p = fmaf(__uint_as_float(hv[j].w), __uint_as_float(rv.w), p);
+                    acc[j] += (double)p;
+                }
             }
         }
     }
@@ -255,8 +269,21 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
         const int nsub = 64 / s;
         const int j = i % s, sub = i / s;
         double v = 0.0;
-        if (sub < nsub)
-            for (int p = sub; p < md.dot_nparts; p += nsub) v += md.dot_parts[(long long)p * s + j];
+        if (sub < nsub) {
+            // eight loads in flight, added in the order of p
+            const int np = md.dot_nparts;
+            const double* __restrict__ parts = md.dot_parts + j;
+            for (int p = sub; p < np; p += 8 * nsub) {
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int pu = p + u * nsub;
+                    x[u] = pu < np ? parts[(long long)pu * s] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v += x[u];
+            }
+        }
         bc[i] = v;
     }
     __syncthreads();

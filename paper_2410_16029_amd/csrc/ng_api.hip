@@ -526,6 +526,9 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
             long long iters = (total4 + 256LL * kDotPartsMax - 1) / (256LL * kDotPartsMax);
             if (iters < 1) iters = 1;
+            // float slots large enough for several passes: a whole number of 1024-vector passes per
+            // workgroup (the kernel then walks the slots one at a time)
+            if (!hist_is_bf16(*hp) && iters >= 3) iters = (iters + 3) / 4 * 4;
             md.dot_iters = (int)iters;
             md.dot_nparts = (int)((total4 + iters * 256 - 1) / (iters * 256));
             if (hp->s > 0)

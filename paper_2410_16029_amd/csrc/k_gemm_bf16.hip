@@ -392,8 +392,8 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], 
                         // (two stores under lane masks: a select on the value would pull every
                         // accumulator into an ordinary register at once)
                         if (row < r) {
-                            if (col < n) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = acc[mi][nj][4 * g + e];
-                            else if (col < ldn) R[(unsigned)row * (unsigned)ldn + (unsigned)col] = 0.f;
+                            if (col < n) __builtin_nontemporal_store(acc[mi][nj][4 * g + e], &R[(unsigned)row * (unsigned)ldn + (unsigned)col]);
+                            else if (col < ldn) __builtin_nontemporal_store(0.f, &R[(unsigned)row * (unsigned)ldn + (unsigned)col]);
                         }
                     }
             }

@@ -60,7 +60,9 @@ enum {
     NG_ERR_NO_PROJECTOR = -5,  /* ng_step before any refresh / commit                 */
     NG_ERR_HIP = -6,           /* a HIP runtime call or kernel launch failed          */
     NG_ERR_NUMERIC = -7,       /* device flag: non-positive pivot or non-finite value */
-    NG_ERR_WORKSPACE = -8      /* workspace too small or misaligned                   */
+    NG_ERR_WORKSPACE = -8,     /* workspace too small or misaligned                   */
+    NG_ERR_NOT_CONVERGED = -9  /* device flag: the refresh's eigen-solve used all its
+                                  refresh_sweeps without reaching its convergence test  */
 };
 
 /* per-matrix caller-owned device buffers, sizes from ng_query_sizes */
@@ -127,6 +129,12 @@ typedef struct ng_matrix_layout {
     int32_t l;          /* sketch width of the refresh                                                   */
     int64_t slot_elems; /* r * ldn: elements per history slot                                            */
     int64_t k_gram_off, k_w64_off, k_w32_off;  /* byte offsets inside the K buffer                       */
+    /* NG_BF16 only (else 0): byte offsets inside the AUX buffer of the two bf16 copies of P that the
+     * step's GEMMs multiply with, both split into blocks of 32 along the contraction index:
+     *   Pb  [ceil(r/32)][m][32]: P[i][rho]   at element ((rho/32) * m + i) * 32 + rho % 32   (update)
+     *   PbT [ceil(m/32)][r][32]: P[i][rho]   at element ((i/32) * r + rho) * 32 + i % 32     (projection)
+     * positions beyond r (Pb) or m (PbT) inside the last block are 0 */
+    int64_t aux_pb_off, aux_pbt_off;
 } ng_matrix_layout;
 
 /* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
@@ -143,12 +151,17 @@ int ng_query_sizes(const ng_matrix_desc* descs, int n_mats, const ng_hparams* hp
 
 /* flags for ng_init_state */
 enum { NG_INIT_DEFAULT = 0,
-       NG_INIT_NO_CLEAR = 1   /* caller has already zero-filled (or restored) every buffer */ };
+       NG_INIT_NO_CLEAR = 1,  /* caller has already zero-filled (or restored) every buffer */
+       NG_INIT_HOST_ONLY = 2  /* touch no device: nothing is uploaded or cleared, and every later call
+                                 that would launch a kernel returns NG_ERR_HIP.  For exercising the
+                                 host-side bookkeeping (validation, counters, layout) without a GPU;
+                                 the buffer and workspace pointers are only checked for alignment */ };
 
 /* Create a handle over caller-owned buffers.  Unless NG_INIT_NO_CLEAR is given,
  * enqueues zero-fills of M, V, H, K, N on `stream`.  Uploads its tables into
- * `workspace` (synchronous copies).  Counters start at t = head = count =
- * n_refresh = 0 and the projector is marked invalid. */
+ * `workspace` (synchronous copies); a failed upload returns NG_ERR_HIP and no
+ * handle.  Counters start at t = head = count = n_refresh = 0 and the projector
+ * is marked invalid. */
 int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, int n_mats,
                   const ng_hparams* hp, void* workspace, size_t workspace_bytes,
                   uint32_t flags, ng_stream stream, ng_state** out);
@@ -188,7 +201,9 @@ int ng_set_counters(ng_state* st, int mat, int64_t t, int32_t head, int32_t coun
 int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out);
 
 /* Synchronises `stream`, reads and clears the device's sticky flag.  Returns
- * NG_OK, NG_ERR_NUMERIC or NG_ERR_HIP. */
+ * NG_OK, NG_ERR_NUMERIC (non-positive pivot, non-finite value; takes precedence),
+ * NG_ERR_NOT_CONVERGED (a refresh whose eigen-solve ran out of sweeps; P is still
+ * orthonormal, its columns may mix neighbouring Ritz vectors) or NG_ERR_HIP. */
 int ng_get_status(ng_state* st, ng_stream stream);
 
 /* Phase timing with HIP events on the stream of the call.  When enabled, ng_step

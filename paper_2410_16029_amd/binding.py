@@ -27,9 +27,9 @@ NG_NORM_S, NG_NORM_COUNT = 0, 1
 NG_ADAM_STANDARD, NG_ADAM_PRINTED = 0, 1
 NG_OK = 0
 NG_ERR_INVALID_ARG, NG_ERR_SHAPE, NG_ERR_DTYPE, NG_ERR_HPARAM = -1, -2, -3, -4
-NG_ERR_NO_PROJECTOR, NG_ERR_HIP, NG_ERR_NUMERIC, NG_ERR_WORKSPACE = -5, -6, -7, -8
+NG_ERR_NO_PROJECTOR, NG_ERR_HIP, NG_ERR_NUMERIC, NG_ERR_WORKSPACE, NG_ERR_NOT_CONVERGED = -5, -6, -7, -8, -9
 NG_BUF_P, NG_BUF_M, NG_BUF_V, NG_BUF_H, NG_BUF_K, NG_BUF_N, NG_BUF_AUX, NG_NBUF = range(8)
-NG_INIT_DEFAULT, NG_INIT_NO_CLEAR = 0, 1
+NG_INIT_DEFAULT, NG_INIT_NO_CLEAR, NG_INIT_HOST_ONLY = 0, 1, 2
 NG_NPHASE = 5
 PHASE_NAMES = ("project", "gram", "solve", "adam", "update")
 
@@ -54,7 +54,8 @@ class ng_matrix_buffers(C.Structure):
 
 class ng_matrix_layout(C.Structure):
     _fields_ = [("ldn", C.c_int32), ("l", C.c_int32), ("slot_elems", C.c_int64),
-                ("k_gram_off", C.c_int64), ("k_w64_off", C.c_int64), ("k_w32_off", C.c_int64)]
+                ("k_gram_off", C.c_int64), ("k_w64_off", C.c_int64), ("k_w32_off", C.c_int64),
+                ("aux_pb_off", C.c_int64), ("aux_pbt_off", C.c_int64)]
 
 
 _P = C.POINTER
@@ -204,7 +205,7 @@ class LayerSet:
     def __init__(self, shapes: Sequence, r, *, s=4, lam=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                  weight_decay=0.0, dtype="f32", adam_mode="standard", power_iters=None, oversample=None,
                  sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False, hist_dtype=None,
-                 sides=None, fisher_norm="s", carry_history=False):
+                 sides=None, fisher_norm="s", carry_history=False, host_only=False):
         self.device = torch.device(device)
         self.shapes = [tuple(x) for x in shapes]
         self.r = r
@@ -236,7 +237,7 @@ class LayerSet:
             row = []
             for b in range(NG_NBUF):
                 nbytes = self.sizes[i][b]
-                if no_clear:
+                if no_clear or host_only:
                     t = torch.zeros(max(nbytes, 16), dtype=torch.uint8, device=self.device)
                 else:
                     t = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=self.device)
@@ -246,7 +247,8 @@ class LayerSet:
         self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=self.device)
         ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
         self.st = ng_init_state(self.descs, self._bufs, hp, ws_ptr, self.workspace_bytes,
-                                NG_INIT_NO_CLEAR if no_clear else NG_INIT_DEFAULT, self.stream())
+                                (NG_INIT_NO_CLEAR if no_clear else NG_INIT_DEFAULT)
+                                | (NG_INIT_HOST_ONLY if host_only else 0), self.stream())
         self.layouts = [ng_get_layout(self.st, i) for i in range(n)]
 
     def stream(self) -> int:
@@ -322,6 +324,24 @@ class LayerSet:
         roct = (r + 7) // 8
         raw = self._view(i, NG_BUF_N, torch.bfloat16, roct * ldn * 8).view(roct, ldn, 8)
         return raw.permute(0, 2, 1).reshape(roct * 8, ldn)[:r, :n].float()
+
+    def Pb(self, i):
+        """The bf16 copy of P that the update GEMM multiplies with, decoded from its blocked layout
+        to a float32 [m][r] tensor (bf16 layer sets only)."""
+        m, _ = self.eff_shape(i)
+        r = self.descs[i].r
+        nblk = (r + 31) // 32
+        raw = self._view(i, NG_BUF_AUX, torch.bfloat16, nblk * m * 32, self.layouts[i].aux_pb_off).view(nblk, m, 32)
+        return raw.permute(1, 0, 2).reshape(m, nblk * 32)[:, :r].float()
+
+    def PbT(self, i):
+        """The bf16 copy of P that the projection GEMM multiplies with (stored transposed and
+        blocked), decoded to a float32 [m][r] tensor (bf16 layer sets only)."""
+        m, _ = self.eff_shape(i)
+        r = self.descs[i].r
+        nblk = (m + 31) // 32
+        raw = self._view(i, NG_BUF_AUX, torch.bfloat16, nblk * r * 32, self.layouts[i].aux_pbt_off).view(nblk, r, 32)
+        return raw.permute(0, 2, 1).reshape(nblk * 32, r)[:m].float()
 
     def close(self) -> None:
         if getattr(self, "st", None) is not None:

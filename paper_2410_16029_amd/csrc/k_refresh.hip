@@ -762,6 +762,8 @@ __global__ __launch_bounds__(256) void k_ritz_sort(const MatDev* __restrict__ ma
         if (rank < md.r && !(vi > 0.0)) bad = true;
     }
     if (bad) atomicOr(status, 8);
+    // no sweep without a rotation was seen before the sweep limit
+    if (threadIdx.x == 0 && md.jflag[1] == 0) atomicOr(status, kStatusNotConverged);
 }
 
 __global__ __launch_bounds__(256) void k_build_rotation(const MatDev* __restrict__ mats) {

@@ -226,6 +226,7 @@ struct ng_state {
     std::vector<int64_t> t, n_refresh;
     std::vector<int32_t> head, count;
     bool projector_valid;
+    bool tables_valid;   // the workspace tables are on the device (false for NG_INIT_HOST_ONLY: nothing may launch)
     char* ws;
     MatDev* d_mats;
     MatDyn* d_dyn;
@@ -357,6 +358,7 @@ int orthonormalise(ng_state* st, bool is_a, bool twice, hipStream_t stream, cons
 }
 
 int finish_projector(ng_state* st, bool clear, hipStream_t stream) {
+    if (!st->tables_valid && (clear || st->hp.grad_dtype == NG_BF16)) return NG_ERR_HIP;
     if (st->hp.grad_dtype == NG_BF16)
         NG_HIP(launch_make_bf16_copies(st->d_mats, st->n_mats, st->max_m, st->max_r, stream));
     if (clear) {
@@ -553,6 +555,11 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         }
         st->n_dots = (int)dots.size();
 
+        st->tables_valid = !(flags & NG_INIT_HOST_ONLY);
+        if (!st->tables_valid) {
+            *out = st;
+            return NG_OK;
+        }
         // upload the tables (synchronous copies; init is not a hot path)
         hipError_t e = hipSuccess;
         // the status word, and behind it (bytes 64..127) a block of zeros the update GEMM fetches
@@ -570,13 +577,11 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             e = hipMemcpy(st->d_patches, pl.patches.data(), sizeof(TileRef) * pl.patches.size(), hipMemcpyHostToDevice);
         if (e == hipSuccess && !pl.skinny.empty())
             e = hipMemcpy(st->d_skinny, pl.skinny.data(), sizeof(TileRef) * pl.skinny.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess && !(flags & NG_INIT_NO_CLEAR)) {
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
             delete st;
             return NG_ERR_HIP;
         }
-        // With NG_INIT_NO_CLEAR a failed table upload is tolerated so that the host-side logic
-        // can be exercised without a device; every later launch then reports NG_ERR_HIP.
-        if (e != hipSuccess) (void)hipGetLastError();
 
         if (!(flags & NG_INIT_NO_CLEAR)) {
             for (int i = 0; i < n_mats; ++i) {
@@ -617,6 +622,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     if (!st || !grads) return NG_ERR_INVALID_ARG;
     for (int i = 0; i < st->n_mats; ++i)
         if (!grads[i]) return NG_ERR_INVALID_ARG;
+    if (!st->tables_valid) return NG_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     const StepScalars sc = make_scalars(st, 0.f);
     int rc;
@@ -689,6 +695,7 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
     for (int i = 0; i < st->n_mats; ++i)
         if (!grads[i] || !weights[i]) return NG_ERR_INVALID_ARG;
     if (!st->projector_valid) return NG_ERR_NO_PROJECTOR;
+    if (!st->tables_valid) return NG_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     const StepScalars sc = make_scalars(st, lr);
     const bool bf = st->hp.grad_dtype == NG_BF16;
@@ -775,11 +782,14 @@ int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out) {
     out->k_gram_off = (int64_t)z.k_gram_off;
     out->k_w64_off = (int64_t)z.k_w64_off;
     out->k_w32_off = (int64_t)z.k_w32_off;
+    out->aux_pb_off = (int64_t)z.aux_pb_off;
+    out->aux_pbt_off = (int64_t)z.aux_pbt_off;
     return NG_OK;
 }
 
 int ng_get_status(ng_state* st, ng_stream stream_) {
     if (!st) return NG_ERR_INVALID_ARG;
+    if (!st->tables_valid) return NG_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     NG_HIP(hipStreamSynchronize(stream));
     int flag = 0;
@@ -787,7 +797,7 @@ int ng_get_status(ng_state* st, ng_stream stream_) {
     if (flag != 0) {
         int zero = 0;
         NG_HIP(hipMemcpy(st->d_status, &zero, sizeof(int), hipMemcpyHostToDevice));
-        return NG_ERR_NUMERIC;
+        return (flag & ~kStatusNotConverged) ? NG_ERR_NUMERIC : NG_ERR_NOT_CONVERGED;
     }
     return NG_OK;
 }
@@ -828,6 +838,7 @@ const char* ng_strerror(int code) {
         case NG_ERR_HIP: return "HIP runtime error";
         case NG_ERR_NUMERIC: return "numeric failure on device (non-positive pivot or non-finite value)";
         case NG_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case NG_ERR_NOT_CONVERGED: return "the refresh's eigen-solve used all its sweeps without converging";
         default: return "unknown error code";
     }
 }

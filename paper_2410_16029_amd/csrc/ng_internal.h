@@ -18,6 +18,9 @@ constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (
 constexpr int kSkinnyMaxRank = 16;   // fp32 layer sets with ranks up to this take the vector-ALU projection / update
 constexpr int kSkinnyRows = 128;     // rows and columns of the gradient / weight one of their workgroups takes
 constexpr int kSkinnyCols = 256;
+// bits of the device's sticky status word: 1 solve (pivot / non-finite), 2 transform+Adam (non-finite),
+// 4 Cholesky pivot of the refresh, 8 non-positive Ritz value among the leading r
+constexpr int kStatusNotConverged = 16;   // the Jacobi eigen-solve of a refresh ran out of sweeps
 constexpr int kJacobiBlock = 16;  // rows per block of the blocked Jacobi (a visit rotates a pair of blocks)
 
 // Static per-matrix description, lives in the workspace (device) and in the handle (host).

@@ -119,11 +119,10 @@ def test_null_pointers_rejected():
 
 
 def _host_only_handle(s=3):
-    """A handle over host memory: legal as long as no kernel runs (NG_INIT_NO_CLEAR)."""
-    return B.LayerSet([(64, 96), (96, 64)], 16, s=s, dtype="f32", device="cpu", no_clear=True)
+    """A handle over host memory: NG_INIT_HOST_ONLY touches no device and lets nothing launch."""
+    return B.LayerSet([(64, 96), (96, 64)], 16, s=s, dtype="f32", device="cpu", host_only=True)
 
 
-@pytest.mark.skipif(torch.cuda.is_available(), reason="exercises the no-device error path")
 def test_host_bookkeeping_without_device():
     ls = _host_only_handle()
     assert ls.counters(0) == (0, 0, 0, 0)
@@ -145,12 +144,29 @@ def test_host_bookkeeping_without_device():
     ls.commit_projector(clear_history=False)
     before = [ls.counters(i) for i in range(2)]
     with pytest.raises(B.NgError) as e:
-        ls.step(g, w, 1e-3)             # the first launch fails: no device here
+        ls.step(g, w, 1e-3)             # a host-only handle launches nothing
     assert e.value.code == B.NG_ERR_HIP
     assert [ls.counters(i) for i in range(2)] == before   # a failed call leaves the counters alone
+    with pytest.raises(B.NgError) as e:
+        ls.refresh(g)
+    assert e.value.code == B.NG_ERR_HIP
+    with pytest.raises(B.NgError) as e:
+        ls.commit_projector(clear_history=True)          # clearing the history would launch
+    assert e.value.code == B.NG_ERR_HIP
+    assert [ls.counters(i) for i in range(2)] == before
+    assert ls.status() == B.NG_ERR_HIP
     lay = B.ng_get_layout(ls.st, 0)
     assert lay.ldn == 96 and lay.slot_elems == 16 * 96
     ls.close()
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="exercises the no-device error path")
+def test_failed_table_upload_returns_an_error_and_no_handle():
+    # without a device the upload of the tables fails: the restore flag must not hide that
+    for no_clear in (False, True):
+        with pytest.raises(B.NgError) as e:
+            B.LayerSet([(64, 96)], 16, s=2, dtype="f32", device="cpu", no_clear=no_clear)
+        assert e.value.code == B.NG_ERR_HIP
 
 
 def test_workspace_too_small_and_misaligned():
@@ -166,14 +182,14 @@ def test_workspace_too_small_and_misaligned():
     wsbuf = torch.zeros(ws + 512, dtype=torch.uint8)
     base = (wsbuf.data_ptr() + 255) // 256 * 256
     st = C.c_void_p()
-    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws - 1, B.NG_INIT_NO_CLEAR, None,
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws - 1, B.NG_INIT_HOST_ONLY, None,
                               C.byref(st))
     assert rc == B.NG_ERR_WORKSPACE
-    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base + 8), ws, B.NG_INIT_NO_CLEAR, None,
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base + 8), ws, B.NG_INIT_HOST_ONLY, None,
                               C.byref(st))
     assert rc == B.NG_ERR_WORKSPACE
     bufs[0].buf[B.NG_BUF_M] = None
-    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws, B.NG_INIT_NO_CLEAR, None,
+    rc = B._lib.ng_init_state(descs, bufs, 1, C.byref(hp), C.c_void_p(base), ws, B.NG_INIT_HOST_ONLY, None,
                               C.byref(st))
     assert rc == B.NG_ERR_INVALID_ARG
 
@@ -187,6 +203,6 @@ def test_sketch_width_is_trimmed_to_a_multiple_of_32_when_that_keeps_r_columns()
              ((256, 512), 64, 32, 96),    # already a multiple
              ((40, 512), 36, 8, 40)]      # clamped to m = 40 first; 32 < 36: kept
     for shape, r, p, want in cases:
-        ls = B.LayerSet([shape], r, s=2, dtype="f32", device="cpu", no_clear=True, oversample=p)
+        ls = B.LayerSet([shape], r, s=2, dtype="f32", device="cpu", host_only=True, oversample=p)
         assert B.ng_get_layout(ls.st, 0).l == want, (shape, r, p)
         ls.close()

@@ -192,6 +192,24 @@ int ng_commit_projector(ng_state* st, int clear_history, ng_stream stream);
 int ng_step(ng_state* st, const void* const* grads, void* const* weights, float lr,
             ng_stream stream);
 
+/* ng_step for callers that must not allocate and have no workspace to spare for it: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as ng_step, but the scratch the step's kernels hand to each other (the
+ * per-step table, the partial sums of the Gram-row reduction, the row-chunk sums of the small-rank
+ * projection, the padded gradient tails) lies in a device array of the library itself instead of
+ * the caller's workspace.  That array has NG_STATIC_SCRATCH_BYTES bytes per GPU, is held by every
+ * GPU the library has run on until the process ends, and is shared by every handle and every call
+ * on that GPU: calls of ng_step_static that overlap on one GPU (two streams, two threads) race;
+ * calls ordered on one stream, also from different handles, are fine (each call rewrites all it
+ * reads; nothing in the array has to start at zero).  A layer set whose step scratch exceeds the
+ * array returns NG_ERR_WORKSPACE (the per-matrix share is 2 KiB * s for the reduction plus, for
+ * fp32 sets of rank <= 16, ceil(m/128) * rank class * ldn * 4 bytes); nothing is launched then.
+ * Calls no hipMalloc / hipFree.  The handle still comes from ng_init_state (its workspace keeps
+ * the static tables and the refresh's scratch). */
+#define NG_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int ng_step_static(ng_state* st, const void* const* grads, void* const* weights, float lr,
+                   ng_stream stream);
+
 int ng_get_counters(const ng_state* st, int mat, int64_t* t, int32_t* head, int32_t* count,
                     int64_t* n_refresh);
 /* Resume: requires 0 <= head < max(s,1), 0 <= count <= s, t >= 0. */

@@ -66,6 +66,7 @@ _lib.ng_init_state.argtypes = [_P(ng_matrix_desc), _P(ng_matrix_buffers), C.c_in
 _lib.ng_refresh_projector.argtypes = [C.c_void_p, _P(C.c_void_p), C.c_void_p]
 _lib.ng_commit_projector.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
 _lib.ng_step.argtypes = [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_float, C.c_void_p]
+_lib.ng_step_static.argtypes = [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_float, C.c_void_p]
 _lib.ng_get_counters.argtypes = [C.c_void_p, C.c_int, _P(C.c_int64), _P(C.c_int32), _P(C.c_int32), _P(C.c_int64)]
 _lib.ng_set_counters.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32, C.c_int64]
 _lib.ng_get_layout.argtypes = [C.c_void_p, C.c_int, _P(ng_matrix_layout)]
@@ -82,7 +83,7 @@ _lib.ng_strerror.restype = C.c_char_p
 _lib.ng_destroy.argtypes = [C.c_void_p]
 _lib.ng_destroy.restype = None
 for _name in ("ng_default_hparams", "ng_query_sizes", "ng_init_state", "ng_refresh_projector", "ng_commit_projector",
-              "ng_step", "ng_get_counters", "ng_set_counters", "ng_get_layout", "ng_get_status", "ng_set_profiling",
+              "ng_step", "ng_step_static", "ng_get_counters", "ng_set_counters", "ng_get_layout", "ng_get_status", "ng_set_profiling",
               "ng_get_phase_ms"):
     getattr(_lib, _name).restype = C.c_int
 
@@ -159,6 +160,12 @@ def ng_step(st, grad_ptrs, weight_ptrs, lr: float, stream: int) -> None:
     _check(_lib.ng_step(st, grad_ptrs if not isinstance(grad_ptrs, (list, tuple)) else _ptr_array(grad_ptrs),
                         weight_ptrs if not isinstance(weight_ptrs, (list, tuple)) else _ptr_array(weight_ptrs),
                         lr, C.c_void_p(stream)), "ng_step")
+
+
+def ng_step_static(st, grad_ptrs, weight_ptrs, lr: float, stream: int) -> None:
+    _check(_lib.ng_step_static(st, grad_ptrs if not isinstance(grad_ptrs, (list, tuple)) else _ptr_array(grad_ptrs),
+                               weight_ptrs if not isinstance(weight_ptrs, (list, tuple)) else _ptr_array(weight_ptrs),
+                               lr, C.c_void_p(stream)), "ng_step_static")
 
 
 def ng_get_counters(st, mat: int):
@@ -268,6 +275,9 @@ class LayerSet:
 
     def step(self, grads, weights, lr: float) -> None:
         ng_step(self.st, self._ptrs(grads), self._ptrs(weights), lr, self.stream())
+
+    def step_static(self, grads, weights, lr: float) -> None:
+        ng_step_static(self.st, self._ptrs(grads), self._ptrs(weights), lr, self.stream())
 
     def status(self) -> int:
         return ng_get_status(self.st, self.stream())

@@ -47,9 +47,10 @@ __global__ void k_upload_dyn(MatDyn* table, DynChunk chunk, int first, int n, co
     // the zero-padded copy of the last gradient row's final partial 8-column chunk (bf16 projection)
     const MatDev& md = mats[first + i];
     const int nf = md.n & 7;
-    if (md.side == NG_SIDE_RIGHT || nf == 0 || md.tail8 == nullptr || chunk.e[i].g == nullptr) return;
+    if (md.side == NG_SIDE_RIGHT || nf == 0 || md.tail8_off < 0 || chunk.e[i].g == nullptr) return;
     const bf16_t* last = (const bf16_t*)chunk.e[i].g + (long long)(md.m - 1) * md.ld_g + (md.n - nf);
-    for (int x = 0; x < 8; ++x) md.tail8[x] = x < nf ? last[x] : (bf16_t)0;
+    bf16_t* tail8 = step_scratch<bf16_t>(table, md.tail8_off);
+    for (int x = 0; x < 8; ++x) tail8[x] = x < nf ? last[x] : (bf16_t)0;
 }
 
 hipError_t launch_upload_dyn(MatDyn* table, const DynChunk& chunk, int first, int n, const MatDev* mats,
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
     __syncthreads();
     if ((int)threadIdx.x < s) {
         double v = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
-        ((NG_AS1 double*)md.dot_parts)[(long long)c.ti * s + threadIdx.x] = v;
+        ((NG_AS1 double*)step_scratch<double>(dyn, md.dot_parts_off))[(long long)c.ti * s + threadIdx.x] = v;
     }
 }
 
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(64) void k_solve(const MatDev* __restrict__ mats, c
         if (sub < nsub) {
             // eight loads in flight, added in the order of p
             const int np = md.dot_nparts;
-            const double* __restrict__ parts = md.dot_parts + j;
+            const double* __restrict__ parts = step_scratch<double>(dyn, md.dot_parts_off) + j;
             for (int p = sub; p < np; p += 8 * nsub) {
                 double x[8];
 #pragma unroll

@@ -915,7 +915,8 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
     ARows a_rm;
     BGrad b_g;
     a_rm.init(md.PbT, md.r, md.ldk, i0, lane, wv);
-    b_g.init(dy.g, md.ld_g, md.m, md.n, j0, lane, wv, md.tail8, zp);
+    b_g.init(dy.g, md.ld_g, md.m, md.n, j0, lane, wv,
+             md.tail8_off >= 0 ? (const void*)step_scratch<char>(dyn, md.tail8_off) : (const void*)zero16, zp);
     auto issue = [&](int kt) {
         unsigned char* stage = smem + (kt % NST) * D::STAGE;
         a_rm.issue(kt, stage, zp, wv);

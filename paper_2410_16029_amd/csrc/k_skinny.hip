@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void k_project_skinny(const MatDev* __restrict
     }
     __syncthreads();
     if (wv == 0 && col < ldn) {
-        float* __restrict__ part = md.skinny_parts + (long long)t.ti * RK * ldn;
+        float* __restrict__ part = step_scratch<float>(dyn, md.skinny_parts_off) + (long long)t.ti * RK * ldn;
 #pragma unroll
         for (int q = 0; q < RK; ++q) {
             f32x4_t s = acc[q];
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(64) void k_skinny_reduce(const MatDev* __restrict__
     const int ldn = md.ldn;
     if (col >= ldn || q >= md.r) return;
     const int chunks = (md.m + kSkinnyRows - 1) / kSkinnyRows;
-    const float* __restrict__ part = md.skinny_parts + (long long)q * ldn + col;
+    const float* __restrict__ part = step_scratch<float>(dyn, md.skinny_parts_off) + (long long)q * ldn + col;
     const long long cstride = (long long)rk * ldn;
     f32x4_t s = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < chunks; c += 8) {             // eight loads in flight, added in chunk order

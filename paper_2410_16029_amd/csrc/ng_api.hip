@@ -6,12 +6,18 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "ng_internal.h"
 
 using namespace ng;
+
+// Step scratch of ng_step_static: device memory of the library itself, so that entry point needs
+// neither a workspace argument nor an allocation.  Never passed to a kernel by name (in host code
+// the name is not a device address): see static_scratch_of_current_device.
+static __device__ __align__(256) unsigned char g_ng_static_scratch[ng::kStaticScratchBytes];
 
 namespace {
 
@@ -126,7 +132,11 @@ struct Plan {
     std::vector<TileRef> proj, upd, dots, patches, skinny;
     int skinny_rk;                              // 0: the MFMA / fp32-GEMM projection and update
     int proj_direct, proj_staged, proj_right;   // lengths of the three runs of proj
-    size_t off_status, off_mats, off_dyn, off_tail8, off_proj, off_upd, off_dots, off_patches, off_skinny, off_scratch;
+    size_t off_status, off_mats, off_step, off_proj, off_upd, off_dots, off_patches, off_skinny, off_scratch;
+    // the scratch block of one step: the per-step table, then what the step's kernels hand to each
+    // other (offsets from the start of the block; per matrix)
+    size_t step_tail8_off, step_bytes;
+    std::vector<size_t> step_parts_off, step_skinny_off;
     size_t total;
 };
 
@@ -196,8 +206,21 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     size_t off = 0;
     p->off_status = off; off += 256;
     p->off_mats = off;   off += align_up(sizeof(MatDev) * (size_t)n_mats, 256);
-    p->off_dyn = off;    off += align_up(sizeof(MatDyn) * (size_t)n_mats, 256);
-    p->off_tail8 = off;  off += align_up((size_t)16 * (size_t)n_mats, 256);
+    {
+        size_t so = align_up(sizeof(MatDyn) * (size_t)n_mats, 256);
+        p->step_tail8_off = so;
+        so += align_up((size_t)16 * (size_t)n_mats, 256);
+        p->step_parts_off.resize(n_mats);
+        p->step_skinny_off.resize(n_mats);
+        for (int i = 0; i < n_mats; ++i) {
+            p->step_parts_off[i] = so;
+            so += p->sz[i].ws_parts;
+            p->step_skinny_off[i] = so;
+            so += p->sz[i].ws_skinny;
+        }
+        p->step_bytes = so;
+    }
+    p->off_step = off;   off += p->step_bytes;
     p->off_proj = off;   off += align_up(sizeof(TileRef) * p->proj.size(), 256);
     p->off_upd = off;    off += align_up(sizeof(TileRef) * p->upd.size(), 256);
     p->off_dots = off;   off += align_up(sizeof(TileRef) * (size_t)n_mats * kDotPartsMax, 256);
@@ -206,8 +229,7 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     p->off_scratch = off;
     for (int i = 0; i < n_mats; ++i) {
         const Sizes& z = p->sz[i];
-        off += z.ws_parts + 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag +
-               z.ws_carry + z.ws_skinny;
+        off += 3 * z.ws_y + z.ws_bm + z.ws_t + z.ws_linv + z.ws_ritz + z.ws_order + z.ws_flag + z.ws_carry;
     }
     p->total = off;
 }
@@ -254,7 +276,8 @@ namespace {
         if (e_ != hipSuccess) return NG_ERR_HIP; \
     } while (0)
 
-int upload_dyn(ng_state* st, const void* const* grads, void* const* weights, bool stepping, hipStream_t stream) {
+int upload_dyn(ng_state* st, MatDyn* dyn, const void* const* grads, void* const* weights, bool stepping,
+               hipStream_t stream) {
     DynChunk chunk;
     const int s = st->hp.s;
     for (int first = 0; first < st->n_mats; first += kDynChunk) {
@@ -278,7 +301,7 @@ int upload_dyn(ng_state* st, const void* const* grads, void* const* weights, boo
                 e.bc2 = 1.f;
             }
         }
-        NG_HIP(launch_upload_dyn(st->d_dyn, chunk, first, n,
+        NG_HIP(launch_upload_dyn(dyn, chunk, first, n,
                                  (stepping && st->hp.grad_dtype == NG_BF16) ? st->d_mats : nullptr, stream));
     }
     return NG_OK;
@@ -311,7 +334,7 @@ int clear_history(ng_state* st, hipStream_t stream) {
 // The refresh's products with the gradient: OP_G_B2A / OP_G_C2A (Ya = G Y), OP_GT_C2B (Yb = G^T Y),
 // OP_QT_G (Bm = Ya^T G).  bf16 gradients on the left side take three bf16 MFMA
 // products (launch_refresh_x3), everything else the fp32 GEMM.
-int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc);
+int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc, const MatDyn* dyn = nullptr);
 int gradient_product(ng_state* st, GemmOp op, bool last, hipStream_t stream, const StepScalars& sc) {
     if (st->hp.grad_dtype == NG_BF16 && !(st->sides & 2)) {
         // planes of the sketch that enter: the random test matrix needs one, the last basis and
@@ -332,8 +355,8 @@ int gradient_product(ng_state* st, GemmOp op, bool last, hipStream_t stream, con
     return gemm(st, op, stream, sc);
 }
 
-int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc) {
-    NG_HIP(launch_gemm_f32(op, st->d_mats, st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], st->max_tk[op],
+int gemm(ng_state* st, GemmOp op, hipStream_t stream, const StepScalars& sc, const MatDyn* dyn) {
+    NG_HIP(launch_gemm_f32(op, st->d_mats, dyn ? dyn : st->d_dyn, st->n_mats, st->max_ti[op], st->max_tj[op], st->max_tk[op],
                            st->hp.grad_dtype, sc, (const char*)st->d_status + 64, stream));
     return NG_OK;
 }
@@ -381,6 +404,93 @@ void drain_events(ng_state* st, bool all) {
         }
         st->ev_pending -= 1;
     }
+}
+
+// One step.  `dyn` is the start of the scratch block the step's kernels use: the per-step table and,
+// behind it, what they hand to each other (see MatDev::dot_parts_off).
+int step_on_scratch(ng_state* st, const void* const* grads, void* const* weights, float lr, hipStream_t stream,
+                    MatDyn* dyn) {
+    if (!grads || !weights) return NG_ERR_INVALID_ARG;
+    if (!isfinite(lr)) return NG_ERR_HPARAM;
+    for (int i = 0; i < st->n_mats; ++i)
+        if (!grads[i] || !weights[i]) return NG_ERR_INVALID_ARG;
+    if (!st->projector_valid) return NG_ERR_NO_PROJECTOR;
+    if (!st->tables_valid) return NG_ERR_HIP;
+    const StepScalars sc = make_scalars(st, lr);
+    const bool bf = st->hp.grad_dtype == NG_BF16;
+    const bool prof = st->profiling && st->ev_created;
+    int slot = 0;
+    if (prof) {
+        drain_events(st, false);
+        slot = st->ev_head;
+    }
+    int rc;
+    if ((rc = upload_dyn(st, dyn, grads, weights, true, stream)) != NG_OK) return rc;
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
+    const int skinny_rk = st->plan.skinny_rk;
+    if (skinny_rk) NG_HIP(launch_project_skinny(st->d_mats, dyn, st->d_skinny, (int)st->plan.skinny.size(), st->n_mats,
+                                                st->max_ldn, skinny_rk, stream));
+    else if (bf) NG_HIP(launch_project_bf16(st->d_mats, dyn, st->d_proj, st->plan.proj_direct, st->plan.proj_staged,
+                                            st->plan.proj_right, st->max_r, sc.hist_bf16, (const char*)st->d_status + 64,
+                                            stream));
+    else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc, dyn)) != NG_OK) return rc;
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
+    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, -1, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
+    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, dyn, 0, st->n_mats, sc, -1, st->d_status, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_ADAM], stream));
+    NG_HIP(launch_transform_adam(st->d_mats, dyn, st->d_patches, (int)st->plan.patches.size(), sc,
+                                 st->hp.grad_dtype, st->d_status, stream));
+
+    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
+    if (skinny_rk) NG_HIP(launch_update_skinny(st->d_mats, dyn, st->d_skinny, (int)st->plan.skinny.size(), skinny_rk,
+                                               sc, stream));
+    else if (bf) NG_HIP(launch_update_bf16(st->d_mats, dyn, st->d_upd, (int)st->plan.upd.size(), sc,
+                                           (const char*)st->d_status + 64, st->sides, stream));
+    else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc, dyn)) != NG_OK) return rc;
+
+    if (prof) {
+        NG_HIP(hipEventRecord(st->ev[slot][NG_NPHASE], stream));
+        st->ev_head = (st->ev_head + 1) % kProfRing;
+        st->ev_pending += 1;
+    }
+
+    const int s = st->hp.s;
+    for (int i = 0; i < st->n_mats; ++i) {
+        st->t[i] += 1;
+        if (s > 0) {
+            st->head[i] = (st->head[i] + 1) % s;
+            if (st->count[i] < s) st->count[i] += 1;
+        }
+    }
+    return NG_OK;
+}
+
+// ---------------------------------------------------------------- the library's own step scratch
+// One array per GPU (every device that loads this code object holds its own copy at its own
+// address).  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address is looked up once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+char* g_static_ptr[kMaxDevices] = {nullptr};
+
+int static_scratch_of_current_device(char** out) {
+    int dev = -1;
+    NG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return NG_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        NG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_ng_static_scratch)));
+        if (!p) return NG_ERR_HIP;
+        g_static_ptr[dev] = (char*)p;
+    }
+    *out = g_static_ptr[dev];
+    return NG_OK;
 }
 
 }  // namespace
@@ -471,7 +581,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
         const Plan& pl = st->plan;
         st->d_status = (int*)(ws + pl.off_status);
         st->d_mats = (MatDev*)(ws + pl.off_mats);
-        st->d_dyn = (MatDyn*)(ws + pl.off_dyn);
+        st->d_dyn = (MatDyn*)(ws + pl.off_step);
         st->d_proj = (TileRef*)(ws + pl.off_proj);
         st->d_upd = (TileRef*)(ws + pl.off_upd);
         st->d_dots = (TileRef*)(ws + pl.off_dots);
@@ -509,9 +619,10 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
                 char* ab = (char*)bufs[i].buf[NG_BUF_AUX];
                 md.Pb = (bf16_t*)(ab + z.aux_pb_off);
                 md.PbT = (bf16_t*)(ab + z.aux_pbt_off);
-                md.tail8 = (bf16_t*)(ws + pl.off_tail8 + (size_t)16 * i);
             }
-            md.dot_parts = (double*)(ws + off); off += z.ws_parts;
+            md.tail8_off = hp->grad_dtype == NG_BF16 ? (long long)(pl.step_tail8_off + (size_t)16 * i) : -1;
+            md.dot_parts_off = (long long)pl.step_parts_off[i];
+            md.skinny_parts_off = z.ws_skinny ? (long long)pl.step_skinny_off[i] : -1;
             md.Ya = (float*)(ws + off); off += z.ws_y;
             md.Yb = (float*)(ws + off); off += z.ws_y;
             md.Yc = (float*)(ws + off); off += z.ws_y;
@@ -522,7 +633,6 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.order = (int*)(ws + off); off += z.ws_order;
             md.jflag = (int*)(ws + off); off += z.ws_flag;
             md.carry = z.ws_carry ? (float*)(ws + off) : nullptr; off += z.ws_carry;
-            md.skinny_parts = z.ws_skinny ? (float*)(ws + off) : nullptr; off += z.ws_skinny;
             md.lp = z.lp;
             // units of the Gram-row reduction: 16-byte vectors of a slot
             const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
@@ -626,7 +736,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
     hipStream_t stream = (hipStream_t)stream_;
     const StepScalars sc = make_scalars(st, 0.f);
     int rc;
-    if ((rc = upload_dyn(st, grads, nullptr, false, stream)) != NG_OK) return rc;
+    if ((rc = upload_dyn(st, st->d_dyn, grads, nullptr, false, stream)) != NG_OK) return rc;
 
     // randomised subspace iteration: Ya = orth(G Omega); q times { Yb = orth(G^T Ya); Ya = orth(G Yb) }
     NG_HIP(launch_fill_gaussian(st->d_mats, st->n_mats, st->max_n, st->hp.seed,
@@ -690,65 +800,18 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
 }
 
 int ng_step(ng_state* st, const void* const* grads, void* const* weights, float lr, ng_stream stream_) {
-    if (!st || !grads || !weights) return NG_ERR_INVALID_ARG;
-    if (!isfinite(lr)) return NG_ERR_HPARAM;
-    for (int i = 0; i < st->n_mats; ++i)
-        if (!grads[i] || !weights[i]) return NG_ERR_INVALID_ARG;
-    if (!st->projector_valid) return NG_ERR_NO_PROJECTOR;
+    if (!st) return NG_ERR_INVALID_ARG;
+    return step_on_scratch(st, grads, weights, lr, (hipStream_t)stream_, st->d_dyn);
+}
+
+int ng_step_static(ng_state* st, const void* const* grads, void* const* weights, float lr, ng_stream stream_) {
+    if (!st) return NG_ERR_INVALID_ARG;
+    if (st->plan.step_bytes > kStaticScratchBytes) return NG_ERR_WORKSPACE;
     if (!st->tables_valid) return NG_ERR_HIP;
-    hipStream_t stream = (hipStream_t)stream_;
-    const StepScalars sc = make_scalars(st, lr);
-    const bool bf = st->hp.grad_dtype == NG_BF16;
-    const bool prof = st->profiling && st->ev_created;
-    int slot = 0;
-    if (prof) {
-        drain_events(st, false);
-        slot = st->ev_head;
-    }
-    int rc;
-    if ((rc = upload_dyn(st, grads, weights, true, stream)) != NG_OK) return rc;
-
-    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_PROJECT], stream));
-    const int skinny_rk = st->plan.skinny_rk;
-    if (skinny_rk) NG_HIP(launch_project_skinny(st->d_mats, st->d_dyn, st->d_skinny, (int)st->plan.skinny.size(), st->n_mats,
-                                                st->max_ldn, skinny_rk, stream));
-    else if (bf) NG_HIP(launch_project_bf16(st->d_mats, st->d_dyn, st->d_proj, st->plan.proj_direct, st->plan.proj_staged,
-                                            st->plan.proj_right, st->max_r, sc.hist_bf16, (const char*)st->d_status + 64,
-                                            stream));
-    else if ((rc = gemm(st, OP_PROJECT_F32, stream, sc)) != NG_OK) return rc;
-
-    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_GRAM], stream));
-    if (sc.use_fisher) NG_HIP(launch_gram_row(st->d_mats, st->d_dyn, st->d_dots, st->n_dots, sc.s, sc.hist_bf16, -1, stream));
-
-    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_SOLVE], stream));
-    if (sc.use_fisher) NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, -1, st->d_status, stream));
-
-    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_ADAM], stream));
-    NG_HIP(launch_transform_adam(st->d_mats, st->d_dyn, st->d_patches, (int)st->plan.patches.size(), sc,
-                                 st->hp.grad_dtype, st->d_status, stream));
-
-    if (prof) NG_HIP(hipEventRecord(st->ev[slot][NG_PHASE_UPDATE], stream));
-    if (skinny_rk) NG_HIP(launch_update_skinny(st->d_mats, st->d_dyn, st->d_skinny, (int)st->plan.skinny.size(), skinny_rk,
-                                               sc, stream));
-    else if (bf) NG_HIP(launch_update_bf16(st->d_mats, st->d_dyn, st->d_upd, (int)st->plan.upd.size(), sc,
-                                           (const char*)st->d_status + 64, st->sides, stream));
-    else if ((rc = gemm(st, OP_UPDATE_F32, stream, sc)) != NG_OK) return rc;
-
-    if (prof) {
-        NG_HIP(hipEventRecord(st->ev[slot][NG_NPHASE], stream));
-        st->ev_head = (st->ev_head + 1) % kProfRing;
-        st->ev_pending += 1;
-    }
-
-    const int s = st->hp.s;
-    for (int i = 0; i < st->n_mats; ++i) {
-        st->t[i] += 1;
-        if (s > 0) {
-            st->head[i] = (st->head[i] + 1) % s;
-            if (st->count[i] < s) st->count[i] += 1;
-        }
-    }
-    return NG_OK;
+    char* scratch = nullptr;
+    int rc = static_scratch_of_current_device(&scratch);
+    if (rc != NG_OK) return rc;
+    return step_on_scratch(st, grads, weights, lr, (hipStream_t)stream_, (MatDyn*)scratch);
 }
 
 int ng_get_counters(const ng_state* st, int mat, int64_t* t, int32_t* head, int32_t* count, int64_t* n_refresh) {

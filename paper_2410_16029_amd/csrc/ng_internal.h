@@ -47,7 +47,11 @@ struct MatDev {
     bf16_t* PbT;      // [ldk/32][r][32]  bf16 copy of P^T, k-blocked: (rho, i) at ((i/32) r + rho) 32 + i%32
                       // (operands of the update / projection GEMMs: the 64 bytes one row gives to a 32-deep
                       // stage lie next to its neighbours', so a tile's stage is one run of whole cache lines)
-    double* dot_parts;   // [kDotPartsMax][s]
+    // Scratch of one step lies behind the per-step table (MatDyn[n_mats]) in one block: the three
+    // offsets below are in bytes from the start of that table (the `dyn` argument of the kernels),
+    // -1 where a matrix has none.  The block is the front of the caller's workspace for ng_step and
+    // the library's own static device array for ng_step_static.
+    long long dot_parts_off;   // double [kDotPartsMax][s]: partial sums of the Gram-row reduction
     int dot_nparts;      // workgroups of the Gram-row reduction for this matrix
     int dot_iters;       // grid-stride iterations per workgroup
     // refresh scratch (all in the workspace)
@@ -62,13 +66,13 @@ struct MatDev {
     int* order;       // [lp]
     int* jflag;       // [0] rotations this sweep, [1] converged
     float* carry;     // [r][ldn] scratch of the history carry-over (null unless enabled)
-    float* skinny_parts;   // [ceil(m/kSkinnyRows)][rk][ldn] row-chunk sums of the small-rank projection (else null)
-    bf16_t* tail8;    // 8 bf16 in the workspace: the last gradient row's columns from the last multiple of
-                      // 8 on, zero-padded (rewritten every step, see launch_upload_dyn)
+    long long skinny_parts_off;   // float [ceil(m/kSkinnyRows)][rk][ldn] row-chunk sums of the small-rank projection
+    long long tail8_off;   // 8 bf16: the last gradient row's columns from the last multiple of 8 on,
+                           // zero-padded (rewritten every step, see launch_upload_dyn)
     int lp;           // l rounded up to a whole number of Jacobi block pairs: order and row pitch of T, Linv
 };
 
-// Per-step values: uploaded into the workspace by a tiny kernel that receives them by value.
+// Per-step values: uploaded into the step's scratch block by a tiny kernel that receives them by value.
 struct MatDyn {
     const void* g;
     void* w;
@@ -80,6 +84,14 @@ struct MatDyn {
 struct DynChunk {
     MatDyn e[kDynChunk];
 };
+
+constexpr size_t kStaticScratchBytes = NG_STATIC_SCRATCH_BYTES;   // the library's own step scratch (ng_step_static)
+
+// address inside the step's scratch block, which starts with the per-step table
+template <typename T>
+__device__ __forceinline__ T* step_scratch(const MatDyn* dyn, long long off) {
+    return reinterpret_cast<T*>(reinterpret_cast<char*>(const_cast<MatDyn*>(dyn)) + off);
+}
 
 struct StepScalars {
     float lambda;

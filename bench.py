@@ -49,15 +49,16 @@ def cpu_baseline(cfg, ls, grads_pool, weights, per_shape_s=5.0):
     import torch
 
     import oracle
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from parity_harness import oracle_hparams, to_f64
+
+    def to_f64(t):
+        return t.detach().to(torch.float64).cpu().numpy()
 
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    hp = oracle_hparams(ls)
+    hp = oracle.HParams(s=cfg.s, lam=cfg.lam, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_dtype=cfg.dtype)
     mats = cfg.matrices()
     total = 0.0
     parts = []
@@ -100,6 +101,7 @@ def main() -> int:
                     help="auto: right-side projection where m > n (the benchmark configurations fix left)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true")
+    ap.add_argument("--no-microbench", action="store_true")
     ap.add_argument("--refresh-in-loop", type=int, default=0, help="refresh every this many timed steps (0 = never)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 10 plain device-to-device copies of MIB MiB "
@@ -152,6 +154,11 @@ def main() -> int:
     wptr = B._ptr_array([w.data_ptr() for w in weights])
     st, cur = ls.st, ls.stream()
 
+    # the timed steps must find the history ring full (steady state): at least s warm-up steps
+    if args.warmup < cfg.s:
+        print("bench.py: warm-up raised from %d to %d steps (the history ring holds s = %d slots)"
+              % (args.warmup, cfg.s, cfg.s), file=sys.stderr)
+        args.warmup = cfg.s
     for k in range(args.warmup):
         B.ng_step(st, gptr[k % len(pool)], wptr, cfg.lr, cur)
     torch.cuda.synchronize()
@@ -188,18 +195,44 @@ def main() -> int:
                     ph["frac_mfma"] = round(ph["TFLOP/s"] / MFMA_PEAK_TFLOPS[cfg.dtype], 4)
             phases[name] = ph
 
+    from paper_2410_16029_amd import build as ngbuild
+
     def measured_traffic(kernel):
-        """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+        """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary -- only if that
+        summary was taken on a library built from the very sources the loaded one was built from."""
         path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, args.config))
-        if args.hist_dtype != "f32":
-            return None   # the committed counter summaries cover the f32-history configuration
+        if args.hist_dtype != "f32" or args.sides != "left" or args.dtype is not None:
+            return None   # the committed counter summaries cover the configuration as BASELINE.json states it
+        have = ngbuild.built_hash()
+        if have is None or have != ngbuild.source_hash():
+            return None
+        traffic, recorded = None, None
         try:
             for line in open(path):
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":")[1])
+                    traffic = float(line.split(":")[1])
+                if line.startswith("kernel_source_hash:"):
+                    recorded = line.split(":")[1].strip()
         except OSError:
-            pass
-        return None
+            return None
+        return traffic if recorded == have else None
+
+    def microbench():
+        """Measured ceilings on this GPU: plain streaming copy and read of 1 GiB (beyond the 256 MB
+        memory-side cache) and a bare bf16 MFMA loop."""
+        n = 1 << 30
+        a = torch.ones(n // 4, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        out = {}
+        ms, work = B.ng_microbench(B.NG_MB_COPY, a.data_ptr(), b.data_ptr(), n, 20, cur)
+        out["stream_copy_GB/s"] = round(work / (ms * 1e-3) / 1e9, 1)
+        ms, work = B.ng_microbench(B.NG_MB_READ, a.data_ptr(), b.data_ptr(), n, 20, cur)
+        out["stream_read_GB/s"] = round(work / (ms * 1e-3) / 1e9, 1)
+        ms, work = B.ng_microbench(B.NG_MB_MFMA_BF16, 0, b.data_ptr(), 8192, 20, cur)
+        out["mfma_bf16_TFLOP/s"] = round(work / (ms * 1e-3) / 1e12, 1)
+        del a, b
+        return out
 
     roofline = None
     if phases:
@@ -235,6 +268,12 @@ def main() -> int:
                                                     / (ms_per_step * 1e-3) / HBM_PEAK_GBS, 4)},
         "refresh_ms": round(refresh_ms, 2),
     }
+    if phases and cfg.dtype == "bf16":
+        fr = {k: phases[k].get("frac_mfma") for k in ("project", "update")}
+        out["gemm_mfma_target"] = {"target_frac": 0.6, "project": fr["project"], "update": fr["update"],
+                                   "met": all(v is not None and v >= 0.6 for v in fr.values())}
+    if not args.no_microbench:
+        out["microbench"] = microbench()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, ls, pool, weights)
     print(json.dumps(out))

@@ -234,6 +234,21 @@ enum { NG_PHASE_PROJECT = 0, NG_PHASE_GRAM, NG_PHASE_SOLVE, NG_PHASE_ADAM, NG_PH
 int ng_set_profiling(ng_state* st, int enabled);
 int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset);
 
+/* Measured ceilings of the GPU the library runs on, to read the step's roofline fractions against:
+ * NG_MB_COPY      plain streaming copy a -> b of `bytes` bytes (device pointers, 16-byte aligned,
+ *                 bytes % 16 == 0); *work = 2 * bytes (read + written);
+ * NG_MB_READ      streaming read of a; b: >= 4 bytes of device memory (never written in practice);
+ *                 *work = bytes;
+ * NG_MB_MFMA_BF16 a bare loop of v_mfma_f32_32x32x16_bf16 on register operands, two wavefronts per
+ *                 SIMD on all 256 units; a ignored, b as for NG_MB_READ, `bytes` = loop trips per
+ *                 wavefront (8 MFMAs each); *work = floating-point operations.
+ * One untimed launch, then `reps` launches timed with HIP events on `stream` (synchronises).
+ * *ms = mean milliseconds per launch, *work = bytes or flops per launch.  No handle needed;
+ * allocates nothing. */
+enum { NG_MB_COPY = 0, NG_MB_READ = 1, NG_MB_MFMA_BF16 = 2 };
+int ng_microbench(int which, const void* a, void* b, size_t bytes, int reps, ng_stream stream,
+                  double* ms, double* work);
+
 const char* ng_strerror(int code);
 
 /* sizeof of a structure of this header as the library was compiled: which = 0 ng_matrix_desc,

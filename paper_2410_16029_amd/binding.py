@@ -73,6 +73,9 @@ _lib.ng_get_layout.argtypes = [C.c_void_p, C.c_int, _P(ng_matrix_layout)]
 _lib.ng_get_status.argtypes = [C.c_void_p, C.c_void_p]
 _lib.ng_set_profiling.argtypes = [C.c_void_p, C.c_int]
 _lib.ng_get_phase_ms.argtypes = [C.c_void_p, _P(C.c_double), _P(C.c_int64), C.c_int]
+_lib.ng_microbench.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, _P(C.c_double),
+                               _P(C.c_double)]
+_lib.ng_microbench.restype = C.c_int
 _lib.ng_struct_size.argtypes = [C.c_int]
 _lib.ng_struct_size.restype = C.c_size_t
 for _which, _cls in enumerate((ng_matrix_desc, ng_hparams, ng_matrix_buffers, ng_matrix_layout)):
@@ -197,6 +200,17 @@ def ng_get_phase_ms(st, reset: bool = True):
     steps = C.c_int64()
     _check(_lib.ng_get_phase_ms(st, ms, C.byref(steps), int(reset)), "ng_get_phase_ms")
     return [ms[i] for i in range(NG_NPHASE)], steps.value
+
+
+NG_MB_COPY, NG_MB_READ, NG_MB_MFMA_BF16 = 0, 1, 2
+
+
+def ng_microbench(which: int, a_ptr: int, b_ptr: int, nbytes: int, reps: int, stream: int):
+    """Returns (mean ms per launch, bytes or flops per launch)."""
+    ms, work = C.c_double(), C.c_double()
+    _check(_lib.ng_microbench(which, C.c_void_p(a_ptr), C.c_void_p(b_ptr), nbytes, reps, C.c_void_p(stream),
+                              C.byref(ms), C.byref(work)), "ng_microbench")
+    return ms.value, work.value
 
 
 def ng_destroy(st) -> None:

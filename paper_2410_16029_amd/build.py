@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libng.so")
-SOURCES = ["ng_api.hip", "k_elementwise.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_refresh.hip", "k_skinny.hip"]
+SOURCES = ["ng_api.hip", "k_elementwise.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_refresh.hip", "k_skinny.hip",
+           "k_microbench.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -19,6 +20,27 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
+
+
+def source_hash() -> str:
+    """Hash of everything the library is compiled from (kernel sources, internal and public headers)."""
+    import hashlib
+
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    files.append(os.path.join(ROOT, "include", "ng.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def built_hash():
+    """source_hash() as it was when libng.so was last built here, or None."""
+    try:
+        return open(os.path.join(HERE, "_build", "source_hash.txt")).read().strip()
+    except OSError:
+        return None
 
 
 def _hipcc() -> str:
@@ -46,6 +68,8 @@ def build(verbose: bool = True, extra=()) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (res.stdout, res.stderr))
+    with open(os.path.join(objdir, "source_hash.txt"), "w") as f:
+        f.write(source_hash() + "\n")
     if verbose:
         print("built", LIB)
     return LIB

@@ -963,14 +963,17 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
             lds_read_tr16(f[kk].bhi[nj], cur + b_off[nj], kk * 16 * BGrad::ROW_BYTES + 4 * BGrad::ROW_BYTES);
         }
     };
-    auto done = [&]() {
+    // Wait for the fragments of step kk.  LDS reads complete in issue order, so when the reads of the other
+    // step were issued after these (LATER of them still allowed in flight) the wait need not cover them.
+    constexpr int STEP_READS = C::MI + 2 * C::NJ;
+    static_assert(STEP_READS <= 15, "the wait count of one step must fit the counter");
+    auto done_step = [&](int kk, bool later_in_flight) {   // kk is a literal at every call
+        if (later_in_flight) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(STEP_READS) : "memory");
+        else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
+        for (int mi = 0; mi < C::MI; ++mi) asm volatile("" : "+v"(f[kk].a[mi])::"memory");
 #pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi) lds_read_done(f[kk].a[mi]);
-#pragma unroll
-            for (int nj = 0; nj < C::NJ; ++nj) lds_read_tr16_done(f[kk].blo[nj], f[kk].bhi[nj]);
-        }
+        for (int nj = 0; nj < C::NJ; ++nj) asm volatile("" : "+v"(f[kk].blo[nj]), "+v"(f[kk].bhi[nj])::"memory");
     };
     auto mma_step = [&](int kk) {
 #pragma unroll
@@ -1003,19 +1006,20 @@ __global__ __launch_bounds__(C::NT) void k_project_bf16_dl(const MatDev* __restr
     read_frags(0);
     for (int kt = 0; kt < nk; ++kt) {
         const bool more = kt + 1 < nk;
+        done_step(0, true);    // the reads of step 1 were issued after those of step 0
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        done_step(1, false);   // this wave holds all of stage kt now
         if (more) {
             const int ahead = nk - kt - 2;   // stages issued beyond kt + 1
             wait_all_but(ahead < NST - 2 ? ahead : NST - 2);
-        }
-        done();
-        if (more) {
-            // a bare barrier: __syncthreads() would also wait for the loads in flight
+            // a bare barrier: __syncthreads() would also wait for the loads in flight.  Behind it every
+            // wave has read buffer kt % NST to the end and stage kt + 1 has landed.
             asm volatile("s_barrier" ::: "memory");
             if (kt + NST < nk) issue(kt + NST);
+            read_step(kt + 1, 0);
         }
-        mma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) read_step(kt + 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         mma_step(1);
         __builtin_amdgcn_sched_barrier(0);

@@ -890,6 +890,47 @@ int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset) {
     return NG_OK;
 }
 
+int ng_microbench(int which, const void* a, void* b, size_t bytes, int reps, ng_stream stream_, double* ms,
+                  double* work) {
+    if (!b || !ms || !work || reps < 1 || reps > 10000) return NG_ERR_INVALID_ARG;
+    if (which != NG_MB_COPY && which != NG_MB_READ && which != NG_MB_MFMA_BF16) return NG_ERR_INVALID_ARG;
+    if (which != NG_MB_MFMA_BF16 && (!a || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)a & 15))) return NG_ERR_INVALID_ARG;
+    if (which == NG_MB_COPY && ((uintptr_t)b & 15)) return NG_ERR_INVALID_ARG;
+    if (which == NG_MB_MFMA_BF16 && (bytes == 0 || bytes > (1u << 24))) return NG_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    NG_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return NG_ERR_HIP;
+    }
+    double w = 0.0;
+    hipError_t e = hipSuccess;
+    for (int k = -1; k < reps && e == hipSuccess; ++k) {
+        if (k == 0) e = hipEventRecord(e0, stream);
+        if (e != hipSuccess) break;
+        if (which == NG_MB_COPY) {
+            e = launch_mb_copy(a, b, bytes, stream);
+            w = 2.0 * (double)bytes;
+        } else if (which == NG_MB_READ) {
+            e = launch_mb_read(a, bytes, b, stream);
+            w = (double)bytes;
+        } else {
+            e = launch_mb_mfma((int)bytes, 2, b, &w, stream);
+        }
+    }
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return NG_ERR_HIP;
+    *ms = (double)t / reps;
+    *work = w;
+    return NG_OK;
+}
+
 const char* ng_strerror(int code) {
     switch (code) {
         case NG_OK: return "ok";

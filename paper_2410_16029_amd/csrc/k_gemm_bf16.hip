@@ -531,8 +531,8 @@ __device__ __forceinline__ void update_load_w(u32x4_t (&wv4)[C::MI][UpdateTile<C
 
 template <class C>
 __device__ __forceinline__ void update_epilogue(floatx16 (&acc)[C::MI][C::NJ],
-                                                u32x4_t (&wv4)[C::MI][UpdateTile<C>::PER_T], bool cols_full,
-                                                float* Cs, NG_AS1 bf16_t* W, unsigned ld_w, int m, int n, int i0,
+                                                u32x4_t (&wv4)[C::MI][UpdateTile<C>::PER_T], bool vec,
+                                                bool cols_full, float* Cs, NG_AS1 bf16_t* W, unsigned ld_w, int m, int n, int i0,
                                                 int j0, int t, int wm, int wn, int li, int h,
                                                 const StepScalars& sc) {
     constexpr int CH = UpdateTile<C>::CH, PER_T = UpdateTile<C>::PER_T;
@@ -546,7 +546,7 @@ __device__ __forceinline__ void update_epilogue(floatx16 (&acc)[C::MI][C::NJ],
                 for (int e = 0; e < 4; ++e)
                     Cs[(wm * 32 + 8 * g + 4 * h + e) * C::LDC + wn * C::WN + nj * 32 + li] = acc[mi][nj][4 * g + e];
         __syncthreads();
-        if (cols_full) {
+        if (vec) {
 #pragma unroll
             for (int p = 0; p < PER_T; ++p) {
                 const int q = t + C::NT * p;
@@ -568,6 +568,18 @@ __device__ __forceinline__ void update_epilogue(floatx16 (&acc)[C::MI][C::NJ],
                 }
                 if (row < m && col + 8 <= n)
                     __builtin_nontemporal_store(ov, (NG_AS1 u32x4_a2*)(W + ((unsigned)row * ld_w + (unsigned)col)));
+                // the one chunk of a row that straddles column n - 1 (n % 8 != 0: only in the tiles of the
+                // last tile column): its leading n - col elements one by one.  The vector loaded for this
+                // chunk came from the clamped address n - 8 and is not used.
+                if (!cols_full && row < m && col < n && col + 8 > n) {
+                    NG_AS1 bf16_t* wp = W + ((unsigned)row * ld_w + (unsigned)col);
+#pragma unroll
+                    for (int x = 0; x < 7; ++x)
+                        if (col + x < n) {
+                            const float w0 = __uint_as_float((unsigned int)wp[x] << 16);
+                            wp[x] = (bf16_t)f2bf(w0 - (sc.lr_scale * cv[x] + sc.lr_wd * w0));
+                        }
+                }
             }
         } else {
 #pragma unroll
@@ -811,10 +823,13 @@ __global__ __launch_bounds__(C::NT) void k_update_bf16_dl(const MatDev* __restri
 
     NG_AS1 bf16_t* W = (NG_AS1 bf16_t*)dy.w;
     const unsigned ld_w = (unsigned)md.ld_w;
-    const bool cols_full = (n >= 8) && ((n & 7) == 0 || j0 + C::BN <= n);
+    // vec: the weight tile goes through 16-byte accesses (needs 8 columns to clamp an address into);
+    // cols_full: no chunk of this tile straddles column n - 1
+    const bool vec = n >= 8;
+    const bool cols_full = vec && ((n & 7) == 0 || j0 + C::BN <= n);
     u32x4_t wv4[C::MI][UpdateTile<C>::PER_T];
-    if (cols_full) update_load_w<C>(wv4, W, ld_w, m, n, i0, j0, t);
-    update_epilogue<C>(acc, wv4, cols_full, reinterpret_cast<float*>(smem), W, ld_w, m, n, i0, j0, t, wm, wn, li, h,
+    if (vec) update_load_w<C>(wv4, W, ld_w, m, n, i0, j0, t);
+    update_epilogue<C>(acc, wv4, vec, cols_full, reinterpret_cast<float*>(smem), W, ld_w, m, n, i0, j0, t, wm, wn, li, h,
                        sc);
 }
 

@@ -75,5 +75,31 @@ def build(verbose: bool = True, extra=()) -> str:
     return LIB
 
 
+def build_host_sanitizer(verbose: bool = True) -> str:
+    """The library with AddressSanitizer + UndefinedBehaviorSanitizer on its HOST side (the device code is
+    compiled as usual), linked with tests/host/abi_driver.cpp into one executable: the host scheduler's
+    validation, planning and bookkeeping under the sanitizers, no GPU needed.  Returns the executable."""
+    objdir = os.path.join(HERE, "_build", "asan")
+    os.makedirs(objdir, exist_ok=True)
+    san = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(lambda s: _compile(s, objdir, san), SOURCES))
+    exe = os.path.join(objdir, "abi_driver")
+    driver = os.path.join(ROOT, "tests", "host", "abi_driver.cpp")
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-std=c++17", "-O1", "-g", "-fno-gpu-sanitize", "-fsanitize=address",
+           "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-I" + os.path.join(ROOT, "include"),
+           "-x", "c++", driver, "-x", "none", *objs, "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("sanitizer link failed:\n%s\n%s" % (res.stdout, res.stderr))
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    if sys.argv[1:] == ["--host-sanitizer"]:
+        build_host_sanitizer()
+    else:
+        build(extra=sys.argv[1:])

@@ -182,9 +182,17 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
             const int bm = direct ? pbm : sbm, bn = direct ? pbn : sbn;
             for (int tj = 0; tj < ceil_div(z.ldn, bn); ++tj)
                 for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) run.push_back(TileRef{i, ti, tj, 0});
-            // update tiles cover the weight in the caller's orientation on either side
-            for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
-                for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
+            // update tiles cover the weight in the caller's orientation on either side.  Consecutive
+            // tiles share one operand panel; the other operand is swept whole once per panel, so the
+            // loop order keeps the smaller of the two whole operands (rows x r against r x columns) as
+            // the one that is swept: it is the one that has to stay in the L2
+            if (d[i].m > d[i].n) {
+                for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti)
+                    for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj) upd.push_back(TileRef{i, ti, tj, 0});
+            } else {
+                for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
+                    for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
+            }
         }
         for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
             for (int tj = 0; tj < ceil_div(z.ldn, kAdamPatchCols); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});

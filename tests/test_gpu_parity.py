@@ -193,8 +193,8 @@ def test_bf16_c3_c4_shapes_one_block(name):
     assert ls.counters(0) == want
 
 
-@pytest.mark.parametrize("name", ["c3", "c4"])
-def test_bf16_c3_c4_full_layer_set_sampled(name):
+@pytest.mark.parametrize("name", ["c2", "c3", "c4"])
+def test_bf16_c2_c3_c4_full_layer_set_sampled(name):
     # every matrix of the set in one layer set (the grouped launches and tile tables the benchmark
     # times); the oracle follows one matrix of each shape from the first and the last block
     cfg = workloads.CONFIGS[name]

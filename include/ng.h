@@ -67,7 +67,7 @@ enum {
 
 /* per-matrix caller-owned device buffers, sizes from ng_query_sizes */
 enum {
-    NG_BUF_P = 0,   /* float  [m][r]                      projector                                   */
+    NG_BUF_P = 0,   /* float  [m][r]                      projector (0 bytes with proj_dtype = NG_BF16) */
     NG_BUF_M,       /* float  [r][ldn]                    first moment                                */
     NG_BUF_V,       /* float  [r][ldn]                    second moment                               */
     NG_BUF_H,       /* float or bf16 (hist_dtype) [max(s,1)][r][ldn]  history ring (one scratch slot when s = 0) */
@@ -116,7 +116,15 @@ typedef struct ng_hparams {
                                      coordinates in the old basis).  1: it re-expresses every slot in
                                      the new basis, H_j <- (P_new^T P_old) H_j, recomputes the Gram
                                      matrix and keeps the ring position                              */
-    int32_t reserved;             /* must be 0                                                       */
+    int32_t proj_dtype;           /* NG_F32 (default): the projector is kept as float [m][r] in NG_BUF_P (plus,
+                                     for NG_BF16 gradients, the two bf16 copies in NG_BUF_AUX that the GEMMs
+                                     multiply with).  NG_BF16 (NG_BF16 gradients only, not with carry_history):
+                                     the low-memory projector -- only the two bf16 copies are kept, NG_BUF_P
+                                     has 0 bytes (its pointer may be NULL); a refresh builds the float
+                                     projector in the workspace, rounds it into the copies and drops it.
+                                     There is then no float P for the caller to read or to commit: a
+                                     checkpoint holds NG_BUF_AUX, and ng_commit_projector only marks
+                                     restored copies valid                                              */
     uint64_t seed;                /* seed of the refresh's random sketch                            */
 } ng_hparams;
 
@@ -139,7 +147,7 @@ typedef struct ng_matrix_layout {
 
 /* Fill hp with the defaults: s=4, lambda=1e-3, betas (0.9, 0.999), eps 1e-8,
  * scale 1, weight_decay 0, NG_F32, NG_ADAM_STANDARD, q=2, p=8, 30 sweeps,
- * hist_dtype NG_F32, fisher_norm NG_NORM_S, carry_history 0, seed 0. */
+ * hist_dtype NG_F32, fisher_norm NG_NORM_S, carry_history 0, proj_dtype NG_F32, seed 0. */
 int ng_default_hparams(ng_hparams* hp);
 
 /* Bytes the caller must allocate.  bytes[i*NG_NBUF + b] = size of buffer b of
@@ -178,7 +186,9 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
 /* The caller has written P (float [m][r], orthonormal columns) into every
  * NG_BUF_P itself (resume from a checkpoint, an external SVD).  Builds the
  * internal copies, marks the projector valid.  clear_history != 0 also clears H,
- * K and sets head = count = 0 and n_refresh += 1 (as a refresh does). */
+ * K and sets head = count = 0 and n_refresh += 1 (as a refresh does).
+ * With proj_dtype = NG_BF16 there is no NG_BUF_P: the caller has restored
+ * NG_BUF_AUX (the two bf16 copies) and this call only marks them valid. */
 int ng_commit_projector(ng_state* st, int clear_history, ng_stream stream);
 
 /* One optimizer step on every matrix (paper Sec. 2.4 with Sec. 2.2):

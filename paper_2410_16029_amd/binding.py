@@ -45,7 +45,7 @@ class ng_hparams(C.Structure):
                 ("grad_dtype", C.c_int32), ("adam_mode", C.c_int32),
                 ("refresh_power_iters", C.c_int32), ("refresh_oversample", C.c_int32),
                 ("refresh_sweeps", C.c_int32), ("hist_dtype", C.c_int32), ("fisher_norm", C.c_int32),
-                ("carry_history", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
+                ("carry_history", C.c_int32), ("proj_dtype", C.c_int32), ("seed", C.c_uint64)]
 
 
 class ng_matrix_buffers(C.Structure):
@@ -226,7 +226,7 @@ class LayerSet:
     def __init__(self, shapes: Sequence, r, *, s=4, lam=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                  weight_decay=0.0, dtype="f32", adam_mode="standard", power_iters=None, oversample=None,
                  sweeps=None, seed=0, device="cuda:0", ld_w=None, ld_g=None, no_clear=False, hist_dtype=None,
-                 sides=None, fisher_norm="s", carry_history=False, host_only=False):
+                 sides=None, fisher_norm="s", carry_history=False, host_only=False, proj_dtype=None):
         self.device = torch.device(device)
         self.shapes = [tuple(x) for x in shapes]
         self.r = r
@@ -247,6 +247,9 @@ class LayerSet:
         self.hist_dtype = hist_dtype if hist_dtype is not None else "f32"
         hp.fisher_norm = {"s": NG_NORM_S, "count": NG_NORM_COUNT}[fisher_norm]
         hp.carry_history = 1 if carry_history else 0
+        if proj_dtype is not None:
+            hp.proj_dtype = {"f32": NG_F32, "bf16": NG_BF16}[proj_dtype]
+        self.proj_dtype = proj_dtype if proj_dtype is not None else "f32"
         self.hp = hp
         self.dtype = dtype
         self.descs = make_descs(self.shapes, r, ld_w, ld_g, sides)
@@ -314,6 +317,10 @@ class LayerSet:
         return (n, m) if self.descs[i].side == NG_SIDE_RIGHT else (m, n)
 
     def P(self, i):
+        """The projector as a float32 [m][r] tensor: a view of NG_BUF_P, or, for the low-memory
+        projector (proj_dtype bf16: there is no float P), the decoded bf16 copy."""
+        if self.proj_dtype == "bf16":
+            return self.Pb(i)
         m, _ = self.eff_shape(i)
         r = self.descs[i].r
         return self._view(i, NG_BUF_P, torch.float32, m * r).view(m, r)

@@ -39,7 +39,11 @@ int validate(const ng_matrix_desc* d, int n_mats, const ng_hparams* hp) {
     if (hp->hist_dtype != NG_F32 && hp->hist_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->hist_dtype == NG_BF16 && hp->grad_dtype != NG_BF16) return NG_ERR_DTYPE;
     if (hp->fisher_norm != NG_NORM_S && hp->fisher_norm != NG_NORM_COUNT) return NG_ERR_HPARAM;
-    if ((hp->carry_history != 0 && hp->carry_history != 1) || hp->reserved != 0) return NG_ERR_HPARAM;
+    if (hp->carry_history != 0 && hp->carry_history != 1) return NG_ERR_HPARAM;
+    if (hp->proj_dtype != NG_F32 && hp->proj_dtype != NG_BF16) return NG_ERR_DTYPE;
+    // the low-memory projector lives in the bf16 copies only: they exist for bf16 gradients, and the
+    // history carry-over needs the outgoing float projector
+    if (hp->proj_dtype == NG_BF16 && (hp->grad_dtype != NG_BF16 || hp->carry_history != 0)) return NG_ERR_HPARAM;
     if (hp->adam_mode != NG_ADAM_STANDARD && hp->adam_mode != NG_ADAM_PRINTED) return NG_ERR_DTYPE;
     if (hp->s < 0 || hp->s > kMaxS) return NG_ERR_SHAPE;
     if (!(hp->lambda > 0.f) || !isfinite(hp->lambda)) return NG_ERR_HPARAM;
@@ -96,7 +100,7 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, int skinny_rk, Siz
     z->roct = ceil_div(d.r, 8);
     z->lp = (int)align_up((size_t)l, (size_t)2 * kJacobiBlock);
     const size_t rn = (size_t)d.r * z->ldn;
-    z->bytes[NG_BUF_P] = align_up((size_t)d.m * d.r * 4, 256);
+    z->bytes[NG_BUF_P] = hp.proj_dtype == NG_BF16 ? 0 : align_up((size_t)d.m * d.r * 4, 256);
     z->bytes[NG_BUF_M] = align_up(rn * 4, 256);
     z->bytes[NG_BUF_V] = align_up(rn * 4, 256);
     z->bytes[NG_BUF_H] = align_up(rn * (hist_is_bf16(hp) ? 2 : 4) * (size_t)(s > 0 ? s : 1), 256);
@@ -388,9 +392,11 @@ int orthonormalise(ng_state* st, bool is_a, bool twice, hipStream_t stream, cons
     return NG_OK;
 }
 
-int finish_projector(ng_state* st, bool clear, hipStream_t stream) {
-    if (!st->tables_valid && (clear || st->hp.grad_dtype == NG_BF16)) return NG_ERR_HIP;
-    if (st->hp.grad_dtype == NG_BF16)
+// copies: build the bf16 copies from the float projector (a commit of a low-memory layer set has none)
+int finish_projector(ng_state* st, bool clear, bool copies, hipStream_t stream) {
+    copies = copies && st->hp.grad_dtype == NG_BF16;
+    if (!st->tables_valid && (clear || copies)) return NG_ERR_HIP;
+    if (copies)
         NG_HIP(launch_make_bf16_copies(st->d_mats, st->n_mats, st->max_m, st->max_r, stream));
     if (clear) {
         int rc = clear_history(st, stream);
@@ -519,7 +525,7 @@ int ng_default_hparams(ng_hparams* hp) {
     hp->hist_dtype = NG_F32;
     hp->fisher_norm = NG_NORM_S;
     hp->carry_history = 0;
-    hp->reserved = 0;
+    hp->proj_dtype = NG_F32;
     hp->adam_mode = NG_ADAM_STANDARD;
     hp->refresh_power_iters = 2;
     hp->refresh_oversample = 8;
@@ -633,6 +639,9 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.skinny_parts_off = z.ws_skinny ? (long long)pl.step_skinny_off[i] : -1;
             md.Ya = (float*)(ws + off); off += z.ws_y;
             md.Yb = (float*)(ws + off); off += z.ws_y;
+            // low-memory projector: the float P of a refresh is transient and lives in the sketch buffer
+            // Yb ([max(m,n)][l] floats, l >= r), which is free from the Rayleigh-Ritz step on
+            if (hp->proj_dtype == NG_BF16) md.P = md.Yb;
             md.Yc = (float*)(ws + off); off += z.ws_y;
             md.Bm = (float*)(ws + off); off += z.ws_bm;
             md.T = (double*)(ws + off); off += z.ws_t;
@@ -723,7 +732,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
 int ng_commit_projector(ng_state* st, int clear, ng_stream stream_) {
     if (!st) return NG_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)stream_;
-    int rc = finish_projector(st, clear != 0, stream);
+    int rc = finish_projector(st, clear != 0, st->hp.proj_dtype != NG_BF16, stream);
     if (rc != NG_OK) return rc;
     st->projector_valid = true;
     if (clear) {
@@ -795,7 +804,7 @@ int ng_refresh_projector(ng_state* st, const void* const* grads, ng_stream strea
             NG_HIP(launch_solve(st->d_mats, st->d_dyn, 0, st->n_mats, sc, row, st->d_status, stream));
         }
     }
-    if ((rc = finish_projector(st, !carry, stream)) != NG_OK) return rc;
+    if ((rc = finish_projector(st, !carry, true, stream)) != NG_OK) return rc;
     st->projector_valid = true;
     for (int i = 0; i < st->n_mats; ++i) {
         if (!carry) {

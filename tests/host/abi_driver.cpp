@@ -130,7 +130,7 @@ int main() {
         h.lambda = 0.f;
         CHECK(make(s, h, NG_INIT_HOST_ONLY) == NG_ERR_HPARAM);
         h = hp;
-        h.reserved = 1;
+        h.proj_dtype = NG_BF16;   // the bf16-only projector needs bf16 gradients
         CHECK(make(s, h, NG_INIT_HOST_ONLY) == NG_ERR_HPARAM);
         CHECK(make(s, hp, NG_INIT_HOST_ONLY) == NG_OK);
         ng_state* st2 = nullptr;

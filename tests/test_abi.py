@@ -31,7 +31,7 @@ def test_binding_structs_match_the_compiled_header():
     # the defaults land in the fields the binding names (a shifted layout would scramble them)
     hp = B.ng_default_hparams()
     assert (hp.refresh_power_iters, hp.refresh_oversample, hp.refresh_sweeps) == (2, 8, 30)
-    assert (hp.hist_dtype, hp.fisher_norm, hp.carry_history, hp.reserved, hp.seed) == (B.NG_F32, B.NG_NORM_S, 0, 0, 0)
+    assert (hp.hist_dtype, hp.fisher_norm, hp.carry_history, hp.proj_dtype, hp.seed) == (B.NG_F32, B.NG_NORM_S, 0, B.NG_F32, 0)
 
 
 def test_query_sizes_c1_and_bf16_layout():
@@ -63,6 +63,15 @@ def test_query_sizes_c1_and_bf16_layout():
     assert sizes16[0][B.NG_BUF_M] == 512 * ldn * 4
     hp.hist_dtype = B.NG_F32
     assert sizes[0][B.NG_BUF_AUX] >= 2 * 2048 * 512 * 2
+    hp.proj_dtype = B.NG_BF16                               # opt-in: the projector only as its two bf16 copies
+    lowmem, _ = B.ng_query_sizes(descs, hp)
+    assert lowmem[0][B.NG_BUF_P] == 0 and lowmem[0][B.NG_BUF_AUX] == sizes[0][B.NG_BUF_AUX]
+    hp.carry_history = 1                                    # ... which the history carry-over cannot work from
+    with pytest.raises(B.NgError) as e:
+        B.ng_query_sizes(descs, hp)
+    assert e.value.code == B.NG_ERR_HPARAM
+    hp.carry_history = 0
+    hp.proj_dtype = B.NG_F32
     # right side: the projector is n x r and the r-space state is r x ldm
     hp.hist_dtype = B.NG_F32
     descs = B.make_descs([(5461, 2048)], 512, sides="auto")
@@ -89,6 +98,8 @@ def test_query_sizes_c1_and_bf16_layout():
     (lambda d, hp: setattr(hp, "hist_dtype", 5), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "hist_dtype", B.NG_BF16), B.NG_ERR_DTYPE),   # bf16 history needs bf16 gradients
     (lambda d, hp: setattr(hp, "fisher_norm", 2), B.NG_ERR_HPARAM),
+    (lambda d, hp: setattr(hp, "proj_dtype", 3), B.NG_ERR_DTYPE),
+    (lambda d, hp: setattr(hp, "proj_dtype", B.NG_BF16), B.NG_ERR_HPARAM),   # bf16-only projector needs bf16 gradients
     (lambda d, hp: setattr(hp, "adam_mode", 2), B.NG_ERR_DTYPE),
     (lambda d, hp: setattr(hp, "refresh_sweeps", 0), B.NG_ERR_HPARAM),
     (lambda d, hp: setattr(d[0], "r", 0), B.NG_ERR_SHAPE),

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pad_g=0, gscale=1.0,
-         energy_tol=2e-3, **kw):
+         energy_tol=2e-3, orth_tol=5e-6, **kw):
     """Free-running lockstep; with pad_w / pad_g the weights / gradients are column slices of
     wider tensors (leading dimension larger than n) whose remaining columns must stay untouched."""
     tol = TOL_F32 if dtype == "f32" else TOL_BF16
@@ -33,7 +33,7 @@ def _run(shapes, r, s, dtype, steps, seed, k=8, check=None, lr=1e-3, pad_w=0, pa
     if pad_g:
         ld_g = [n + pad_g for (m, n) in shapes]
     ls = B.LayerSet(shapes, r, s=s, dtype=dtype, device=DEV, ld_w=ld_w, ld_g=ld_g, **kw)
-    lk = Lockstep(ls, check=check, tol=tol, k_signal=k, energy_tol=energy_tol)
+    lk = Lockstep(ls, check=check, tol=tol, k_signal=k, energy_tol=energy_tol, orth_tol=orth_tol)
     lk.set_weights(W)
     errs = []
     for step in range(steps):
@@ -125,6 +125,52 @@ def test_bf16_history_slots_1b_shapes_and_no_fisher():
     # s = 0: the single scratch slot is bf16 too
     ls, errs = _run([(200, 333), (130, 64)], 24, 0, "bf16", 3, seed=29, k=24, hist_dtype="bf16")
     _assert_all(errs, TOL_BF16, "bf16 history, s=0")
+
+
+def test_low_memory_projector_bf16_copies_only():
+    """proj_dtype = bf16: no float projector is kept (NG_BUF_P has 0 bytes); a refresh builds it in the
+    workspace, rounds it into the two bf16 copies the GEMMs multiply with and drops it.  The oracle steps
+    with that bf16 projector, which is orthonormal to the rounding of bf16 only (orth_tol).  Ragged
+    shapes, both sides, a second refresh in the middle of the run, then one block of the 1.1B shapes."""
+    shapes = [(384, 520), (200, 333), (520, 384), (333, 200)]
+    sides = [B.NG_SIDE_LEFT, B.NG_SIDE_LEFT, B.NG_SIDE_RIGHT, B.NG_SIDE_RIGHT]
+    stream = workloads.TorchGradientStream(shapes, 16, 0.01, 97, "bf16", DEV)
+    W = workloads.torch_weights(shapes, 97, "bf16", DEV)
+    ls = B.LayerSet(shapes, 64, s=4, dtype="bf16", device=DEV, sides=sides, proj_dtype="bf16")
+    assert all(ls.sizes[i][B.NG_BUF_P] == 0 for i in range(len(shapes)))
+    lk = Lockstep(ls, tol=TOL_BF16, k_signal=16, orth_tol=2e-3)
+    lk.set_weights(W)
+    errs = []
+    for step in range(8):
+        G = stream.next_set()
+        if step in (0, 5):
+            lk.refresh(G)
+            assert ls.status() == B.NG_OK
+        errs.append(lk.step(G, W, 1e-3))
+    assert ls.status() == B.NG_OK
+    _assert_all(errs, TOL_BF16, "low-memory projector")
+    assert ls.counters(0) == (8, 3, 3, 2)
+    # a checkpoint is the buffers as they are (the copies live in NG_BUF_AUX): restore into a fresh layer
+    # set, mark the copies valid, and the next step gives the same bits
+    G = stream.next_set()
+    ls2 = B.LayerSet(shapes, 64, s=4, dtype="bf16", device=DEV, sides=sides, proj_dtype="bf16")
+    torch.cuda.synchronize()
+    for row, row2 in zip(ls.buffers, ls2.buffers):
+        for b, b2 in zip(row, row2):
+            b2.copy_(b)
+    for i in range(len(shapes)):
+        B.ng_set_counters(ls2.st, i, *ls.counters(i))
+    ls2.commit_projector(clear_history=False)
+    W2 = [w.clone() for w in W]
+    ls.step(G, W, 1e-3)
+    ls2.step(G, W2, 1e-3)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(W, W2))
+    # 1.1B shapes
+    cfg = workloads.CONFIGS["c5"]
+    ls, errs = _run(cfg.matrices()[:7], cfg.r, cfg.s, "bf16", 3, seed=cfg.seed, k=cfg.k, check=[0, 4, 6],
+                    energy_tol=1e-3, orth_tol=2e-3, proj_dtype="bf16")
+    _assert_all(errs, TOL_BF16, "low-memory projector, c5 block")
 
 
 @pytest.mark.parametrize("name,dtype", [("ft4", "f32"), ("ft4", "bf16"), ("ft8", "f32"), ("ft8", "bf16")])

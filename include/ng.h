@@ -214,8 +214,10 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
  * reads; nothing in the array has to start at zero).  A layer set whose step scratch exceeds the
  * array returns NG_ERR_WORKSPACE (the per-matrix share is 2 KiB * s for the reduction plus, for
  * fp32 sets of rank <= 16, ceil(m/128) * rank class * ldn * 4 bytes); nothing is launched then.
- * Calls no hipMalloc / hipFree.  The handle still comes from ng_init_state (its workspace keeps
- * the static tables and the refresh's scratch). */
+ * Calls no hipMalloc / hipFree.  The first call on a GPU looks the array's address up
+ * (hipGetSymbolAddress, once per device and process): make that call outside a graph capture.
+ * The handle still comes from ng_init_state (its workspace keeps the static tables and the
+ * refresh's scratch). */
 #define NG_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
 int ng_step_static(ng_state* st, const void* const* grads, void* const* weights, float lr,
                    ng_stream stream);

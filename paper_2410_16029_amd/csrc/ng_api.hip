@@ -958,7 +958,8 @@ const char* ng_strerror(int code) {
         case NG_ERR_NO_PROJECTOR: return "no projector: call ng_refresh_projector or ng_commit_projector first";
         case NG_ERR_HIP: return "HIP runtime error";
         case NG_ERR_NUMERIC: return "numeric failure on device (non-positive pivot or non-finite value)";
-        case NG_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case NG_ERR_WORKSPACE:
+            return "workspace too small or misaligned (ng_step_static: the step's scratch exceeds the library's array)";
         case NG_ERR_NOT_CONVERGED: return "the refresh's eigen-solve used all its sweeps without converging";
         default: return "unknown error code";
     }

@@ -127,6 +127,37 @@ def test_bf16_history_slots_1b_shapes_and_no_fisher():
     _assert_all(errs, TOL_BF16, "bf16 history, s=0")
 
 
+def test_f32_mid_size_layer_set_many_tiles():
+    # fp32 gradients at sizes where the fp32 MFMA GEMMs run many tiles per matrix and the Gram-row
+    # reduction many workgroups (the small fp32 configuration is a single 256 x 512 matrix)
+    shapes = [(1024, 1536), (1536, 1024), (777, 1290)]
+    ls, errs = _run(shapes, 128, 8, "f32", 10, seed=111, k=32)
+    _assert_all(errs, TOL_F32, "f32 mid size")
+    assert ls.counters(2) == (10, 2, 8, 1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_long_free_run_with_refreshes(dtype):
+    # 40 free-running steps, the projector refreshed every 16: errors must not accumulate past the tolerance
+    shapes = [(384, 520), (333, 200)]
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    stream = workloads.TorchGradientStream(shapes, 16, 0.01, 113, dtype, DEV)
+    W = workloads.torch_weights(shapes, 113, dtype, DEV)
+    ls = B.LayerSet(shapes, 32, s=8, dtype=dtype, device=DEV)
+    lk = Lockstep(ls, tol=tol, k_signal=16)
+    lk.set_weights(W)
+    errs = []
+    for step in range(40):
+        G = stream.next_set()
+        if step % 16 == 0:
+            lk.refresh(G)
+            assert ls.status() == B.NG_OK
+        errs.append(lk.step(G, W, 1e-3))
+    assert ls.status() == B.NG_OK
+    _assert_all(errs, tol, "40 steps " + dtype)
+    assert ls.counters(0) == (40, 0, 8, 3)
+
+
 def test_low_memory_projector_bf16_copies_only():
     """proj_dtype = bf16: no float projector is kept (NG_BUF_P has 0 bytes); a refresh builds it in the
     workspace, rounds it into the two bf16 copies the GEMMs multiply with and drops it.  The oracle steps

@@ -77,6 +77,15 @@ def test_static_scratch_step_matches_workspace_step_on_two_calls_in_a_row():
     mid.step()
     mid.step()
     mid.assert_equal("fp32, s = 0")
+    # right-side matrices, bf16 history slots, the low-memory projector, phase events recorded
+    opt = _twin([(333, 200), (200, 333)], 24, 3, "bf16", seed=109, k=24, sides="auto", hist_dtype="bf16",
+                proj_dtype="bf16")
+    B.ng_set_profiling(opt.a.st, True)
+    for _ in range(4):
+        opt.step()
+    opt.assert_equal("bf16 options")
+    ms, steps = B.ng_get_phase_ms(opt.a.st)
+    assert steps == 4 and all(x >= 0.0 for x in ms)
 
 
 def test_static_scratch_rejects_layer_sets_beyond_its_size():

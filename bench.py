@@ -219,7 +219,8 @@ def main() -> int:
 
     def microbench():
         """Measured ceilings on this GPU: plain streaming copy and read of 1 GiB (beyond the 256 MB
-        memory-side cache) and a bare bf16 MFMA loop."""
+        memory-side cache) and a bare bf16 MFMA loop, on constant operands (the nominal rate) and on
+        pseudo-random operands that change with every MFMA (the clock the chip holds on real data)."""
         n = 1 << 30
         a = torch.ones(n // 4, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -231,6 +232,8 @@ def main() -> int:
         out["stream_read_GB/s"] = round(work / (ms * 1e-3) / 1e9, 1)
         ms, work = B.ng_microbench(B.NG_MB_MFMA_BF16, 0, b.data_ptr(), 8192, 20, cur)
         out["mfma_bf16_TFLOP/s"] = round(work / (ms * 1e-3) / 1e12, 1)
+        ms, work = B.ng_microbench(B.NG_MB_MFMA_BF16_RANDOM, 0, b.data_ptr(), 8192, 20, cur)
+        out["mfma_bf16_random_operands_TFLOP/s"] = round(work / (ms * 1e-3) / 1e12, 1)
         del a, b
         return out
 

@@ -253,11 +253,14 @@ int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset);
  *                 *work = bytes;
  * NG_MB_MFMA_BF16 a bare loop of v_mfma_f32_32x32x16_bf16 on register operands, two wavefronts per
  *                 SIMD on all 256 units; a ignored, b as for NG_MB_READ, `bytes` = loop trips per
- *                 wavefront (8 MFMAs each); *work = floating-point operations.
+ *                 wavefront (8 MFMAs each); *work = floating-point operations.  The operands are small
+ *                 integers that never change: the nominal rate at the full clock;
+ * NG_MB_MFMA_BF16_RANDOM the same loop on pseudo-random operands that change from one MFMA to the next:
+ *                 the switching activity of real data, under which the chip lowers its clock.
  * One untimed launch, then `reps` launches timed with HIP events on `stream` (synchronises).
  * *ms = mean milliseconds per launch, *work = bytes or flops per launch.  No handle needed;
  * allocates nothing. */
-enum { NG_MB_COPY = 0, NG_MB_READ = 1, NG_MB_MFMA_BF16 = 2 };
+enum { NG_MB_COPY = 0, NG_MB_READ = 1, NG_MB_MFMA_BF16 = 2, NG_MB_MFMA_BF16_RANDOM = 3 };
 int ng_microbench(int which, const void* a, void* b, size_t bytes, int reps, ng_stream stream,
                   double* ms, double* work);
 

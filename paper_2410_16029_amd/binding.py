@@ -202,7 +202,7 @@ def ng_get_phase_ms(st, reset: bool = True):
     return [ms[i] for i in range(NG_NPHASE)], steps.value
 
 
-NG_MB_COPY, NG_MB_READ, NG_MB_MFMA_BF16 = 0, 1, 2
+NG_MB_COPY, NG_MB_READ, NG_MB_MFMA_BF16, NG_MB_MFMA_BF16_RANDOM = 0, 1, 2, 3
 
 
 def ng_microbench(which: int, a_ptr: int, b_ptr: int, nbytes: int, reps: int, stream: int):

@@ -910,10 +910,11 @@ int ng_get_phase_ms(ng_state* st, double* ms, int64_t* steps, int reset) {
 int ng_microbench(int which, const void* a, void* b, size_t bytes, int reps, ng_stream stream_, double* ms,
                   double* work) {
     if (!b || !ms || !work || reps < 1 || reps > 10000) return NG_ERR_INVALID_ARG;
-    if (which != NG_MB_COPY && which != NG_MB_READ && which != NG_MB_MFMA_BF16) return NG_ERR_INVALID_ARG;
-    if (which != NG_MB_MFMA_BF16 && (!a || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)a & 15))) return NG_ERR_INVALID_ARG;
+    if (which < NG_MB_COPY || which > NG_MB_MFMA_BF16_RANDOM) return NG_ERR_INVALID_ARG;
+    const bool mfma = which == NG_MB_MFMA_BF16 || which == NG_MB_MFMA_BF16_RANDOM;
+    if (!mfma && (!a || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)a & 15))) return NG_ERR_INVALID_ARG;
     if (which == NG_MB_COPY && ((uintptr_t)b & 15)) return NG_ERR_INVALID_ARG;
-    if (which == NG_MB_MFMA_BF16 && (bytes == 0 || bytes > (1u << 24))) return NG_ERR_INVALID_ARG;
+    if (mfma && (bytes == 0 || bytes > (1u << 24))) return NG_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)stream_;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     NG_HIP(hipEventCreate(&e0));
@@ -933,7 +934,7 @@ int ng_microbench(int which, const void* a, void* b, size_t bytes, int reps, ng_
             e = launch_mb_read(a, bytes, b, stream);
             w = (double)bytes;
         } else {
-            e = launch_mb_mfma((int)bytes, 2, b, &w, stream);
+            e = launch_mb_mfma((int)bytes, 2, which == NG_MB_MFMA_BF16_RANDOM, b, &w, stream);
         }
     }
     float t = 0.f;

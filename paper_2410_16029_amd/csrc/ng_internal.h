@@ -218,6 +218,7 @@ hipError_t launch_sign_fix(const MatDev* mats, int n_mats, int max_r, hipStream_
 // micro-benchmarks (k_microbench.hip)
 hipError_t launch_mb_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 hipError_t launch_mb_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
-hipError_t launch_mb_mfma(int iters, int waves_per_simd, void* sink, double* flops, hipStream_t stream);
+hipError_t launch_mb_mfma(int iters, int waves_per_simd, bool random_operands, void* sink, double* flops,
+                          hipStream_t stream);
 
 }  // namespace ng

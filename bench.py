@@ -202,7 +202,7 @@ def main() -> int:
         summary was taken on a library built from the very sources the loaded one was built from."""
         path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, args.config))
         if args.hist_dtype != "f32" or args.sides != "left" or args.dtype is not None:
-            return None   # the committed counter summaries cover the configuration as BASELINE.json states it
+            return None   # the committed counter summaries cover the default configuration (f32 history, left side, bf16)
         have = ngbuild.built_hash()
         if have is None or have != ngbuild.source_hash():
             return None

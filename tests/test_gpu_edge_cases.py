@@ -158,6 +158,48 @@ def test_long_free_run_with_refreshes(dtype):
     assert ls.counters(0) == (40, 0, 8, 3)
 
 
+@pytest.mark.parametrize("dtype,shape,r", [("bf16", (16384, 32000), 1024), ("f32", (8192, 40000), 256),
+                                           ("bf16", (32000, 16384), 512)])
+def test_near_the_largest_matrix_the_library_accepts(dtype, shape, r):
+    """One matrix just below the size limit (rows x leading dimension x 4 bytes < 2 GiB: the kernels address
+    a matrix with 32-bit offsets), two steps, every tensor against the oracle.  The refresh invariants
+    are not evaluated here (a full SVD of such a matrix takes minutes on the host): orthonormality and the
+    captured energy of the signal part are checked directly."""
+    m, n = shape
+    assert 0.6 * 2 ** 31 < m * n * 4 < 2 ** 31
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    stream = workloads.TorchGradientStream([shape], 64, 0.01, 131, dtype, DEV)
+    W = workloads.torch_weights([shape], 131, dtype, DEV)
+    ls = B.LayerSet([shape], r, s=2, dtype=dtype, device=DEV)
+    lk = Lockstep(ls, tol=tol, check_refresh=False)
+    lk.set_weights(W)
+    errs = []
+    for step in range(2):
+        G = stream.next_set()
+        if step == 0:
+            lk.refresh(G)
+            assert ls.status() == B.NG_OK
+            P = ls.P(0).double()
+            eye = torch.eye(r, dtype=torch.float64, device=DEV)
+            orth = float((P.T @ P - eye).abs().max())
+            print("orthonormality", orth)
+            # the last orthonormalisation accumulates its Gram matrix over the rows in float: the bound
+            # grows with the square root of the row count (5e-6 holds up to about 8000 rows)
+            assert orth <= max(5e-6, 1e-7 * ls.eff_shape(0)[0] ** 0.5)
+            # G = A B^T + 0.01 E with A, B ~ N(0, 1/k), k = 64: the rank-64 signal carries m n / k of the
+            # energy against 1e-4 m n of the noise, i.e. a share of 1 / (1 + 1e-4 k) = 0.99364 in
+            # expectation; a projector that holds the signal subspace keeps at least that share (plus
+            # r / min(m, n) of the noise)
+            Gd = G[0].double()
+            kept = float(((P.T @ Gd) ** 2).sum() / (Gd ** 2).sum())
+            print("kept energy", kept)
+            assert kept >= (1.0 / (1.0 + 1e-4 * 64)) * (1.0 - 1e-3)
+            del P, Gd, eye
+        errs.append(lk.step(G, W, 1e-3))
+    assert ls.status() == B.NG_OK
+    _assert_all(errs, tol, "near-maximum %s %s" % (dtype, shape))
+
+
 def test_low_memory_projector_bf16_copies_only():
     """proj_dtype = bf16: no float projector is kept (NG_BUF_P has 0 bytes); a refresh builds it in the
     workspace, rounds it into the two bf16 copies the GEMMs multiply with and drops it.  The oracle steps

@@ -102,7 +102,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true")
     ap.add_argument("--no-microbench", action="store_true")
-    ap.add_argument("--refresh-in-loop", type=int, default=0, help="refresh every this many timed steps (0 = never)")
+    ap.add_argument("--refresh-in-loop", type=int, default=None,
+                    help="refresh every this many timed steps (0 = never); default: 200 for c4, whose "
+                         "definition counts one refresh per 200 timed steps (run it with --steps 400), else 0")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 10 plain device-to-device copies of MIB MiB "
                          "(calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -130,6 +132,8 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4, "copies": 10}))
         return 0
     cfg = workloads.CONFIGS[args.config]
+    if args.refresh_in_loop is None:
+        args.refresh_in_loop = 200 if args.config == "c4" else 0
     if args.dtype is not None:
         import dataclasses
         cfg = dataclasses.replace(cfg, dtype=args.dtype)

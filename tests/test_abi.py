@@ -217,3 +217,23 @@ def test_sketch_width_is_trimmed_to_a_multiple_of_32_when_that_keeps_r_columns()
         ls = B.LayerSet([shape], r, s=2, dtype="f32", device="cpu", host_only=True, oversample=p)
         assert B.ng_get_layout(ls.st, 0).l == want, (shape, r, p)
         ls.close()
+
+
+def test_microbench_rejects_bad_arguments_before_any_device_call():
+    ms, work = C.c_double(), C.c_double()
+    lib = B._lib
+    buf = (C.c_char * 64)()
+    a = C.addressof(buf)
+    a16 = (a + 15) & ~15
+
+    def call(which, pa, pb, nbytes, reps):
+        return lib.ng_microbench(which, C.c_void_p(pa), C.c_void_p(pb), nbytes, reps, None, C.byref(ms), C.byref(work))
+
+    assert call(7, a16, a16, 16, 1) == B.NG_ERR_INVALID_ARG            # unknown benchmark
+    assert call(B.NG_MB_COPY, a16, a16, 16, 0) == B.NG_ERR_INVALID_ARG  # no repetitions
+    assert call(B.NG_MB_COPY, a16, a16, 24, 1) == B.NG_ERR_INVALID_ARG  # not whole 16-byte vectors
+    assert call(B.NG_MB_COPY, a16 + 4, a16, 16, 1) == B.NG_ERR_INVALID_ARG   # misaligned source
+    assert call(B.NG_MB_COPY, a16, a16 + 4, 16, 1) == B.NG_ERR_INVALID_ARG   # misaligned destination
+    assert call(B.NG_MB_READ, 0, a16, 16, 1) == B.NG_ERR_INVALID_ARG    # no source
+    assert call(B.NG_MB_MFMA_BF16, 0, 0, 16, 1) == B.NG_ERR_INVALID_ARG  # no sink
+    assert call(B.NG_MB_MFMA_BF16, 0, a16, 1 << 25, 1) == B.NG_ERR_INVALID_ARG   # loop count beyond the cap

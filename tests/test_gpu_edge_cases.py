@@ -412,3 +412,28 @@ def test_rank_beyond_the_lds_resident_triangular_inverse():
     # fits in LDS, so the solved blocks are read back from global memory
     ls, errs = _run([(1300, 1400)], 1200, 2, "f32", 2, seed=92, k=1250)
     _assert_all(errs, TOL_F32, "rank 1200")
+
+
+def test_microbench_copy_is_exact_and_reports_its_work():
+    """The streaming copy behind the measured ceilings moves every byte (whole chunks, a ragged last chunk,
+    fewer vectors than one workgroup), the read leaves its sink alone, the MFMA loop reports its flops."""
+    cur = torch.cuda.current_stream().cuda_stream
+    for n16 in (1, 255, 4096, 3 * 4096 + 777, 256 * 16 * 4096 + 5):
+        src = torch.randint(-2**31, 2**31 - 1, (n16 * 4,), dtype=torch.int32, device=DEV)
+        dst = torch.zeros(n16 * 4 + 4, dtype=torch.int32, device=DEV)
+        ms, work = B.ng_microbench(B.NG_MB_COPY, src.data_ptr(), dst.data_ptr(), n16 * 16, 1, cur)
+        torch.cuda.synchronize()
+        assert work == 2 * n16 * 16 and ms > 0
+        assert torch.equal(dst[:-4], src), n16
+        assert int(dst[-4:].abs().sum()) == 0, "copy wrote past its size"
+        sink = torch.full((4,), 7, dtype=torch.int32, device=DEV)
+        ms, work = B.ng_microbench(B.NG_MB_READ, src.data_ptr(), sink.data_ptr(), n16 * 16, 2, cur)
+        torch.cuda.synchronize()
+        assert work == n16 * 16 and sink.tolist() == [7, 7, 7, 7]
+    sink = torch.zeros(4, dtype=torch.float32, device=DEV)
+    for which in (B.NG_MB_MFMA_BF16, B.NG_MB_MFMA_BF16_RANDOM):
+        ms, work = B.ng_microbench(which, 0, sink.data_ptr(), 64, 1, cur)
+        # 256 units x 4 SIMDs x 2 resident wavefronts, four workgroups deep; 64 trips of 8 MFMAs of 2*32*32*16 flop
+        assert work == 256 * 4 * 2 * 4 * 64 * 8 * 2 * 32 * 32 * 16 and ms > 0
+    torch.cuda.synchronize()
+    assert sink.tolist() == [0.0] * 4

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -145,16 +146,35 @@ struct Plan {
 };
 
 // Round-robin workgroup dispatch puts workgroup id w on XCD (w mod 8).  To let one XCD work
-// through a contiguous run of the logical tile order (tiles that share operand panels stay
-// in one L2), hardware id w takes logical index (w mod 8) * ceil(T/8) + w / 8.
-void xcd_order(const std::vector<TileRef>& logical, std::vector<TileRef>* out) {
+// through a contiguous run of the logical tile order (tiles that share operand panels stay in one
+// L2), the logical order is cut into 8 runs of about equal cost (cost[i] = contraction length of tile
+// i) and hardware id w takes entry w / 8 of run w mod 8.  Inside a run the tiles are taken longest
+// first (stable: tiles of one matrix stay together): an XCD's units pick tiles off its run as they
+// become free, and a run that ends with its longest tiles leaves most units idle while the last few
+// finish (the 5461-deep tiles of a 1.1B-shaped block are 2.7 times as long as the others).
+// Runs shorter than the longest are padded with entries whose workgroups exit at once.
+void xcd_order(const std::vector<TileRef>& logical, const std::vector<int>& cost, std::vector<TileRef>* out) {
     const size_t T = logical.size();
-    const size_t per = (T + 7) / 8;
-    out->assign(per * 8, TileRef{-1, 0, 0, 0});
-    for (size_t w = 0; w < per * 8; ++w) {
-        size_t idx = (w % 8) * per + w / 8;
-        if (idx < T) (*out)[w] = logical[idx];
+    out->clear();
+    if (T == 0) return;
+    double total = 0.0;
+    for (size_t i = 0; i < T; ++i) total += (double)cost[i];
+    std::vector<std::vector<size_t>> run(8);
+    double acc = 0.0;
+    for (size_t i = 0; i < T; ++i) {
+        // the run in which the tile's midpoint falls
+        size_t x = (size_t)((acc + 0.5 * (double)cost[i]) * 8.0 / total);
+        run[x < 8 ? x : 7].push_back(i);
+        acc += (double)cost[i];
     }
+    size_t per = 0;
+    for (auto& r : run) {
+        std::stable_sort(r.begin(), r.end(), [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+        per = r.size() > per ? r.size() : per;
+    }
+    out->assign(per * 8, TileRef{-1, 0, 0, 0});
+    for (size_t x = 0; x < 8; ++x)
+        for (size_t k = 0; k < run[x].size(); ++k) (*out)[k * 8 + x] = logical[run[x][k]];
 }
 
 void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* p) {
@@ -166,6 +186,7 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
     bf16_tile_shape(2, max_r, &sbm, &sbn);
     bf16_tile_shape(1, max_r, &ubm, &ubn);
     std::vector<TileRef> proj_direct, proj_staged, proj_right, upd;
+    std::vector<int> cost_direct, cost_staged, cost_right, cost_upd;   // contraction length per tile
     p->dots.clear();
     p->patches.clear();
     p->skinny.clear();
@@ -183,9 +204,13 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         } else if (hp.grad_dtype == NG_BF16) {
             const bool direct = d[i].side != NG_SIDE_RIGHT && projection_tile_direct(effective(d[i]).n);
             std::vector<TileRef>& run = direct ? proj_direct : d[i].side == NG_SIDE_RIGHT ? proj_right : proj_staged;
+            std::vector<int>& run_cost = direct ? cost_direct : d[i].side == NG_SIDE_RIGHT ? cost_right : cost_staged;
             const int bm = direct ? pbm : sbm, bn = direct ? pbn : sbn;
             for (int tj = 0; tj < ceil_div(z.ldn, bn); ++tj)
-                for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) run.push_back(TileRef{i, ti, tj, 0});
+                for (int ti = 0; ti < ceil_div(d[i].r, bm); ++ti) {
+                    run.push_back(TileRef{i, ti, tj, 0});
+                    run_cost.push_back(effective(d[i]).m);
+                }
             // update tiles cover the weight in the caller's orientation on either side.  Consecutive
             // tiles share one operand panel; the other operand is swept whole once per panel, so the
             // loop order keeps the smaller of the two whole operands (rows x r against r x columns) as
@@ -197,15 +222,16 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
                 for (int tj = 0; tj < ceil_div(d[i].n, ubn); ++tj)
                     for (int ti = 0; ti < ceil_div(d[i].m, ubm); ++ti) upd.push_back(TileRef{i, ti, tj, 0});
             }
+            cost_upd.resize(upd.size(), d[i].r);
         }
         for (int ti = 0; ti < ceil_div(d[i].r, 32); ++ti)
             for (int tj = 0; tj < ceil_div(z.ldn, kAdamPatchCols); ++tj) p->patches.push_back(TileRef{i, ti, tj, 0});
     }
     {
         std::vector<TileRef> a, b, c;
-        xcd_order(proj_direct, &a);
-        xcd_order(proj_staged, &b);
-        xcd_order(proj_right, &c);
+        xcd_order(proj_direct, cost_direct, &a);
+        xcd_order(proj_staged, cost_staged, &b);
+        xcd_order(proj_right, cost_right, &c);
         p->proj_direct = (int)a.size();
         p->proj_staged = (int)b.size();
         p->proj_right = (int)c.size();
@@ -213,7 +239,7 @@ void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* 
         p->proj.insert(p->proj.end(), b.begin(), b.end());
         p->proj.insert(p->proj.end(), c.begin(), c.end());
     }
-    xcd_order(upd, &p->upd);
+    xcd_order(upd, cost_upd, &p->upd);
     // Gram-row parts are appended in make_mats (they need dot_nparts)
     size_t off = 0;
     p->off_status = off; off += 256;

@@ -216,6 +216,9 @@ int ng_step(ng_state* st, const void* const* grads, void* const* weights, float 
  * fp32 sets of rank <= 16, ceil(m/128) * rank class * ldn * 4 bytes); nothing is launched then.
  * Calls no hipMalloc / hipFree.  The first call on a GPU looks the array's address up
  * (hipGetSymbolAddress, once per device and process): make that call outside a graph capture.
+ * A captured call holds this step's ring position, bias corrections, learning rate and the
+ * gradient / weight pointers as launch arguments: replaying the graph repeats that step (the host
+ * counters advance at capture, not at replay), so capture each step anew or use the graph for one.
  * The handle still comes from ng_init_state (its workspace keeps the static tables and the
  * refresh's scratch). */
 #define NG_STATIC_SCRATCH_BYTES ((size_t)32 << 20)

@@ -71,6 +71,8 @@ enum {
     NG_BUF_M,       /* float  [r][ldn]                    first moment                                */
     NG_BUF_V,       /* float  [r][ldn]                    second moment                               */
     NG_BUF_H,       /* float or bf16 (hist_dtype) [max(s,1)][r][ldn]  history ring (one scratch slot when s = 0) */
+                    /* (M, V and the slots of H: r x ldn elements each, in column panels where
+                       ng_matrix_layout::panel_cols < ldn)                                            */
     NG_BUF_K,       /* double [s*s] Gram, double [s] w, then float [s] w  (see ng_matrix_layout)      */
     NG_BUF_N,       /* update direction: float [r][ldn] (NG_F32) or bf16 [ceil(r/8)][ldn][8] (NG_BF16) */
     NG_BUF_AUX,     /* NG_BF16 only: bf16 copies of P; 0 bytes for NG_F32 (pointer may be NULL)       */
@@ -136,6 +138,15 @@ typedef struct ng_matrix_layout {
     int32_t ldn;        /* padded row length (elements) of M, V, N and of every H slot; columns >= n are 0 */
     int32_t l;          /* sketch width of the refresh                                                   */
     int64_t slot_elems; /* r * ldn: elements per history slot                                            */
+    /* M, V and every H slot are stored as column panels of panel_cols columns: element (row, col) lies at
+     *   p * r * panel_cols + row * pitch + (col - p * panel_cols),  p = col / panel_cols,
+     *   pitch = min(panel_cols, ldn - p * panel_cols)
+     * i.e. panel p is a row-major r x pitch block and the panels follow each other; the array is still
+     * r * ldn elements.  panel_cols == ldn (one panel) is the plain row-major [r][ldn] array: always so for
+     * NG_F32 gradients, with carry_history, and where ldn < 2304; otherwise panel_cols = 2048 (the row
+     * pitch at which the streaming kernels run fastest).  N is not panelled. */
+    int32_t panel_cols;
+    int32_t reserved0;
     int64_t k_gram_off, k_w64_off, k_w32_off;  /* byte offsets inside the K buffer                       */
     /* NG_BF16 only (else 0): byte offsets inside the AUX buffer of the two bf16 copies of P that the
      * step's GEMMs multiply with, both split into blocks of 32 along the contraction index:

@@ -54,6 +54,7 @@ class ng_matrix_buffers(C.Structure):
 
 class ng_matrix_layout(C.Structure):
     _fields_ = [("ldn", C.c_int32), ("l", C.c_int32), ("slot_elems", C.c_int64),
+                ("panel_cols", C.c_int32), ("reserved0", C.c_int32),
                 ("k_gram_off", C.c_int64), ("k_w64_off", C.c_int64), ("k_w32_off", C.c_int64),
                 ("aux_pb_off", C.c_int64), ("aux_pbt_off", C.c_int64)]
 
@@ -302,7 +303,7 @@ class LayerSet:
     def counters(self, mat: int = 0):
         return ng_get_counters(self.st, mat)
 
-    # ---- typed views of the state buffers (no copies)
+    # ---- typed views of the state buffers (no copies, except M, V, H of panelled states)
     def _view(self, i, b, dtype, count, offset=0):
         t = self.buffers[i][b]
         esz = torch.empty((), dtype=dtype).element_size()
@@ -325,19 +326,33 @@ class LayerSet:
         r = self.descs[i].r
         return self._view(i, NG_BUF_P, torch.float32, m * r).view(m, r)
 
+    def _unpanel(self, i, flat):
+        """[..., r * ldn] elements in the library's column-panel order -> [..., r, ldn] row-major
+        (a view when the array has one panel, else a copy)."""
+        r, ldn, pw = self.descs[i].r, self.layouts[i].ldn, self.layouts[i].panel_cols
+        lead = flat.shape[:-1]
+        if pw >= ldn:
+            return flat.view(*lead, r, ldn)
+        parts, off = [], 0
+        for c0 in range(0, ldn, pw):
+            pitch = min(pw, ldn - c0)
+            parts.append(flat[..., off:off + r * pitch].reshape(*lead, r, pitch))
+            off += r * pitch
+        return torch.cat(parts, dim=-1)
+
     def M(self, i):
         r, ldn = self.descs[i].r, self.layouts[i].ldn
-        return self._view(i, NG_BUF_M, torch.float32, r * ldn).view(r, ldn)
+        return self._unpanel(i, self._view(i, NG_BUF_M, torch.float32, r * ldn))
 
     def V(self, i):
         r, ldn = self.descs[i].r, self.layouts[i].ldn
-        return self._view(i, NG_BUF_V, torch.float32, r * ldn).view(r, ldn)
+        return self._unpanel(i, self._view(i, NG_BUF_V, torch.float32, r * ldn))
 
     def H(self, i):
         r, ldn = self.descs[i].r, self.layouts[i].ldn
         s = max(self.hp.s, 1)
         ht = torch.bfloat16 if self.hist_dtype == "bf16" else torch.float32
-        return self._view(i, NG_BUF_H, ht, s * r * ldn).view(s, r, ldn)
+        return self._unpanel(i, self._view(i, NG_BUF_H, ht, s * r * ldn).view(s, r * ldn))
 
     def K(self, i):
         s = self.hp.s

@@ -408,10 +408,11 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     // Branch-free loads: a row beyond nrow re-reads the band's last valid row and its result is dropped.
     // Element offsets of this thread's row segments inside a slot / inside M, V (32-bit).
     unsigned eoff[RT];
+    const StatePanel sp = state_panel(r, ldn, md.pw, pr.tj * kAdamPatchCols);   // the same for the whole workgroup
 #pragma unroll
     for (int e = 0; e < RT; ++e) {
         const int row = row0 + e < r ? row0 + e : r - 1;
-        eoff[e] = (unsigned)row * (unsigned)ldn + (unsigned)col0;
+        eoff[e] = sp.at(row, col0);
     }
     constexpr unsigned HS = HB ? 2u : 4u;   // bytes per history element
 

@@ -377,6 +377,7 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], 
                                                  unsigned char* smem, int i0, int j0, int t, int wm, int wn, int li,
                                                  int h) {
     const int r = md.r, ldn = md.ldn, n = md.n;   // columns n..ldn-1 of the slot are zero
+    const StatePanel sp = state_panel(r, ldn, md.pw, j0);   // a tile lies in one column panel of the slot
     if (!HB) {
         NG_AS1 float* R = (NG_AS1 float*)md.H + (long long)dy.head * md.slot_elems;
 #pragma unroll
@@ -392,8 +393,8 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], 
                         // (two stores under lane masks: a select on the value would pull every
                         // accumulator into an ordinary register at once)
                         if (row < r) {
-                            if (col < n) __builtin_nontemporal_store(acc[mi][nj][4 * g + e], &R[(unsigned)row * (unsigned)ldn + (unsigned)col]);
-                            else if (col < ldn) __builtin_nontemporal_store(0.f, &R[(unsigned)row * (unsigned)ldn + (unsigned)col]);
+                            if (col < n) __builtin_nontemporal_store(acc[mi][nj][4 * g + e], &R[sp.at(row, col)]);
+                            else if (col < ldn) __builtin_nontemporal_store(0.f, &R[sp.at(row, col)]);
                         }
                     }
             }
@@ -438,7 +439,7 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], 
                     ov.y = pack_bf16x2(c0.z, c0.w);
                     ov.z = pack_bf16x2(c1.x, c1.y);
                     ov.w = pack_bf16x2(c1.z, c1.w);
-                    *(NG_AS1 u32x4_t*)(Rb + ((unsigned)row * (unsigned)ldn + (unsigned)col)) = ov;
+                    *(NG_AS1 u32x4_t*)(Rb + sp.at(row, col)) = ov;
                 }
             }
             __syncthreads();

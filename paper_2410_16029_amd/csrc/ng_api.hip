@@ -26,7 +26,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Sizes {   // per-matrix derived sizes
-    int ldn, l, ldk, ldr, roct, lp;
+    int ldn, pw, l, ldk, ldr, roct, lp;
     size_t bytes[NG_NBUF];
     size_t k_gram_off, k_w64_off, k_w32_off;
     size_t aux_pb_off, aux_pbt_off;
@@ -88,6 +88,11 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, int skinny_rk, Siz
     memset(z, 0, sizeof(*z));
     const int s = hp.s;
     z->ldn = (int)align_up((size_t)d.n, 32);
+    // Wide states of bf16 layer sets are stored as column panels (see state_panel).  Only the bf16
+    // projection and the transform address them in two dimensions; the fp32 GEMMs that the fp32
+    // path and the history carry-over run on the slots want plain row-major.
+    // (a last panel narrower than two patches would be all row ends: such rows stay whole)
+    z->pw = (hp.grad_dtype == NG_BF16 && !hp.carry_history && z->ldn >= kStatePanelCols + 256) ? kStatePanelCols : z->ldn;
     int l = d.r + hp.refresh_oversample;
     if (l > d.m) l = d.m;
     if (l > d.n) l = d.n;
@@ -646,6 +651,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.l = z.l; md.ldk = z.ldk; md.ldr = z.ldr; md.roct = z.roct;
             md.ld_w = descs[i].ld_w; md.ld_g = descs[i].ld_g;
             md.slot_elems = (long long)md.r * z.ldn;
+            md.pw = z.pw;
             md.P = (float*)bufs[i].buf[NG_BUF_P];
             md.M = (float*)bufs[i].buf[NG_BUF_M];
             md.V = (float*)bufs[i].buf[NG_BUF_V];
@@ -885,6 +891,8 @@ int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out) {
     out->ldn = z.ldn;
     out->l = z.l;
     out->slot_elems = (int64_t)st->descs[mat].r * z.ldn;
+    out->panel_cols = z.pw;
+    out->reserved0 = 0;
     out->k_gram_off = (int64_t)z.k_gram_off;
     out->k_w64_off = (int64_t)z.k_w64_off;
     out->k_w32_off = (int64_t)z.k_w32_off;

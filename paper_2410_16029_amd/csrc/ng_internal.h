@@ -18,6 +18,7 @@ constexpr int kDynChunk = 96;    // per-step table entries uploaded per launch (
 constexpr int kSkinnyMaxRank = 16;   // fp32 layer sets with ranks up to this take the vector-ALU projection / update
 constexpr int kSkinnyRows = 128;     // rows and columns of the gradient / weight one of their workgroups takes
 constexpr int kSkinnyCols = 256;
+constexpr int kStatePanelCols = 2048;   // columns per panel of a wide M, V or history slot (see state_panel)
 // bits of the device's sticky status word: 1 solve (pivot / non-finite), 2 transform+Adam (non-finite),
 // 4 Cholesky pivot of the refresh, 8 non-positive Ritz value among the leading r
 constexpr int kStatusNotConverged = 16;   // the Jacobi eigen-solve of a refresh ran out of sweeps
@@ -35,6 +36,7 @@ struct MatDev {
     int roct;         // ceil(r/8): octets of N in the bf16 layout
     long long ld_w, ld_g;
     long long slot_elems;   // r * ldn
+    int pw;           // columns per panel of M, V and every history slot (== ldn: one panel, plain row-major)
     float* P;
     float* M;
     float* V;
@@ -86,6 +88,28 @@ struct DynChunk {
 };
 
 constexpr size_t kStaticScratchBytes = NG_STATIC_SCRATCH_BYTES;   // the library's own step scratch (ng_step_static)
+
+// M, V and every history slot hold r x ldn elements as column panels of pw columns: panel p (columns
+// p pw .. min(ldn, (p + 1) pw) - 1) is a row-major r x pitch block, pitch = its column count, and the
+// panels lie one after the other (the array stays r * ldn elements long and, read flat, is a permutation
+// of the row-major one).  pw is a multiple of every tile and patch width, so a tile lies in one panel.
+// pw == ldn is the plain row-major array.  A 2048-column panel gives 4-byte elements a row pitch of
+// 8 KB, at which the streaming kernels run fastest (transform+Adam on 5472-column states: 5.8 TB/s
+// row-major against 6.6 TB/s for 2048-column states).
+struct StatePanel {
+    unsigned base;   // element offset of the panel inside the array
+    int pitch;       // its row pitch (= its columns)
+    int col0;        // its first column
+    __host__ __device__ unsigned at(int row, int col) const { return base + (unsigned)row * (unsigned)pitch + (unsigned)(col - col0); }
+};
+__host__ __device__ inline StatePanel state_panel(int r, int ldn, int pw, int col) {
+    StatePanel sp;
+    const int p = col / pw;
+    sp.col0 = p * pw;
+    sp.pitch = ldn - sp.col0 < pw ? ldn - sp.col0 : pw;
+    sp.base = (unsigned)p * (unsigned)r * (unsigned)pw;
+    return sp;
+}
 
 // address inside the step's scratch block, which starts with the per-step table
 template <typename T>

@@ -167,7 +167,42 @@ def test_host_bookkeeping_without_device():
     assert [ls.counters(i) for i in range(2)] == before
     assert ls.status() == B.NG_ERR_HIP
     lay = B.ng_get_layout(ls.st, 0)
-    assert lay.ldn == 96 and lay.slot_elems == 16 * 96
+    assert lay.ldn == 96 and lay.slot_elems == 16 * 96 and lay.panel_cols == 96
+    ls.close()
+
+
+def test_wide_bf16_states_are_column_panels_and_the_decoder_undoes_them():
+    """M, V and the history slots of a bf16 layer set are stored as 2048-column panels where the padded
+    row has 2304 elements or more; everything else stays plain row-major."""
+    def layout(shape, **kw):
+        ls = B.LayerSet([shape], 8, s=2, device="cpu", host_only=True, **kw)
+        lay = B.ng_get_layout(ls.st, 0)
+        out = (lay.ldn, lay.panel_cols, lay.slot_elems)
+        ls.close()
+        return out
+    assert layout((64, 5461), dtype="bf16") == (5472, 2048, 8 * 5472)
+    assert layout((64, 4096), dtype="bf16") == (4096, 2048, 8 * 4096)
+    assert layout((64, 2736), dtype="bf16") == (2752, 2048, 8 * 2752)
+    assert layout((64, 2304), dtype="bf16") == (2304, 2048, 8 * 2304)
+    assert layout((64, 2272), dtype="bf16") == (2272, 2272, 8 * 2272)          # a sliver of a second panel: one
+    assert layout((64, 5461), dtype="f32") == (5472, 5472, 8 * 5472)           # fp32 gradients: row-major
+    assert layout((64, 5461), dtype="bf16", carry_history=True) == (5472, 5472, 8 * 5472)
+    assert layout((5461, 64), dtype="bf16", sides="auto") == (5472, 2048, 8 * 5472)   # right side: r x ldm
+    # the binding's decoder: element (row, col) sits at p r pw + row pitch + (col - p pw)
+    ls = B.LayerSet([(64, 4200)], 8, s=2, dtype="bf16", device="cpu", host_only=True)
+    r, ldn, pw = 8, 4224, 2048
+    flat = torch.arange(r * ldn, dtype=torch.float32)
+    ls.buffers[0][B.NG_BUF_M].view(torch.float32)[:r * ldn] = flat
+    M = ls.M(0)
+    assert M.shape == (r, ldn)
+    for row, col in [(0, 0), (3, 2047), (0, 2048), (7, 4095), (0, 4096), (5, 4223)]:
+        pnl = col // pw
+        pitch = min(pw, ldn - pnl * pw)
+        assert M[row, col] == pnl * r * pw + row * pitch + (col - pnl * pw), (row, col)
+    hflat = torch.arange(2 * r * ldn, dtype=torch.float32)
+    ls.buffers[0][B.NG_BUF_H].view(torch.float32)[:2 * r * ldn] = hflat
+    H = ls.H(0)
+    assert H.shape == (2, r, ldn) and H[1, 2, 4100] == r * ldn + 2 * r * pw + 2 * 128 + 4
     ls.close()
 
 

@@ -414,6 +414,18 @@ def test_rank_beyond_the_lds_resident_triangular_inverse():
     _assert_all(errs, TOL_F32, "rank 1200")
 
 
+@pytest.mark.parametrize("hist", [None, "bf16"])
+def test_wide_states_in_column_panels(hist):
+    """Rows of 2304 padded elements or more: M, V and the history slots are stored as 2048-column panels
+    (two whole panels and a ragged third one, on both sides, two exact panels, the narrowest second panel,
+    beside one-panel matrices)."""
+    shapes = [(96, 4200), (4131, 72), (80, 4096), (64, 520), (72, 2300), (72, 2270)]
+    ls, errs = _run(shapes, 32, 3, "bf16", 6, seed=61, hist_dtype=hist, sides=[0, 1, 0, 0, 0, 0])
+    assert [B.ng_get_layout(ls.st, i).panel_cols for i in range(6)] == [2048, 2048, 2048, 544, 2048, 2272]
+    assert [B.ng_get_layout(ls.st, i).ldn for i in range(6)] == [4224, 4160, 4096, 544, 2304, 2272]
+    _assert_all(errs, TOL_BF16, "panels hist=%s" % hist)
+
+
 def test_microbench_copy_is_exact_and_reports_its_work():
     """The streaming copy behind the measured ceilings moves every byte (whole chunks, a ragged last chunk,
     fewer vectors than one workgroup), the read leaves its sink alone, the MFMA loop reports its flops."""

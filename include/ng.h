@@ -71,8 +71,8 @@ enum {
     NG_BUF_M,       /* float  [r][ldn]                    first moment                                */
     NG_BUF_V,       /* float  [r][ldn]                    second moment                               */
     NG_BUF_H,       /* float or bf16 (hist_dtype) [max(s,1)][r][ldn]  history ring (one scratch slot when s = 0) */
-                    /* (M, V and the slots of H: r x ldn elements each, in column panels where
-                       ng_matrix_layout::panel_cols < ldn)                                            */
+                    /* (M, V and the slots of H: stored in column panels where
+                       ng_matrix_layout::panel_cols < ldn, see there)                                 */
     NG_BUF_K,       /* double [s*s] Gram, double [s] w, then float [s] w  (see ng_matrix_layout)      */
     NG_BUF_N,       /* update direction: float [r][ldn] (NG_F32) or bf16 [ceil(r/8)][ldn][8] (NG_BF16) */
     NG_BUF_AUX,     /* NG_BF16 only: bf16 copies of P; 0 bytes for NG_F32 (pointer may be NULL)       */
@@ -137,14 +137,15 @@ typedef struct ng_matrix_buffers {
 typedef struct ng_matrix_layout {
     int32_t ldn;        /* padded row length (elements) of M, V, N and of every H slot; columns >= n are 0 */
     int32_t l;          /* sketch width of the refresh                                                   */
-    int64_t slot_elems; /* r * ldn: elements per history slot                                            */
+    int64_t slot_elems; /* elements from one history slot to the next (r * ldn unless panelled, see below)    */
     /* M, V and every H slot are stored as column panels of panel_cols columns: element (row, col) lies at
-     *   p * r * panel_cols + row * pitch + (col - p * panel_cols),  p = col / panel_cols,
-     *   pitch = min(panel_cols, ldn - p * panel_cols)
-     * i.e. panel p is a row-major r x pitch block and the panels follow each other; the array is still
-     * r * ldn elements.  panel_cols == ldn (one panel) is the plain row-major [r][ldn] array: always so for
-     * NG_F32 gradients, with carry_history, and where ldn < 2304; otherwise panel_cols = 2048 (the row
-     * pitch at which the streaming kernels run fastest).  N is not panelled. */
+     *   p * r * panel_cols + row * panel_cols + (col - p * panel_cols),  p = col / panel_cols
+     * i.e. panel p is a row-major r x panel_cols block and the panels follow each other.  panel_cols ==
+     * ldn (one panel) is the plain row-major [r][ldn] array: always so for NG_F32 gradients, with
+     * carry_history, and where ldn < 2304.  Otherwise panel_cols = 2048 (the row pitch at which the
+     * streaming kernels run fastest); the arrays then hold r * ceil(ldn / 2048) * 2048 elements (the sizes
+     * ng_query_sizes reports, and slot_elems above, count them) and the last panel's columns from ldn on
+     * are padding that stays 0.  N is not panelled. */
     int32_t panel_cols;
     int32_t reserved0;
     int64_t k_gram_off, k_w64_off, k_w32_off;  /* byte offsets inside the K buffer                       */

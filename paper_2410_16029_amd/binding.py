@@ -326,33 +326,34 @@ class LayerSet:
         r = self.descs[i].r
         return self._view(i, NG_BUF_P, torch.float32, m * r).view(m, r)
 
+    def _state_elems(self, i):
+        """Elements of M, V or one history slot as stored (the last panel of a panelled state is padded)."""
+        r, ldn, pw = self.descs[i].r, self.layouts[i].ldn, self.layouts[i].panel_cols
+        return r * (-(-ldn // pw) * pw)
+
     def _unpanel(self, i, flat):
-        """[..., r * ldn] elements in the library's column-panel order -> [..., r, ldn] row-major
+        """[..., stored elements] in the library's column-panel order -> [..., r, ldn] row-major
         (a view when the array has one panel, else a copy)."""
         r, ldn, pw = self.descs[i].r, self.layouts[i].ldn, self.layouts[i].panel_cols
         lead = flat.shape[:-1]
         if pw >= ldn:
             return flat.view(*lead, r, ldn)
-        parts, off = [], 0
-        for c0 in range(0, ldn, pw):
-            pitch = min(pw, ldn - c0)
-            parts.append(flat[..., off:off + r * pitch].reshape(*lead, r, pitch))
-            off += r * pitch
-        return torch.cat(parts, dim=-1)
+        npan = -(-ldn // pw)
+        x = flat.view(*lead, npan, r, pw)
+        x = x.movedim(-3, -2).reshape(*lead, r, npan * pw)
+        return x[..., :ldn]
 
     def M(self, i):
-        r, ldn = self.descs[i].r, self.layouts[i].ldn
-        return self._unpanel(i, self._view(i, NG_BUF_M, torch.float32, r * ldn))
+        return self._unpanel(i, self._view(i, NG_BUF_M, torch.float32, self._state_elems(i)))
 
     def V(self, i):
-        r, ldn = self.descs[i].r, self.layouts[i].ldn
-        return self._unpanel(i, self._view(i, NG_BUF_V, torch.float32, r * ldn))
+        return self._unpanel(i, self._view(i, NG_BUF_V, torch.float32, self._state_elems(i)))
 
     def H(self, i):
-        r, ldn = self.descs[i].r, self.layouts[i].ldn
         s = max(self.hp.s, 1)
         ht = torch.bfloat16 if self.hist_dtype == "bf16" else torch.float32
-        return self._unpanel(i, self._view(i, NG_BUF_H, ht, s * r * ldn).view(s, r * ldn))
+        n = self._state_elems(i)
+        return self._unpanel(i, self._view(i, NG_BUF_H, ht, s * n).view(s, n))
 
     def K(self, i):
         s = self.hp.s

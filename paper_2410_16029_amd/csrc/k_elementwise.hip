@@ -116,11 +116,12 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
     const TileRef c = chunks[blockIdx.x];
     const MatDev& md = mats[c.mat];
     const int head = row_override >= 0 ? row_override : dyn[c.mat].head;
-    const long long totalv = md.slot_elems >> (HB ? 3 : 2);   // 16-byte vectors per slot
+    const long long totalv = md.slot_elems >> (HB ? 3 : 2);   // 16-byte vectors from one slot to the next
+    const FlatState fs = flat_state(md.r, md.ldn, md.pw, HB ? 8 : 4);   // positions q -> vectors of a slot
     const long long span = (long long)md.dot_iters * 256;
     const long long q0 = (long long)c.ti * span;
     long long q1 = q0 + span;
-    if (q1 > totalv) q1 = totalv;
+    if (q1 > (long long)fs.count) q1 = fs.count;
     const NG_AS1 u32x4_t* __restrict__ H = (const NG_AS1 u32x4_t*)md.H;
     const NG_AS1 u32x4_t* __restrict__ R = H + (long long)head * totalv;
 
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const bool ok = q + 256 * u < q1;
-                qq[u] = ok ? q + 256 * u : q;          // a position past the end re-reads q against a zero R
+                qq[u] = fs.at((unsigned)(ok ? q + 256 * u : q));   // a position past the end re-reads q against a zero R
                 rv[u] = ok ? R[qq[u]] : zero4;
             }
 #pragma unroll
@@ -173,10 +174,11 @@ __global__ __launch_bounds__(256) void k_gram_row(const MatDev* __restrict__ mat
 #pragma unroll
         for (int j = 0; j < SMAX; ++j) slot_off[j] = (long long)(j < s ? j : s - 1) * totalv;
         for (long long q = q0 + threadIdx.x; q < q1; q += 256) {
-            const u32x4_t rv = R[q];
+            const long long a = fs.at((unsigned)q);
+            const u32x4_t rv = R[a];
             u32x4_t hv[SMAX];
 #pragma unroll
-            for (int j = 0; j < SMAX; ++j) hv[j] = __builtin_nontemporal_load(H + (slot_off[j] + q));
+            for (int j = 0; j < SMAX; ++j) hv[j] = __builtin_nontemporal_load(H + (slot_off[j] + a));
             if (HB) {
                 float rf[8];
 #pragma unroll
@@ -408,7 +410,7 @@ __global__ __launch_bounds__(256) void k_transform_adam(const MatDev* __restrict
     // Branch-free loads: a row beyond nrow re-reads the band's last valid row and its result is dropped.
     // Element offsets of this thread's row segments inside a slot / inside M, V (32-bit).
     unsigned eoff[RT];
-    const StatePanel sp = state_panel(r, ldn, md.pw, pr.tj * kAdamPatchCols);   // the same for the whole workgroup
+    const StatePanel sp = state_panel(r, md.pw, pr.tj * kAdamPatchCols);   // the same for the whole workgroup
 #pragma unroll
     for (int e = 0; e < RT; ++e) {
         const int row = row0 + e < r ? row0 + e : r - 1;

@@ -377,7 +377,7 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[C::MI][C::NJ], 
                                                  unsigned char* smem, int i0, int j0, int t, int wm, int wn, int li,
                                                  int h) {
     const int r = md.r, ldn = md.ldn, n = md.n;   // columns n..ldn-1 of the slot are zero
-    const StatePanel sp = state_panel(r, ldn, md.pw, j0);   // a tile lies in one column panel of the slot
+    const StatePanel sp = state_panel(r, md.pw, j0);   // a tile lies in one column panel of the slot
     if (!HB) {
         NG_AS1 float* R = (NG_AS1 float*)md.H + (long long)dy.head * md.slot_elems;
 #pragma unroll

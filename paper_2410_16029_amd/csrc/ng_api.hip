@@ -106,10 +106,11 @@ void derive(const ng_matrix_desc& user, const ng_hparams& hp, int skinny_rk, Siz
     z->roct = ceil_div(d.r, 8);
     z->lp = (int)align_up((size_t)l, (size_t)2 * kJacobiBlock);
     const size_t rn = (size_t)d.r * z->ldn;
+    const size_t state = (size_t)d.r * state_cols(z->ldn, z->pw);   // elements of M, V, a history slot as stored
     z->bytes[NG_BUF_P] = hp.proj_dtype == NG_BF16 ? 0 : align_up((size_t)d.m * d.r * 4, 256);
-    z->bytes[NG_BUF_M] = align_up(rn * 4, 256);
-    z->bytes[NG_BUF_V] = align_up(rn * 4, 256);
-    z->bytes[NG_BUF_H] = align_up(rn * (hist_is_bf16(hp) ? 2 : 4) * (size_t)(s > 0 ? s : 1), 256);
+    z->bytes[NG_BUF_M] = align_up(state * 4, 256);
+    z->bytes[NG_BUF_V] = align_up(state * 4, 256);
+    z->bytes[NG_BUF_H] = align_up(state * (hist_is_bf16(hp) ? 2 : 4) * (size_t)(s > 0 ? s : 1), 256);
     z->k_gram_off = 0;
     z->k_w64_off = align_up((size_t)s * s * 8, 16);
     z->k_w32_off = z->k_w64_off + align_up((size_t)s * 8, 16);
@@ -650,7 +651,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             st->sides |= descs[i].side == NG_SIDE_RIGHT ? 2 : 1;
             md.l = z.l; md.ldk = z.ldk; md.ldr = z.ldr; md.roct = z.roct;
             md.ld_w = descs[i].ld_w; md.ld_g = descs[i].ld_g;
-            md.slot_elems = (long long)md.r * z.ldn;
+            md.slot_elems = (long long)md.r * state_cols(z.ldn, z.pw);
             md.pw = z.pw;
             md.P = (float*)bufs[i].buf[NG_BUF_P];
             md.M = (float*)bufs[i].buf[NG_BUF_M];
@@ -684,7 +685,7 @@ int ng_init_state(const ng_matrix_desc* descs, const ng_matrix_buffers* bufs, in
             md.carry = z.ws_carry ? (float*)(ws + off) : nullptr; off += z.ws_carry;
             md.lp = z.lp;
             // units of the Gram-row reduction: 16-byte vectors of a slot
-            const long long total4 = md.slot_elems / (hist_is_bf16(*hp) ? 8 : 4);
+            const long long total4 = (long long)md.r * z.ldn / (hist_is_bf16(*hp) ? 8 : 4);   // positions that hold columns below ldn
             long long iters = (total4 + 256LL * kDotPartsMax - 1) / (256LL * kDotPartsMax);
             if (iters < 1) iters = 1;
             // float slots large enough for several passes: a whole number of 1024-vector passes per
@@ -890,7 +891,7 @@ int ng_get_layout(const ng_state* st, int mat, ng_matrix_layout* out) {
     const Sizes& z = st->plan.sz[mat];
     out->ldn = z.ldn;
     out->l = z.l;
-    out->slot_elems = (int64_t)st->descs[mat].r * z.ldn;
+    out->slot_elems = (int64_t)st->descs[mat].r * state_cols(z.ldn, z.pw);
     out->panel_cols = z.pw;
     out->reserved0 = 0;
     out->k_gram_off = (int64_t)z.k_gram_off;

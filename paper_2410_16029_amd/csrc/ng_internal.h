@@ -35,7 +35,7 @@ struct MatDev {
     int ldr;          // contraction length of Pb (r rounded up to 32)
     int roct;         // ceil(r/8): octets of N in the bf16 layout
     long long ld_w, ld_g;
-    long long slot_elems;   // r * ldn
+    long long slot_elems;   // elements from one history slot to the next: r * state_cols(ldn, pw)
     int pw;           // columns per panel of M, V and every history slot (== ldn: one panel, plain row-major)
     float* P;
     float* M;
@@ -89,26 +89,51 @@ struct DynChunk {
 
 constexpr size_t kStaticScratchBytes = NG_STATIC_SCRATCH_BYTES;   // the library's own step scratch (ng_step_static)
 
-// M, V and every history slot hold r x ldn elements as column panels of pw columns: panel p (columns
-// p pw .. min(ldn, (p + 1) pw) - 1) is a row-major r x pitch block, pitch = its column count, and the
-// panels lie one after the other (the array stays r * ldn elements long and, read flat, is a permutation
-// of the row-major one).  pw is a multiple of every tile and patch width, so a tile lies in one panel.
-// pw == ldn is the plain row-major array.  A 2048-column panel gives 4-byte elements a row pitch of
-// 8 KB, at which the streaming kernels run fastest (transform+Adam on 5472-column states: 5.8 TB/s
-// row-major against 6.6 TB/s for 2048-column states).
+// M, V and every history slot hold their r x ldn elements as column panels of pw columns: panel p
+// (columns p pw .. p pw + pw - 1) is a row-major r x pw block, and the panels lie one after the other.
+// pw == ldn is the plain row-major array.  Otherwise pw = kStatePanelCols, a multiple of every tile and
+// patch width (a tile lies in one panel), and the last panel's columns from ldn on are padding: zero,
+// never written, and skipped by the kernels that read an array flat.  A 2048-column panel gives 4-byte
+// elements a row pitch of 8 KB, at which the streaming kernels run fastest (transform+Adam: 6.6 TB/s on
+// 2048-column states against 5.8 TB/s on row-major 5472-column ones and 5.1 TB/s at a 5.5 KB pitch).
 struct StatePanel {
     unsigned base;   // element offset of the panel inside the array
-    int pitch;       // its row pitch (= its columns)
+    int pitch;       // its row pitch
     int col0;        // its first column
     __host__ __device__ unsigned at(int row, int col) const { return base + (unsigned)row * (unsigned)pitch + (unsigned)(col - col0); }
 };
-__host__ __device__ inline StatePanel state_panel(int r, int ldn, int pw, int col) {
+__host__ __device__ inline StatePanel state_panel(int r, int pw, int col) {
     StatePanel sp;
     const int p = col / pw;
     sp.col0 = p * pw;
-    sp.pitch = ldn - sp.col0 < pw ? ldn - sp.col0 : pw;
+    sp.pitch = pw;
     sp.base = (unsigned)p * (unsigned)r * (unsigned)pw;
     return sp;
+}
+// columns an array of ldn columns occupies in panels of pw
+__host__ __device__ inline int state_cols(int ldn, int pw) { return (ldn + pw - 1) / pw * pw; }
+
+// The same arrays read flat, V elements per 16-byte vector: the r * ldn / V vectors that hold the
+// columns below ldn, numbered in storage order; position q lies at vector at(q) of the array.
+struct FlatState {
+    unsigned whole;      // vectors before the last panel (stored without gaps)
+    unsigned row_valid;  // vectors per row of the last panel that hold columns below ldn
+    unsigned row_pitch;  // vectors per stored row of the last panel
+    unsigned count;      // r * ldn / V
+    __host__ __device__ unsigned at(unsigned q) const {
+        if (q < whole || row_valid == row_pitch) return q;
+        const unsigned k = q - whole, row = k / row_valid;
+        return whole + row * row_pitch + (k - row * row_valid);
+    }
+};
+__host__ __device__ inline FlatState flat_state(int r, int ldn, int pw, int V) {
+    FlatState f;
+    const int last0 = (ldn - 1) / pw * pw;   // first column of the last panel
+    f.whole = (unsigned)last0 / (unsigned)V * (unsigned)r;
+    f.row_valid = (unsigned)(ldn - last0) / (unsigned)V;
+    f.row_pitch = (unsigned)pw / (unsigned)V;
+    f.count = (unsigned)r * (unsigned)ldn / (unsigned)V;
+    return f;
 }
 
 // address inside the step's scratch block, which starts with the per-step table

@@ -87,7 +87,10 @@ int main() {
         for (int i = 0; i < n; ++i) {
             ng_matrix_layout lay;
             CHECK(ng_get_layout(s.st, i, &lay) == NG_OK);
-            CHECK(lay.ldn % 32 == 0 && lay.slot_elems == (int64_t)s.descs[i].r * lay.ldn);
+            // one panel: the plain row-major slot; else 2048-column panels with the last one padded
+            const int64_t stored_cols = (lay.ldn + lay.panel_cols - 1) / lay.panel_cols * (int64_t)lay.panel_cols;
+            CHECK(lay.ldn % 32 == 0 && (lay.panel_cols == lay.ldn || lay.panel_cols == 2048));
+            CHECK(lay.slot_elems == (int64_t)s.descs[i].r * stored_cols);
             int64_t t = -1, nref = -1;
             int32_t head = -1, count = -1;
             CHECK(ng_get_counters(s.st, i, &t, &head, &count, &nref) == NG_OK && t == 0 && head == 0 && count == 0 && nref == 0);

@@ -53,14 +53,14 @@ def test_query_sizes_c1_and_bf16_layout():
     hp.s = 16
     descs = B.make_descs([(2048, 5461)], 512)
     sizes, _ = B.ng_query_sizes(descs, hp)
-    ldn = 5472
-    assert sizes[0][B.NG_BUF_M] == 512 * ldn * 4
-    assert sizes[0][B.NG_BUF_H] == 16 * 512 * ldn * 4
+    ldn, stored = 5472, 6144                                # M, V, H: three 2048-column panels, the last one padded
+    assert sizes[0][B.NG_BUF_M] == 512 * stored * 4
+    assert sizes[0][B.NG_BUF_H] == 16 * 512 * stored * 4
     assert sizes[0][B.NG_BUF_N] == (512 // 8) * ldn * 8 * 2
     hp.hist_dtype = B.NG_BF16                               # opt-in: bf16 history slots
     sizes16, _ = B.ng_query_sizes(descs, hp)
-    assert sizes16[0][B.NG_BUF_H] == 16 * 512 * ldn * 2
-    assert sizes16[0][B.NG_BUF_M] == 512 * ldn * 4
+    assert sizes16[0][B.NG_BUF_H] == 16 * 512 * stored * 2
+    assert sizes16[0][B.NG_BUF_M] == 512 * stored * 4
     hp.hist_dtype = B.NG_F32
     assert sizes[0][B.NG_BUF_AUX] >= 2 * 2048 * 512 * 2
     hp.proj_dtype = B.NG_BF16                               # opt-in: the projector only as its two bf16 copies
@@ -78,12 +78,12 @@ def test_query_sizes_c1_and_bf16_layout():
     assert descs[0].side == B.NG_SIDE_RIGHT
     right, _ = B.ng_query_sizes(descs, hp)
     assert right[0][B.NG_BUF_P] == 2048 * 512 * 4
-    assert right[0][B.NG_BUF_M] == 512 * 5472 * 4
+    assert right[0][B.NG_BUF_M] == 512 * stored * 4
     descs = B.make_descs([(2048, 5461)], 512)
     # s = 0 keeps one scratch slot for the projected gradient
     hp.s = 0
     sizes, _ = B.ng_query_sizes(descs, hp)
-    assert sizes[0][B.NG_BUF_H] == 512 * ldn * 4
+    assert sizes[0][B.NG_BUF_H] == 512 * stored * 4
 
 
 @pytest.mark.parametrize("mutate,code", [
@@ -180,29 +180,34 @@ def test_wide_bf16_states_are_column_panels_and_the_decoder_undoes_them():
         out = (lay.ldn, lay.panel_cols, lay.slot_elems)
         ls.close()
         return out
-    assert layout((64, 5461), dtype="bf16") == (5472, 2048, 8 * 5472)
+    assert layout((64, 5461), dtype="bf16") == (5472, 2048, 8 * 6144)           # the last panel is padded
     assert layout((64, 4096), dtype="bf16") == (4096, 2048, 8 * 4096)
-    assert layout((64, 2736), dtype="bf16") == (2752, 2048, 8 * 2752)
-    assert layout((64, 2304), dtype="bf16") == (2304, 2048, 8 * 2304)
+    assert layout((64, 2736), dtype="bf16") == (2752, 2048, 8 * 4096)
+    assert layout((64, 2304), dtype="bf16") == (2304, 2048, 8 * 4096)
     assert layout((64, 2272), dtype="bf16") == (2272, 2272, 8 * 2272)          # a sliver of a second panel: one
     assert layout((64, 5461), dtype="f32") == (5472, 5472, 8 * 5472)           # fp32 gradients: row-major
     assert layout((64, 5461), dtype="bf16", carry_history=True) == (5472, 5472, 8 * 5472)
-    assert layout((5461, 64), dtype="bf16", sides="auto") == (5472, 2048, 8 * 5472)   # right side: r x ldm
-    # the binding's decoder: element (row, col) sits at p r pw + row pitch + (col - p pw)
+    assert layout((5461, 64), dtype="bf16", sides="auto") == (5472, 2048, 8 * 6144)   # right side: r x ldm
+    # sizes count the padded last panel
+    hp = B.ng_default_hparams()
+    hp.grad_dtype, hp.s = B.NG_BF16, 2
+    sizes, _ = B.ng_query_sizes(B.make_descs([(64, 4200)], 8), hp)
+    assert sizes[0][B.NG_BUF_M] == sizes[0][B.NG_BUF_V] == 8 * 6144 * 4 and sizes[0][B.NG_BUF_H] == 2 * 8 * 6144 * 4
+    assert sizes[0][B.NG_BUF_N] == 1 * 4224 * 8 * 2                            # N is not panelled
+    # the binding's decoder: element (row, col) sits at p r pw + row pw + (col - p pw)
     ls = B.LayerSet([(64, 4200)], 8, s=2, dtype="bf16", device="cpu", host_only=True)
-    r, ldn, pw = 8, 4224, 2048
-    flat = torch.arange(r * ldn, dtype=torch.float32)
-    ls.buffers[0][B.NG_BUF_M].view(torch.float32)[:r * ldn] = flat
+    r, ldn, pw, stored = 8, 4224, 2048, 8 * 6144
+    flat = torch.arange(stored, dtype=torch.float32)
+    ls.buffers[0][B.NG_BUF_M].view(torch.float32)[:stored] = flat
     M = ls.M(0)
     assert M.shape == (r, ldn)
     for row, col in [(0, 0), (3, 2047), (0, 2048), (7, 4095), (0, 4096), (5, 4223)]:
         pnl = col // pw
-        pitch = min(pw, ldn - pnl * pw)
-        assert M[row, col] == pnl * r * pw + row * pitch + (col - pnl * pw), (row, col)
-    hflat = torch.arange(2 * r * ldn, dtype=torch.float32)
-    ls.buffers[0][B.NG_BUF_H].view(torch.float32)[:2 * r * ldn] = hflat
+        assert M[row, col] == pnl * r * pw + row * pw + (col - pnl * pw), (row, col)
+    hflat = torch.arange(2 * stored, dtype=torch.float32)
+    ls.buffers[0][B.NG_BUF_H].view(torch.float32)[:2 * stored] = hflat
     H = ls.H(0)
-    assert H.shape == (2, r, ldn) and H[1, 2, 4100] == r * ldn + 2 * r * pw + 2 * 128 + 4
+    assert H.shape == (2, r, ldn) and H[1, 2, 4100] == stored + 2 * r * pw + 2 * pw + 4
     ls.close()
 
 

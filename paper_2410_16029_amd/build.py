@@ -89,6 +89,9 @@ def build_host_sanitizer(verbose: bool = True) -> str:
     driver = os.path.join(ROOT, "tests", "host", "abi_driver.cpp")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-std=c++17", "-O1", "-g", "-fno-gpu-sanitize", "-fsanitize=address",
            "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-I" + os.path.join(ROOT, "include"),
+           # the driver also sees the internal header, as plain C++
+           "-I" + CSRC, "-D__HIP_PLATFORM_AMD__",
+           "-I" + os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(_hipcc()))), "include"),
            "-x", "c++", driver, "-x", "none", *objs, "-o", exe]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -20,6 +20,38 @@ using namespace ng;
 // the name is not a device address): see static_scratch_of_current_device.
 static __device__ __align__(256) unsigned char g_ng_static_scratch[ng::kStaticScratchBytes];
 
+// Round-robin workgroup dispatch puts workgroup id w on XCD (w mod 8).  To let one XCD work
+// through a contiguous run of the logical tile order (tiles that share operand panels stay in one
+// L2), the logical order is cut into 8 runs of about equal cost (cost[i] = contraction length of tile
+// i) and hardware id w takes entry w / 8 of run w mod 8.  Inside a run the tiles are taken longest
+// first (stable: tiles of one matrix stay together): an XCD's units pick tiles off its run as they
+// become free, and a run that ends with its longest tiles leaves most units idle while the last few
+// finish (the 5461-deep tiles of a 1.1B-shaped block are 2.7 times as long as the others).
+// Runs shorter than the longest are padded with entries whose workgroups exit at once.
+void ng::xcd_order(const std::vector<TileRef>& logical, const std::vector<int>& cost, std::vector<TileRef>* out) {
+    const size_t T = logical.size();
+    out->clear();
+    if (T == 0) return;
+    double total = 0.0;
+    for (size_t i = 0; i < T; ++i) total += (double)cost[i];
+    std::vector<std::vector<size_t>> run(8);
+    double acc = 0.0;
+    for (size_t i = 0; i < T; ++i) {
+        // the run in which the tile's midpoint falls
+        size_t x = (size_t)((acc + 0.5 * (double)cost[i]) * 8.0 / total);
+        run[x < 8 ? x : 7].push_back(i);
+        acc += (double)cost[i];
+    }
+    size_t per = 0;
+    for (auto& r : run) {
+        std::stable_sort(r.begin(), r.end(), [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+        per = r.size() > per ? r.size() : per;
+    }
+    out->assign(per * 8, TileRef{-1, 0, 0, 0});
+    for (size_t x = 0; x < 8; ++x)
+        for (size_t k = 0; k < run[x].size(); ++k) (*out)[k * 8 + x] = logical[run[x][k]];
+}
+
 namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -150,38 +182,6 @@ struct Plan {
     std::vector<size_t> step_parts_off, step_skinny_off;
     size_t total;
 };
-
-// Round-robin workgroup dispatch puts workgroup id w on XCD (w mod 8).  To let one XCD work
-// through a contiguous run of the logical tile order (tiles that share operand panels stay in one
-// L2), the logical order is cut into 8 runs of about equal cost (cost[i] = contraction length of tile
-// i) and hardware id w takes entry w / 8 of run w mod 8.  Inside a run the tiles are taken longest
-// first (stable: tiles of one matrix stay together): an XCD's units pick tiles off its run as they
-// become free, and a run that ends with its longest tiles leaves most units idle while the last few
-// finish (the 5461-deep tiles of a 1.1B-shaped block are 2.7 times as long as the others).
-// Runs shorter than the longest are padded with entries whose workgroups exit at once.
-void xcd_order(const std::vector<TileRef>& logical, const std::vector<int>& cost, std::vector<TileRef>* out) {
-    const size_t T = logical.size();
-    out->clear();
-    if (T == 0) return;
-    double total = 0.0;
-    for (size_t i = 0; i < T; ++i) total += (double)cost[i];
-    std::vector<std::vector<size_t>> run(8);
-    double acc = 0.0;
-    for (size_t i = 0; i < T; ++i) {
-        // the run in which the tile's midpoint falls
-        size_t x = (size_t)((acc + 0.5 * (double)cost[i]) * 8.0 / total);
-        run[x < 8 ? x : 7].push_back(i);
-        acc += (double)cost[i];
-    }
-    size_t per = 0;
-    for (auto& r : run) {
-        std::stable_sort(r.begin(), r.end(), [&](size_t a, size_t b) { return cost[a] > cost[b]; });
-        per = r.size() > per ? r.size() : per;
-    }
-    out->assign(per * 8, TileRef{-1, 0, 0, 0});
-    for (size_t x = 0; x < 8; ++x)
-        for (size_t k = 0; k < run[x].size(); ++k) (*out)[k * 8 + x] = logical[run[x][k]];
-}
 
 void make_plan(const ng_matrix_desc* d, int n_mats, const ng_hparams& hp, Plan* p) {
     p->sz.resize(n_mats);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "ng.h"
 
 namespace ng {
@@ -161,6 +163,9 @@ struct TileRef {
     int ti, tj;
     int pad;
 };
+
+// Host side: the order in which a grouped GEMM launch's tile table lists the tiles (ng_api.hip).
+void xcd_order(const std::vector<TileRef>& logical, const std::vector<int>& cost, std::vector<TileRef>* out);
 
 // Left-side projection tiles of a gradient with at least 8 columns take the direct-to-LDS kernel.  It
 // reads whole 16-byte chunks; the one chunk per row that straddles the last column (n % 8 != 0) reads up

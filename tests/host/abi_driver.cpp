@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "ng.h"
+#include "ng_internal.h"   // ng::xcd_order, ng::TileRef (internal, host side)
 
 static int g_failed = 0;
 #define CHECK(cond)                                                         \
@@ -53,7 +54,60 @@ static int make(Set& s, const ng_hparams& hp, uint32_t flags) {
     return ng_init_state(s.descs.data(), s.bufs.data(), n, &hp, s.ws, s.ws_bytes, flags, nullptr, &s.st);
 }
 
+// The tile-table order: every tile exactly once, eight runs (entry k of run x at 8 k + x) of about equal
+// cost, longest tiles first inside a run and otherwise in the logical order, padding entries with mat < 0.
+static void check_tile_order() {
+    std::vector<ng::TileRef> out;
+    ng::xcd_order({}, {}, &out);
+    CHECK(out.empty());
+    ng::xcd_order({ng::TileRef{7, 1, 2, 0}}, {5}, &out);
+    CHECK(out.size() == 8);
+    int seen = 0;
+    for (const ng::TileRef& t : out) seen += t.mat == 7 && t.ti == 1 && t.tj == 2 ? 1 : (t.mat < 0 ? 0 : 100);
+    CHECK(seen == 1);
+    // 24 blocks of a 1.1B-shaped layer set: 4 x 16 + 2 x 44 tiles of length 2048, then 16 of length 5461
+    std::vector<ng::TileRef> logical;
+    std::vector<int> cost;
+    for (int b = 0; b < 24; ++b)
+        for (int k = 0; k < 7; ++k) {
+            const int tiles = k < 4 ? 16 : k < 6 ? 44 : 16;
+            for (int t = 0; t < tiles; ++t) {
+                logical.push_back(ng::TileRef{b * 7 + k, t & 1, t >> 1, 0});
+                cost.push_back(k == 6 ? 5461 : 2048);
+            }
+        }
+    ng::xcd_order(logical, cost, &out);
+    CHECK(out.size() % 8 == 0 && out.size() >= logical.size());
+    std::vector<int> hits(logical.size(), 0);
+    long long run_cost[8] = {0}, total = 0;
+    for (int c : cost) total += c;
+    for (size_t x = 0; x < 8; ++x) {
+        int prev_cost = 1 << 30, prev_idx = -1;
+        bool padding_seen = false;
+        for (size_t k = 0; 8 * k + x < out.size(); ++k) {
+            const ng::TileRef& t = out[8 * k + x];
+            if (t.mat < 0) { padding_seen = true; continue; }
+            CHECK(!padding_seen);   // padding only at the end of a run
+            // find the tile in the logical order (mat, ti, tj are unique there)
+            int idx = -1;
+            for (size_t i = 0; i < logical.size(); ++i)
+                if (logical[i].mat == t.mat && logical[i].ti == t.ti && logical[i].tj == t.tj) { idx = (int)i; break; }
+            CHECK(idx >= 0);
+            if (idx < 0) continue;
+            ++hits[idx];
+            run_cost[x] += cost[idx];
+            CHECK(cost[idx] <= prev_cost);                                  // longest first
+            if (cost[idx] == prev_cost) CHECK(idx > prev_idx);              // stable inside a cost class
+            prev_cost = cost[idx];
+            prev_idx = idx;
+        }
+    }
+    for (int h : hits) CHECK(h == 1);
+    for (size_t x = 0; x < 8; ++x) CHECK(run_cost[x] * 8 >= total - 8LL * 5461 && run_cost[x] * 8 <= total + 8LL * 5461);
+}
+
 int main() {
+    check_tile_order();
     ng_hparams hp;
     CHECK(ng_default_hparams(&hp) == NG_OK);
     CHECK(ng_default_hparams(nullptr) == NG_ERR_INVALID_ARG);
